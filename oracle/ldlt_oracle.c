@@ -1,0 +1,194 @@
+/*
+ * CPU oracle for log|det A| and sign(det A) of a symmetric matrix.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference the GPU
+ * library is checked against.  It shares no code with the HIP path, is never
+ * called by it, and must only be used from tests, the smoke check and the
+ * benchmark's CPU-baseline leg.
+ *
+ * What it computes.  The paper's method (Sec. 2.2, Eq. 1 and the paragraph after
+ * it; App. D) reaches, up to rounding, the exact log-determinant: the sum of the
+ * log-determinants of the diagonal factors met while the Schur complement is
+ * reduced block by block.  For the symmetric case the factorisation is
+ * A = L D L^T with unit lower-triangular L and diagonal D (Sec. 2.2, last two
+ * paragraphs; App. D first paragraph: the factorisation also yields the
+ * determinants of all leading principal sub-matrices), so
+ *
+ *      log|det A| = sum_j log|d_j| ,     sign det A = prod_j sgn d_j .
+ *
+ * The oracle is that definition written out, unblocked, without pivoting, in
+ * `long double` (x87 80-bit, 64-bit significand):
+ *
+ *      d_j  = a_jj - sum_{k<j} l_jk^2 d_k
+ *      l_ij = (a_ij - sum_{k<j} l_ik l_jk d_k) / d_j        (i > j)
+ *
+ * Only the lower triangle of the row-major input is read.  The input bits
+ * (double or float) are converted exactly to long double.
+ *
+ * The only parallelism is an OpenMP `parallel for` over the rows i of one
+ * pivot column j; the summation order inside every dot product is k = 0..j-1.
+ *
+ * Also here: a brute-force Leibniz determinant (sum over all permutations),
+ * used to pin the factorisation on tiny matrices.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef long double xreal;
+
+/* Row i of the strictly-lower factor is stored packed: i entries. */
+static inline size_t row_off(size_t i) { return i * (i - 1) / 2; }
+
+/*
+ * Core recurrence.  `get(ctx, i, j)` returns a_ij (i >= j) as long double.
+ * Outputs (any may be NULL):
+ *   d_out[n]       pivots d_j rounded to double
+ *   cum_out[n]     running sums  sum_{j<=k} log|d_j|  (log-determinants of the
+ *                  leading principal sub-matrices), rounded to double
+ *   l_out[n*n]     row-major unit lower factor L (upper part zero), double
+ * Returns 0 on success, 1 if an exact zero pivot was met (then *sign = 0,
+ * *logabsdet = -inf, *bad = its index), 2 on allocation failure.
+ */
+typedef xreal (*getter)(const void *ctx, size_t i, size_t j, size_t lda);
+
+static xreal get_f64(const void *a, size_t i, size_t j, size_t lda) {
+  return (xreal)((const double *)a)[i * lda + j];
+}
+static xreal get_f32(const void *a, size_t i, size_t j, size_t lda) {
+  return (xreal)((const float *)a)[i * lda + j];
+}
+
+static int ldlt_core(const void *a, size_t n, size_t lda, getter get,
+                     double *logabsdet, int *sign, int64_t *bad,
+                     int64_t *negative, double *d_out, double *cum_out,
+                     double *l_out) {
+  *logabsdet = 0.0;
+  *sign = 1;
+  if (bad) *bad = -1;
+  if (negative) *negative = 0;
+  if (n == 0) return 0;
+
+  size_t nl = n * (n - 1) / 2;
+  xreal *l = (xreal *)malloc((nl ? nl : 1) * sizeof(xreal));
+  xreal *d = (xreal *)malloc(n * sizeof(xreal));
+  xreal *v = (xreal *)malloc(n * sizeof(xreal)); /* v_k = l_jk d_k */
+  if (!l || !d || !v) {
+    free(l); free(d); free(v);
+    return 2;
+  }
+
+  int status = 0;
+  xreal acc_log = 0.0L;
+  int sg = 1;
+  int64_t neg = 0;
+
+  for (size_t j = 0; j < n; ++j) {
+    const xreal *lj = l + (j ? row_off(j) : 0);
+    xreal s = get(a, j, j, lda);
+    for (size_t k = 0; k < j; ++k) {
+      v[k] = lj[k] * d[k];
+      s -= lj[k] * v[k];
+    }
+    d[j] = s;
+    if (s == 0.0L) {
+      status = 1;
+      if (bad) *bad = (int64_t)j;
+      break;
+    }
+    if (s < 0.0L) { sg = -sg; ++neg; }
+    acc_log += logl(fabsl(s));
+    if (cum_out) cum_out[j] = (double)acc_log;
+
+    long i;
+#pragma omp parallel for schedule(static)
+    for (i = (long)j + 1; i < (long)n; ++i) {
+      xreal *li = l + row_off((size_t)i);
+      xreal t = get(a, (size_t)i, j, lda);
+      for (size_t k = 0; k < j; ++k) t -= li[k] * v[k];
+      li[j] = t / s;
+    }
+  }
+
+  if (status == 0) {
+    *logabsdet = (double)acc_log;
+    *sign = sg;
+  } else {
+    *logabsdet = -INFINITY;
+    *sign = 0;
+  }
+  if (negative) *negative = neg;
+  if (d_out)
+    for (size_t j = 0; j < n; ++j) d_out[j] = (double)d[j];
+  if (l_out && status == 0) {
+    memset(l_out, 0, n * n * sizeof(double));
+    for (size_t i = 0; i < n; ++i) {
+      for (size_t k = 0; k < i; ++k) l_out[i * n + k] = (double)l[row_off(i) + k];
+      l_out[i * n + i] = 1.0;
+    }
+  }
+  free(l); free(d); free(v);
+  return status;
+}
+
+int oracle_ldlt_f64(const double *a, int64_t n, int64_t lda, double *logabsdet,
+                    int *sign, int64_t *bad, int64_t *negative, double *d_out,
+                    double *cum_out, double *l_out) {
+  return ldlt_core(a, (size_t)n, (size_t)lda, get_f64, logabsdet, sign, bad,
+                   negative, d_out, cum_out, l_out);
+}
+
+int oracle_ldlt_f32(const float *a, int64_t n, int64_t lda, double *logabsdet,
+                    int *sign, int64_t *bad, int64_t *negative, double *d_out,
+                    double *cum_out, double *l_out) {
+  return ldlt_core(a, (size_t)n, (size_t)lda, get_f32, logabsdet, sign, bad,
+                   negative, d_out, cum_out, l_out);
+}
+
+/*
+ * Leibniz formula: det A = sum over permutations p of sgn(p) prod_i a_{i,p(i)}.
+ * Reads the FULL n x n row-major matrix (so it also serves non-symmetric
+ * checks).  n <= 10.  Returns log|det| and sign; det itself via *det_out
+ * (long double rounded to double) when not NULL.
+ */
+static void leibniz_rec(const double *a, int n, int row, unsigned used,
+                        xreal prod, int inv_parity, xreal *acc) {
+  if (row == n) {
+    *acc += inv_parity ? -prod : prod;
+    return;
+  }
+  for (int c = 0; c < n; ++c) {
+    if (used & (1u << c)) continue;
+    /* inversions added by putting column c in this row: columns > c already used */
+    int inv = 0;
+    for (int c2 = c + 1; c2 < n; ++c2)
+      if (used & (1u << c2)) ++inv;
+    leibniz_rec(a, n, row + 1, used | (1u << c),
+                prod * (xreal)a[row * n + c], inv_parity ^ (inv & 1), acc);
+  }
+}
+
+int oracle_leibniz_f64(const double *a, int n, double *logabsdet, int *sign,
+                       double *det_out) {
+  if (n < 0 || n > 10) return 2;
+  xreal acc = 0.0L;
+  if (n == 0) acc = 1.0L;
+  else leibniz_rec(a, n, 0, 0u, 1.0L, 0, &acc);
+  if (det_out) *det_out = (double)acc;
+  if (acc == 0.0L) { *logabsdet = -INFINITY; *sign = 0; }
+  else { *logabsdet = (double)logl(fabsl(acc)); *sign = acc > 0 ? 1 : -1; }
+  return 0;
+}
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
