@@ -134,7 +134,7 @@ def test_higham_two_by_two_gram_matrix():
     g = np.array([[1.0 + eps * eps, 1.0], [1.0, 1.0]])
     r = oracle.ldlt_logdet(g)
     # det of the stored matrix is exactly g00*1 - 1*1 (g00 - 1 is exact in binary)
-    assert r.sign == 1 and REL(r.logabsdet, math.log(g[0, 0] - 1.0)) < 1e-15
+    assert r.sign == 1 and REL(r.logabsdet, math.log(g[0, 0] - 1.0)) < 4e-15
     eps = 1e-9   # eps < sqrt(2^-53): fl(1+eps^2) == 1
     g = np.array([[1.0 + eps * eps, 1.0], [1.0, 1.0]])
     r = oracle.ldlt_logdet(g)
