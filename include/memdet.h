@@ -1,0 +1,234 @@
+/*
+ * memdet.h - C ABI of the MI355X (gfx950) log-determinant library.
+ *
+ * The library computes  log|det A|  and  sign(det A)  of a large symmetric
+ * matrix by a hierarchical block-wise LDL^T decomposition under a device-memory
+ * budget: the symmetric case ("case II") of the paper's memory-constrained
+ * algorithm (Sec. 2.2: block Schur-complement recursion of Eq. 1, stored-triangle
+ * processing and diagonal scaling for LDL^T; App. D: inputs "matrix, maximum
+ * memory c", outputs "l = log|det|, sigma = sign").  No pivoting is done: D is
+ * diagonal, L unit lower triangular, and
+ *
+ *      logabsdet = sum_j log|d_j| ,   sign = prod_j sgn(d_j) .
+ *
+ * Conventions common to every entry point
+ *  - Only the LOWER triangle of the matrix is read.  Element (i, j), i >= j.
+ *  - All sizes are in elements unless a name says bytes.  n may be any value
+ *    >= 0; it need not be a multiple of block_size (the last block row/column is
+ *    smaller, as in App. D where blocks are "at most b x b").
+ *  - block_size is the order b of the square blocks the matrix is cut into (the
+ *    paper's b = m / n_b).  It is rounded up to a multiple of 64 internally
+ *    (result->block_size_used); the result does not depend on it beyond rounding.
+ *  - Functions return an mdet_status; they never throw, abort or exit.  `result`
+ *    is fully written on MDET_OK and MDET_ESINGULAR, and its hip_error /
+ *    bad_pivot_index fields on the corresponding failures.
+ *  - Calls are synchronous: on return all device work of the call has finished.
+ *  - The library uses the HIP device that is current in the calling thread.
+ *  - Thread safety: calls that use distinct workspaces may run concurrently.
+ */
+#ifndef MEMDET_H
+#define MEMDET_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { MDET_F32 = 0, MDET_F64 = 1 } mdet_dtype;
+
+typedef enum {
+  MDET_OK = 0,
+  MDET_EINVAL = 1,        /* bad argument (null pointer, negative size, ld < n, ...) */
+  MDET_EBUDGET = 2,       /* mem_budget_bytes below the minimum working set        */
+  MDET_ENOMEM_DEVICE = 3, /* device allocation failed / workspace too small        */
+  MDET_ENOMEM_HOST = 4,   /* host allocation failed                                */
+  MDET_EHIP = 5,          /* a HIP call failed; raw code in result->hip_error      */
+  MDET_ESINGULAR = 6,     /* exact zero pivot: sign = 0, logabsdet = -inf          */
+  MDET_ENONFINITE = 7,    /* NaN/Inf pivot met (input not finite or overflow)      */
+  MDET_EPROVIDER = 8      /* the block provider returned non-zero                  */
+} mdet_status;
+
+/* Parameters of one log-determinant call.  Zero-initialise, then set fields. */
+typedef struct mdet_params {
+  uint32_t struct_size;      /* = sizeof(mdet_params); guards ABI drift            */
+  int32_t dtype;             /* mdet_dtype: type of the matrix AND of the arithmetic */
+  int64_t n;                 /* matrix order (the paper's m)                        */
+  int64_t block_size;        /* b; 0 = let the library choose                       */
+  uint64_t mem_budget_bytes; /* cap on device bytes this call may allocate or use as
+                                workspace (the paper's c, App. D).  0 = no cap.
+                                For mdet_logdet_device the caller's matrix itself is
+                                not counted; for the host/provider entry points every
+                                device byte is.                                     */
+  int32_t overwrite;         /* 1: the input may be destroyed (it then holds the
+                                factor: unit-lower L below the diagonal, D on it).
+                                0: the input is preserved (paper's overwrite=False:
+                                Schur-updated blocks go to scratch space instead).  */
+  int32_t lookahead;         /* 1 (default when 0 is passed with flags==0) ...      */
+  uint32_t flags;            /* MDET_FLAG_* bits                                    */
+  void* stream;              /* hipStream_t to order the work after (borrowed, e.g.
+                                from PyTorch); NULL = the default stream.  The call
+                                still synchronises before returning.               */
+  void* dev_workspace;       /* optional caller-owned device scratch (e.g. a
+                                torch.empty buffer); NULL = the library hipMallocs
+                                what it needs (within the budget) and frees it.     */
+  uint64_t dev_workspace_bytes;
+  void* host_scratch;        /* out-of-core with overwrite=0 only: pinned host
+                                memory of at least mdet_workspace_query()'s
+                                host_bytes that receives the updated blocks; NULL =
+                                the library allocates pinned memory itself.        */
+  uint64_t host_scratch_bytes;
+} mdet_params;
+
+#define MDET_FLAG_NO_LOOKAHEAD 1u /* run every step on one stream, strictly in order
+                                     (results are bit-identical either way)        */
+#define MDET_FLAG_FORCE_OUT_OF_CORE 2u /* host entry points: stream blocks even if the
+                                     whole triangle would fit in the budget         */
+
+typedef struct mdet_result {
+  double logabsdet;            /* log|det A|; -inf when sign == 0                    */
+  int32_t sign;                /* -1, 0, +1 (numpy.linalg.slogdet convention)        */
+  int32_t hip_error;           /* raw hipError_t of the failing call, else 0         */
+  int64_t bad_pivot_index;     /* first zero / non-finite pivot, else -1             */
+  int64_t negative_pivots;     /* number of d_j < 0 (not an error: Sec. 2.2 explains
+                                  why LDL^T is preferred to Cholesky)                */
+  int64_t block_size_used;     /* b after rounding                                   */
+  int64_t num_blocks;          /* n_b = ceil(n / b)                                  */
+  int32_t out_of_core;         /* 1 if blocks were streamed from host memory         */
+  int32_t num_superpanels;     /* out-of-core: number of resident column groups      */
+  double flops;                /* fused multiply-adds x 2 actually launched          */
+  double t_total;              /* seconds, wall clock of the call                    */
+  uint64_t bytes_h2d;          /* host -> device bytes moved                         */
+  uint64_t bytes_d2h;          /* device -> host bytes moved                         */
+  uint64_t dev_bytes_high_water; /* device bytes in use at the peak (<= budget)      */
+  uint64_t kernel_launches;
+} mdet_result;
+
+/*
+ * Block provider (the paper's "matrix stored on disk, may not be loaded on
+ * memory", App. D): called by mdet_logdet_provider from the calling thread to fetch
+ * the stored-triangle block with block coordinates (bi, bj), bi >= bj, i.e. rows
+ * [bi*b, bi*b+rows) x columns [bj*b, bj*b+cols) with b = block_size_used.  It must
+ * write the block row-major with leading dimension `ld` elements into the HOST
+ * buffer `dst` (pinned memory owned by the library) and return 0; any other
+ * return value aborts the call with MDET_EPROVIDER.  For diagonal blocks only the
+ * lower triangle need be filled.
+ */
+typedef int (*mdet_block_provider)(void* user, int64_t bi, int64_t bj, int64_t rows,
+                                   int64_t cols, void* dst, int64_t ld);
+
+/* Host planner (no GPU needed): what a call with these parameters would do. */
+typedef struct mdet_plan_info {
+  int64_t block_size_used;
+  int64_t num_blocks;           /* n_b                                              */
+  int32_t out_of_core;          /* host entry points: 0 in-core, 1 streamed          */
+  int32_t num_superpanels;      /* groups of block columns resident at a time        */
+  uint64_t dev_bytes_needed;    /* device workspace the call will use (<= budget)    */
+  uint64_t host_bytes_needed;   /* pinned scratch needed when overwrite == 0         */
+  uint64_t host_matrix_bytes;   /* size of the packed lower block-column layout      */
+  uint64_t stream_bytes_h2d;    /* predicted host->device traffic                    */
+  uint64_t stream_bytes_d2h;    /* predicted device->host traffic                    */
+  double fma_decomp, fma_solve, fma_gemm, fma_syrk; /* App. E.1, Table "complexity"  */
+} mdet_plan_info;
+
+/*
+ * mdet_plan: computes the block grid and residency plan for an n x n matrix in the
+ * packed host layout (see mdet_logdet_host) under params->mem_budget_bytes, and
+ * the work split of App. E.1.  `for_device_input` != 0 plans mdet_logdet_device
+ * instead (matrix already in HBM).  Pure host code.  Returns MDET_EBUDGET when the
+ * budget cannot hold the minimum working set.
+ */
+int mdet_plan(const mdet_params* params, int for_device_input, mdet_plan_info* info);
+
+/* Device / pinned-host scratch sizes a call needs (subset of mdet_plan). */
+int mdet_workspace_query(const mdet_params* params, int for_device_input,
+                         uint64_t* dev_bytes, uint64_t* host_bytes);
+
+/*
+ * mdet_logdet_device: matrix resident in HBM.
+ *   dA    DEVICE pointer, n x n row-major with leading dimension ld >= n elements
+ *         of params->dtype; only the lower triangle is read.  With overwrite = 1
+ *         it is factored in place; with overwrite = 0 the library works on a copy
+ *         in its workspace (n*ld_padded elements are then part of the workspace).
+ *   diag  optional DEVICE pointer to n elements of params->dtype receiving the
+ *         pivots d_j (cumulative sums of log|d_j| are the log-determinants of the
+ *         leading principal sub-matrices, App. D); NULL to skip.
+ * Caller owns every buffer.  Errors: see mdet_status.
+ */
+int mdet_logdet_device(const mdet_params* params, void* dA, int64_t ld,
+                       mdet_result* result, void* diag);
+
+/*
+ * mdet_logdet_host: matrix in HOST memory (pinned memory gives full link speed;
+ * pageable memory works but is slower), in the packed lower block-column layout:
+ * with b = block_size rounded up to a multiple of 64 and n_b = ceil(n/b), block
+ * column j (columns [j*b, min(n, (j+1)*b)), width w_j) stores rows [j*b, n)
+ * row-major with leading dimension w_j, and block columns follow each other:
+ *      offset_j = sum_{t<j} (n - t*b) * w_t      (elements)
+ * (use mdet_host_layout_offset).  Entries above the diagonal inside the diagonal
+ * blocks are never read.  If the whole layout plus workspace fits in
+ * mem_budget_bytes the factorisation runs in-core; otherwise block columns are
+ * processed in resident groups while already-factored blocks stream in from the
+ * host over side streams, and factored groups are written back (to hA when
+ * overwrite = 1, to host scratch otherwise).
+ *   diag  optional HOST pointer to n elements of params->dtype.
+ */
+int mdet_logdet_host(const mdet_params* params, void* hA, mdet_result* result,
+                     void* diag);
+
+/* As mdet_logdet_host, but blocks are fetched through `provider` (e.g. from disk)
+ * into library-owned pinned memory laid out as above.  overwrite is ignored. */
+int mdet_logdet_provider(const mdet_params* params, mdet_block_provider provider,
+                         void* user, mdet_result* result, void* diag);
+
+/* Element offset of block column j in the packed host layout; total elements for
+ * j = n_b.  b must already be a multiple of 64.  Returns -1 on bad arguments. */
+int64_t mdet_host_layout_offset(int64_t n, int64_t b, int64_t j);
+
+/* The paper's rule for the number of blocks from a memory cap (App. D: r = m
+ * sqrt(beta/c); n_b = 1, 2 or ceil(2r); b = 1 + floor((m-1)/n_b)).  Provided for
+ * reference and comparison; the library's own plan is mdet_plan. */
+int mdet_paper_block_rule(int64_t m, int32_t beta, uint64_t c, int64_t* n_b, int64_t* b);
+
+/* Closed-form operation count of App. E.1 for the symmetric case, in fused
+ * multiply-adds: m^3/6 - m^2/4 + m/12. */
+double mdet_paper_fma_count(int64_t m);
+
+/*
+ * Single steps of the path, exposed for tests and benchmarks.  All pointers are
+ * DEVICE pointers to elements of `dtype`; matrices are row-major; `stream` is a
+ * hipStream_t or NULL; the calls are asynchronous (enqueue only) and return
+ * MDET_EINVAL on misaligned or inconsistent arguments (leading dimensions and
+ * base pointers must keep rows 16-byte aligned, K must be a multiple of 64).
+ */
+
+/* Trailing Schur-complement update (Sec. 2.2, S <- S - C B with the diagonal
+ * scaling of the LDL^T case):  C[M x N] -= A[M x K] diag(d[K]) B[N x K]^T.
+ * lower != 0: C's (0,0) lies on the matrix diagonal and only entries with
+ * column <= row are computed and stored (Gramian / lower-triangle case). */
+int mdet_step_schur_update(int32_t dtype, void* C, int64_t ldc, const void* A,
+                           int64_t lda, const void* B, int64_t ldb, const void* d,
+                           int64_t M, int64_t N, int64_t K, int32_t lower, void* stream);
+
+/* Factor one block column in place: P points at its diagonal entry; the panel has
+ * m rows and w <= m columns.  On return the top w x w block holds L (strictly
+ * lower) and D (diagonal), the rows below hold L_ik = A_ik L_kk^-T D_k^-1, and
+ * d[w], dinv[w] hold the pivots and their reciprocals.  flags: device pointer to
+ * 4 int64 (zero it first): [0] first bad pivot index + 1 as a negative... see
+ * memdet_api.hip; pass the buffer returned by the workspace helpers in tests. */
+int mdet_step_panel_factor(int32_t dtype, void* P, int64_t ld, int64_t m, int64_t w,
+                           void* d, void* dinv, int64_t pivot_index0, void* flags,
+                           void* stream);
+
+/* sum log|d_j|, sign and negative count of d[0..n) -> out[0] = logabsdet (double),
+ * out[1] = sign (as double), out[2] = negative count (as double).  out: DEVICE. */
+int mdet_step_logdet_reduce(int32_t dtype, const void* d, int64_t n, double* out,
+                            void* stream);
+
+const char* mdet_strerror(int status);
+const char* mdet_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MEMDET_H */

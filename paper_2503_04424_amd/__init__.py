@@ -1,0 +1,16 @@
+"""MI355X-native hierarchical block LDL^T log-determinant (thin Python binding).
+
+Every step of the path runs inside ``libmemdet.so`` (hand-written HIP for
+gfx950); this package only marshals arguments.  PyTorch tensors are used as
+device / pinned-host memory and for the current stream handle.
+"""
+from .binding import (  # noqa: F401
+    MDET_F32, MDET_F64, FLAG_NO_LOOKAHEAD, FLAG_FORCE_OUT_OF_CORE,
+    MemdetError, LogdetResult, PlanInfo, Status,
+    lib, lib_path, load,
+    mdet_plan, mdet_workspace_query, mdet_logdet_device, mdet_logdet_host,
+    mdet_logdet_provider, mdet_host_layout_offset, mdet_paper_block_rule,
+    mdet_paper_fma_count, mdet_step_schur_update, mdet_step_panel_factor,
+    mdet_step_logdet_reduce, mdet_strerror, mdet_version,
+    pack_lower_block_columns,
+)

@@ -1,0 +1,218 @@
+// Trailing Schur-complement update on the matrix cores.
+//
+// Sec. 2.2 of the paper forms S <- S - C B for every block of the trailing matrix
+// (App. E.1 counts it as "full" and "Gramian" matrix multiplications); in the
+// LDL^T case the product carries the diagonal scaling:
+//
+//      C[M x N]  -=  A[M x K] * diag(d[0..K)) * B[N x K]^T
+//
+// with A and B rows of the already-factored block column (unit-lower factor L)
+// and d its pivots.  All three matrices are row-major, so both operands are read
+// along K with unit stride.
+//
+// Tiling (gfx950): 256 threads = 4 wavefronts in a 2 x 2 arrangement, each
+// wavefront owns a 64 x 64 piece of a 128 x 128 block of C as 4 x 4 MFMA tiles of
+// 16 x 16 (v_mfma_f64_16x16x4_f64 / v_mfma_f32_16x16x4_f32).  K is walked in
+// slabs of 128 bytes per row (16 doubles / 32 floats) that are staged through
+// LDS, double buffered, with the next slab's global loads in flight while the
+// current one is multiplied.  The scaling by -d is applied to the A operand as it
+// is written to LDS; the accumulators are seeded with C.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mdet {
+
+template <typename T> struct Mfma;
+
+template <> struct Mfma<double> {
+  typedef double acc_t __attribute__((ext_vector_type(4)));
+  typedef double vec_t __attribute__((ext_vector_type(2)));   // 16 bytes
+  static constexpr int VEC = 2;
+  static constexpr int BK = 16;
+  static __device__ __forceinline__ acc_t mfma(double a, double b, acc_t c) {
+    return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+  }
+  // row inside the 16 x 16 tile held by accumulator register r of this lane
+  static __device__ __forceinline__ int acc_row(int lane, int r) { return 4 * r + (lane >> 4); }
+};
+
+template <> struct Mfma<float> {
+  typedef float acc_t __attribute__((ext_vector_type(4)));
+  typedef float vec_t __attribute__((ext_vector_type(4)));    // 16 bytes
+  static constexpr int VEC = 4;
+  static constexpr int BK = 32;
+  static __device__ __forceinline__ acc_t mfma(float a, float b, acc_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ int acc_row(int lane, int r) { return 4 * (lane >> 4) + r; }
+};
+
+constexpr int UPD_BM = 128;
+constexpr int UPD_BN = 128;
+constexpr int UPD_THREADS = 256;
+constexpr int UPD_ROW_BYTES = 144;   // 128 data bytes + 16 pad: conflict-free 16-lane reads
+
+// Number of 128 x 128 blocks a launch needs.
+static inline int64_t update_num_blocks(int64_t M, int64_t N, bool lower) {
+  int64_t nbm = (M + UPD_BM - 1) / UPD_BM, nbn = (N + UPD_BN - 1) / UPD_BN;
+  if (!lower) return nbm * nbn;
+  int64_t t = nbm < nbn ? nbm : nbn;           // rows inside the triangular part
+  return t * (t + 1) / 2 + (nbm - t) * nbn;
+}
+
+template <typename T, bool LOWER>
+__global__ __launch_bounds__(UPD_THREADS) void schur_update_kernel(
+    T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
+    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K,
+    int nbn) {
+  using X = Mfma<T>;
+  using acc_t = typename X::acc_t;
+  using vec_t = typename X::vec_t;
+  constexpr int BK = X::BK, VEC = X::VEC;
+  constexpr int S = UPD_ROW_BYTES / (int)sizeof(T);   // LDS row stride in elements
+  constexpr int HALF = BK / 2;                        // elements each thread stages per row
+  constexpr int NV = HALF / VEC;                      // 16-byte vectors per thread per operand (4)
+  constexpr int KS = BK / 4;                          // MFMA k-steps per slab
+
+  __shared__ __attribute__((aligned(16))) T As[2][UPD_BM * S];
+  __shared__ __attribute__((aligned(16))) T Bs[2][UPD_BN * S];
+
+  // ---- which block -------------------------------------------------------
+  int bm, bn;
+  {
+    int64_t id = blockIdx.x;
+    if (LOWER) {
+      int64_t tri = (int64_t)nbn * (nbn + 1) / 2;
+      if (id < tri) {
+        int64_t r = (int64_t)((sqrt(8.0 * (double)id + 1.0) - 1.0) * 0.5);
+        while (r * (r + 1) / 2 > id) --r;
+        while ((r + 1) * (r + 2) / 2 <= id) ++r;
+        bm = (int)r;
+        bn = (int)(id - r * (r + 1) / 2);
+      } else {
+        int64_t rest = id - tri;
+        bm = nbn + (int)(rest / nbn);
+        bn = (int)(rest % nbn);
+      }
+    } else {
+      bm = (int)(id / nbn);
+      bn = (int)(id % nbn);
+    }
+  }
+  const int row0 = bm * UPD_BM, col0 = bn * UPD_BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  // a wavefront whose 64 x 64 piece lies strictly above the diagonal has nothing to do
+  const bool active = !(LOWER && (row0 + wm * 64 + 63 < col0 + wn * 64));
+
+  // ---- global -> register staging ---------------------------------------
+  const int srow = tid >> 1, shalf = tid & 1;
+  int ar = row0 + srow; if (ar > M - 1) ar = M - 1;
+  int br = col0 + srow; if (br > N - 1) br = N - 1;
+  const T* Ap = A + (int64_t)ar * lda + shalf * HALF;
+  const T* Bp = B + (int64_t)br * ldb + shalf * HALF;
+  const T* dp = d + shalf * HALF;
+  vec_t ra[NV], rb[NV], rd[NV];
+
+  auto gload = [&](int kt) {
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      ra[v] = *reinterpret_cast<const vec_t*>(Ap + (int64_t)kt * BK + v * VEC);
+      rb[v] = *reinterpret_cast<const vec_t*>(Bp + (int64_t)kt * BK + v * VEC);
+      rd[v] = *reinterpret_cast<const vec_t*>(dp + (int64_t)kt * BK + v * VEC);
+    }
+  };
+  auto sstore = [&](int buf) {
+    T* as = &As[buf][srow * S + shalf * HALF];
+    T* bs = &Bs[buf][srow * S + shalf * HALF];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      *reinterpret_cast<vec_t*>(as + v * VEC) = -(ra[v] * rd[v]);
+      *reinterpret_cast<vec_t*>(bs + v * VEC) = rb[v];
+    }
+  };
+
+  const int r16 = lane & 15, g = lane >> 4;
+
+  // The accumulators start from C and the (negated) products are added to them in
+  // K order, so every entry is reduced term by term exactly as in the unblocked
+  // recurrence a_ij - sum_k l_ik d_k l_jk; when the Schur complement is much
+  // smaller than a_ij (low-rank Gram matrix plus a small shift) the late roundings
+  // are then relative to the small running value, not to the full sum.
+  acc_t acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = acc_t{0, 0, 0, 0};
+  if (active) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int grow = row0 + wm * 64 + i * 16 + X::acc_row(lane, r);
+        if (grow >= M) continue;
+        const T* crow = C + (int64_t)grow * ldc;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int gcol = col0 + wn * 64 + j * 16 + r16;
+          if (gcol < N && (!LOWER || gcol <= grow)) acc[i][j][r] = crow[gcol];
+        }
+      }
+    }
+  }
+
+  const int nk = K / BK;
+
+  gload(0);
+  sstore(0);
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nk) gload(kt + 1);
+    if (active) {
+      // lane group g owns the KS consecutive k's [g*KS, (g+1)*KS) of the slab; MFMA
+      // step s multiplies the s-th of them from every group (any assignment of the
+      // slab's k's to steps is valid as long as A and B use the same one).
+      const T* as = &As[buf][(wm * 64 + r16) * S + g * KS];
+      const T* bs = &Bs[buf][(wn * 64 + r16) * S + g * KS];
+#pragma unroll
+      for (int h = 0; h < KS / VEC; ++h) {
+        vec_t fa[4], fb[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          fa[t] = *reinterpret_cast<const vec_t*>(as + t * 16 * S + h * VEC);
+          fb[t] = *reinterpret_cast<const vec_t*>(bs + t * 16 * S + h * VEC);
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i][j] = X::mfma(fa[i][e], fb[j][e], acc[i][j]);
+      }
+    }
+    if (kt + 1 < nk) sstore(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: store the reduced block ----------------------------------
+  if (!active) return;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int grow = row0 + wm * 64 + i * 16 + X::acc_row(lane, r);
+      if (grow >= M) continue;
+      T* crow = C + (int64_t)grow * ldc;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int gcol = col0 + wn * 64 + j * 16 + r16;
+        if (gcol < N && (!LOWER || gcol <= grow)) crow[gcol] = acc[i][j][r];
+      }
+    }
+  }
+}
+
+}  // namespace mdet

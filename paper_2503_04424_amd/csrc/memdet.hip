@@ -1,0 +1,557 @@
+// C ABI, host scheduler and kernel launchers of the MI355X log-determinant library.
+//
+// The path (symmetric / LDL^T case of the paper's memory-constrained algorithm,
+// Sec. 2.2 and App. D), one block column k at a time:
+//   1. factor the block column: its diagonal block in place (A_kk = L D L^T) and
+//      the rows below it (L_ik = A_ik L_kk^-T D^-1), recursively by halves down to
+//      64-column leaves, every product inside it on the matrix cores;
+//   2. reduce log|d| and sign of its pivots;
+//   3. Schur-update every block of the trailing lower triangle:
+//      A_ij -= L_ik D_k L_jk^T   (full products off the diagonal, lower-triangle
+//      "Gramian" products on it);
+// and, when the matrix does not fit the device budget, block columns are kept
+// resident a group at a time while factored columns stream past from host memory.
+#include <hip/hip_runtime.h>
+
+#include <chrono>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "../../include/memdet.h"
+#include "kernels_leaf.h"
+#include "kernels_reduce.h"
+#include "kernels_update.h"
+#include "plan.h"
+
+namespace mdet {
+
+// ---------------------------------------------------------------------------
+// error plumbing
+// ---------------------------------------------------------------------------
+struct HipFail {
+  hipError_t code = hipSuccess;
+  bool ok() const { return code == hipSuccess; }
+  void check(hipError_t e) { if (code == hipSuccess && e != hipSuccess) code = e; }
+};
+
+#define MDET_HIP(ctx, call) (ctx).check((call))
+
+// ---------------------------------------------------------------------------
+// per-device stream / event cache (streams are created once and reused)
+// ---------------------------------------------------------------------------
+struct StreamSet {
+  hipStream_t main = nullptr, side = nullptr, h2d = nullptr, d2h = nullptr;
+  bool ready = false;
+};
+static std::mutex g_mu;
+static StreamSet g_streams[64];
+
+static hipError_t get_streams(int dev, StreamSet** out) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  StreamSet& s = g_streams[dev];
+  if (!s.ready) {
+    hipError_t e;
+    if ((e = hipStreamCreateWithFlags(&s.main, hipStreamNonBlocking)) != hipSuccess) return e;
+    if ((e = hipStreamCreateWithFlags(&s.side, hipStreamNonBlocking)) != hipSuccess) return e;
+    if ((e = hipStreamCreateWithFlags(&s.h2d, hipStreamNonBlocking)) != hipSuccess) return e;
+    if ((e = hipStreamCreateWithFlags(&s.d2h, hipStreamNonBlocking)) != hipSuccess) return e;
+    s.ready = true;
+  }
+  *out = &s;
+  return hipSuccess;
+}
+
+// A small pool of reusable events (timing disabled).
+struct EventPool {
+  std::vector<hipEvent_t> ev;
+  size_t next = 0;
+  HipFail* fail;
+  explicit EventPool(HipFail* f) : fail(f) {}
+  hipEvent_t get() {
+    if (next == ev.size()) {
+      hipEvent_t e = nullptr;
+      fail->check(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+      ev.push_back(e);
+    }
+    return ev[next++];
+  }
+  ~EventPool() { for (auto e : ev) if (e) (void)hipEventDestroy(e); }
+};
+
+// ---------------------------------------------------------------------------
+// kernel launchers
+// ---------------------------------------------------------------------------
+template <typename T>
+struct Launcher {
+  HipFail* fail;
+  T* dvec = nullptr;
+  T* dinv = nullptr;
+  DevFlags* flags = nullptr;
+  double fma = 0.0;
+  uint64_t launches = 0;
+
+  static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+  // C[M x N] -= A[M x K] diag(d) B[N x K]^T ; lower: only column <= row.
+  int update(hipStream_t st, T* C, int64_t ldc, const T* A, int64_t lda, const T* B, int64_t ldb,
+             const T* d, int64_t M, int64_t N, int64_t K, bool lower) {
+    if (M <= 0 || N <= 0 || K <= 0) return MDET_OK;
+    constexpr int vec = 16 / (int)sizeof(T);
+    if (K % 64 != 0 || lda % vec != 0 || ldb % vec != 0 || !aligned16(A) || !aligned16(B) ||
+        !aligned16(d) || M > INT32_MAX || N > INT32_MAX || K > INT32_MAX || ldc < N)
+      return MDET_EINVAL;
+    int64_t nbn = (N + UPD_BN - 1) / UPD_BN;
+    int64_t nblk = update_num_blocks(M, N, lower);
+    if (nblk > INT32_MAX) return MDET_EINVAL;
+    dim3 grid((unsigned)nblk), block(UPD_THREADS);
+    if (lower)
+      hipLaunchKernelGGL((schur_update_kernel<T, true>), grid, block, 0, st, C, ldc, A, lda, B, ldb,
+                         d, (int)M, (int)N, (int)K, (int)nbn);
+    else
+      hipLaunchKernelGGL((schur_update_kernel<T, false>), grid, block, 0, st, C, ldc, A, lda, B,
+                         ldb, d, (int)M, (int)N, (int)K, (int)nbn);
+    fail->check(hipGetLastError());
+    ++launches;
+    if (lower) {
+      // entries (r, c), c <= r, of an M x N trapezoid whose (0,0) is on the diagonal
+      double t = (double)(M < N ? M : N);
+      fma += (t * (t + 1) / 2 + (double)(M - (int64_t)t) * (double)N) * (double)K;
+    } else {
+      fma += (double)M * (double)N * (double)K;
+    }
+    return MDET_OK;
+  }
+
+  // Factor block column: P at its diagonal entry, m rows, w columns (w <= m).
+  // d0: index of its first pivot in dvec/dinv.
+  int factor_cols(hipStream_t st, T* P, int64_t ld, int64_t m, int64_t w, int64_t d0) {
+    if (w <= 0) return MDET_OK;
+    if (w <= LEAF) {
+      hipLaunchKernelGGL((leaf_factor_kernel<T>), dim3(1), dim3(64), 0, st, P, ld, (int)w,
+                         dvec + d0, dinv + d0, (long long)d0, flags);
+      fail->check(hipGetLastError());
+      ++launches;
+      fma += ((double)w * w * w - (double)w) / 6.0;
+      int64_t below = m - w;
+      if (below > 0) {
+        if (below > INT32_MAX) return MDET_EINVAL;
+        int64_t nblk = (below + LEAF * SOLVE_WAVES - 1) / (LEAF * SOLVE_WAVES);
+        hipLaunchKernelGGL((leaf_solve_kernel<T>), dim3((unsigned)nblk), dim3(64 * SOLVE_WAVES), 0,
+                           st, P + w * ld, ld, (int)below, (int)w, (const T*)P, ld,
+                           (const T*)(dinv + d0));
+        fail->check(hipGetLastError());
+        ++launches;
+        fma += (double)below * ((double)w * (w - 1) / 2.0);
+      }
+      return MDET_OK;
+    }
+    // split at a multiple of the leaf width nearest the middle
+    int64_t leaves = (w + LEAF - 1) / LEAF;
+    int64_t w1 = (leaves / 2) * LEAF;
+    int rc = factor_cols(st, P, ld, m, w1, d0);
+    if (rc != MDET_OK) return rc;
+    // columns [w1, w), rows [w1, m)  -=  L[rows, 0:w1] D L[cols, 0:w1]^T
+    T* C = P + w1 * ld + w1;
+    const T* A = P + w1 * ld;
+    rc = update(st, C, ld, A, ld, A, ld, dvec + d0, m - w1, w - w1, w1, true);
+    if (rc != MDET_OK) return rc;
+    return factor_cols(st, C, ld, m - w1, w - w1, d0 + w1);
+  }
+
+  void reduce(hipStream_t st, int64_t n, int64_t bs, int64_t T_, double* partial, double* out,
+              double* running) {
+    if (T_ > 0) {
+      hipLaunchKernelGGL((logdet_partial_kernel<T>), dim3((unsigned)T_), dim3(RED_THREADS), 0, st,
+                         (const T*)dvec, n, bs, partial);
+      fail->check(hipGetLastError());
+      ++launches;
+    }
+    hipLaunchKernelGGL(logdet_combine_kernel, dim3(1), dim3(64), 0, st, (const double*)partial, T_,
+                       out, running);
+    fail->check(hipGetLastError());
+    ++launches;
+  }
+};
+
+// One block column as the device sees it: `base` points at its diagonal entry.
+template <typename T>
+struct ColRef {
+  T* base;
+  int64_t ld;
+};
+
+// ---------------------------------------------------------------------------
+// in-core driver: right-looking over block columns, optional look-ahead
+// ---------------------------------------------------------------------------
+// cols[j] for j in [jb, je) must be resident and hold columns already updated by
+// every block column < jb.  `dense`: all columns live in one row-major array, so
+// the bulk of a trailing update can be a single launch.
+template <typename T>
+static int factor_resident(Launcher<T>& L, const Plan& pl, std::vector<ColRef<T>>& cols, int64_t jb,
+                           int64_t je, bool dense, bool lookahead, hipStream_t s0, hipStream_t s1,
+                           EventPool& events) {
+  const int64_t bs = pl.bs, n = pl.n;
+  hipEvent_t ev_bulk_prev = nullptr;
+  if (!lookahead) s1 = s0;
+  for (int64_t k = jb; k < je; ++k) {
+    const int64_t wk = pl.col_width(k);
+    const int64_t mk = n - k * bs;
+    int rc = L.factor_cols(s0, cols[k].base, cols[k].ld, mk, wk, k * bs);
+    if (rc != MDET_OK) return rc;
+    if (k + 1 >= je) break;
+    hipEvent_t ev_panel = nullptr;
+    if (lookahead && k + 2 < je) {
+      ev_panel = events.get();
+      L.fail->check(hipEventRecord(ev_panel, s0));
+    }
+    // next column first (on the panel stream), so its factorisation can start early
+    if (lookahead && ev_bulk_prev) L.fail->check(hipStreamWaitEvent(s0, ev_bulk_prev, 0));
+    {
+      const int64_t j = k + 1;
+      const T* A = cols[k].base + (j - k) * bs * cols[k].ld;
+      rc = L.update(s0, cols[j].base, cols[j].ld, A, cols[k].ld, A, cols[k].ld, L.dvec + k * bs,
+                    n - j * bs, pl.col_width(j), wk, true);
+      if (rc != MDET_OK) return rc;
+    }
+    if (k + 2 < je) {
+      if (lookahead) L.fail->check(hipStreamWaitEvent(s1, ev_panel, 0));
+      if (dense) {
+        const int64_t j = k + 2;
+        const T* A = cols[k].base + (j - k) * bs * cols[k].ld;
+        // all remaining resident columns in one launch (they are contiguous in memory)
+        int64_t ncols = (je < pl.T ? je * bs : n) - j * bs;
+        rc = L.update(s1, cols[j].base, cols[j].ld, A, cols[k].ld, A, cols[k].ld, L.dvec + k * bs,
+                      n - j * bs, ncols, wk, true);
+        if (rc != MDET_OK) return rc;
+      } else {
+        for (int64_t j = k + 2; j < je; ++j) {
+          const T* A = cols[k].base + (j - k) * bs * cols[k].ld;
+          rc = L.update(s1, cols[j].base, cols[j].ld, A, cols[k].ld, A, cols[k].ld,
+                        L.dvec + k * bs, n - j * bs, pl.col_width(j), wk, true);
+          if (rc != MDET_OK) return rc;
+        }
+      }
+      if (lookahead) {
+        ev_bulk_prev = events.get();
+        L.fail->check(hipEventRecord(ev_bulk_prev, s1));
+      }
+    }
+  }
+  // join the side stream back into the main one
+  if (lookahead && ev_bulk_prev) L.fail->check(hipStreamWaitEvent(s0, ev_bulk_prev, 0));
+  return MDET_OK;
+}
+
+// ---------------------------------------------------------------------------
+// result collection
+// ---------------------------------------------------------------------------
+struct DeviceOut {
+  double out[3];
+  DevFlags flags;
+};
+
+static int finish_result(const DeviceOut& o, mdet_result* r) {
+  r->negative_pivots = (int64_t)o.out[2];
+  if (o.flags.first_bad != ~0ull) {
+    r->bad_pivot_index = (int64_t)o.flags.first_bad;
+    if (o.flags.bad_kind == 1) {
+      r->sign = 0;
+      r->logabsdet = -HUGE_VAL;
+      return MDET_ESINGULAR;
+    }
+    r->sign = 0;
+    r->logabsdet = std::nan("");
+    return MDET_ENONFINITE;
+  }
+  r->bad_pivot_index = -1;
+  r->logabsdet = o.out[0];
+  r->sign = (int)o.out[1];
+  if (!std::isfinite(r->logabsdet)) return MDET_ENONFINITE;
+  return MDET_OK;
+}
+
+static void init_result(mdet_result* r, const Plan& pl) {
+  std::memset(r, 0, sizeof(*r));
+  r->bad_pivot_index = -1;
+  r->sign = 1;
+  r->block_size_used = pl.bs;
+  r->num_blocks = pl.T;
+  r->out_of_core = pl.out_of_core;
+  r->num_superpanels = (int32_t)pl.panels.size();
+}
+
+// Workspace: either the caller's buffer or a library allocation.
+struct Workspace {
+  char* base = nullptr;
+  uint64_t bytes = 0;
+  bool owned = false;
+  int acquire(const mdet_params& p, uint64_t need, HipFail& f) {
+    if (p.dev_workspace) {
+      if (p.dev_workspace_bytes < need || ((uintptr_t)p.dev_workspace & 255u)) return MDET_ENOMEM_DEVICE;
+      base = (char*)p.dev_workspace;
+      bytes = p.dev_workspace_bytes;
+      return MDET_OK;
+    }
+    void* q = nullptr;
+    hipError_t e = hipMalloc(&q, need ? need : 256);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      f.code = e;
+      return MDET_ENOMEM_DEVICE;
+    }
+    base = (char*)q;
+    bytes = need;
+    owned = true;
+    return MDET_OK;
+  }
+  ~Workspace() { if (owned && base) (void)hipFree(base); }
+};
+
+template <typename T>
+static void bind_small(Launcher<T>& L, char* base, const SmallArea& sa) {
+  L.dvec = (T*)(base + sa.dvec);
+  L.dinv = (T*)(base + sa.dinv);
+  L.flags = (DevFlags*)(base + sa.flags);
+}
+
+template <typename T>
+static void reset_flags(Launcher<T>& L, hipStream_t st) {
+  // 0xFF bytes: first_bad = ~0 (none)
+  L.fail->check(hipMemsetAsync(L.flags, 0xFF, sizeof(DevFlags), st));
+}
+
+// ---------------------------------------------------------------------------
+// mdet_logdet_device
+// ---------------------------------------------------------------------------
+template <typename T>
+static int logdet_device_t(const mdet_params& p, const Plan& pl, T* dA, int64_t ld, mdet_result* res,
+                           T* diag) {
+  HipFail fail;
+  int dev = 0;
+  MDET_HIP(fail, hipGetDevice(&dev));
+  StreamSet* ss = nullptr;
+  MDET_HIP(fail, get_streams(dev, &ss));
+  if (!fail.ok()) { res->hip_error = fail.code; return MDET_EHIP; }
+
+  Workspace ws;
+  int rc = ws.acquire(p, pl.dev_bytes, fail);
+  if (rc != MDET_OK) { res->hip_error = fail.code; return rc; }
+  res->dev_bytes_high_water = pl.dev_bytes;
+
+  const SmallArea sa = small_area(pl.n, pl.T, pl.beta);
+  Launcher<T> L;
+  L.fail = &fail;
+  bind_small(L, ws.base, sa);
+  double* partial = (double*)(ws.base + sa.partial);
+  double* out = (double*)(ws.base + sa.out);
+  double* running = (double*)(ws.base + sa.running);
+
+  EventPool events(&fail);
+  hipStream_t user = (hipStream_t)p.stream;
+  hipStream_t s0 = ss->main, s1 = ss->side;
+  // order our work after whatever the caller queued on its stream
+  hipEvent_t ev_in = events.get();
+  MDET_HIP(fail, hipEventRecord(ev_in, user));
+  MDET_HIP(fail, hipStreamWaitEvent(s0, ev_in, 0));
+
+  T* W = dA;
+  int64_t ldw = ld;
+  if (pl.need_copy && pl.n > 0) {
+    constexpr int vec = 16 / (int)sizeof(T);
+    ldw = round_up(pl.n, vec);
+    W = (T*)(ws.base + sa.total);
+    MDET_HIP(fail, hipMemcpy2DAsync(W, ldw * sizeof(T), dA, ld * sizeof(T), pl.n * sizeof(T), pl.n,
+                                    hipMemcpyDeviceToDevice, s0));
+  }
+  reset_flags(L, s0);
+
+  std::vector<ColRef<T>> cols((size_t)pl.T);
+  for (int64_t j = 0; j < pl.T; ++j) cols[j] = {W + j * pl.bs * ldw + j * pl.bs, ldw};
+  const bool lookahead = !(p.flags & MDET_FLAG_NO_LOOKAHEAD);
+  rc = factor_resident(L, pl, cols, 0, pl.T, true, lookahead, s0, s1, events);
+  if (rc == MDET_OK) {
+    L.reduce(s0, pl.n, pl.bs, pl.T, partial, out, running);
+    if (diag && pl.n > 0)
+      MDET_HIP(fail, hipMemcpyAsync(diag, L.dvec, pl.n * sizeof(T), hipMemcpyDeviceToDevice, s0));
+  }
+  DeviceOut o;
+  std::memset(&o, 0, sizeof(o));
+  if (rc == MDET_OK) {
+    MDET_HIP(fail, hipMemcpyAsync(o.out, out, sizeof(o.out), hipMemcpyDeviceToHost, s0));
+    MDET_HIP(fail, hipMemcpyAsync(&o.flags, L.flags, sizeof(DevFlags), hipMemcpyDeviceToHost, s0));
+  }
+  MDET_HIP(fail, hipStreamSynchronize(s1));
+  MDET_HIP(fail, hipStreamSynchronize(s0));
+  res->flops = 2.0 * L.fma;
+  res->kernel_launches = L.launches;
+  if (!fail.ok()) { res->hip_error = fail.code; return MDET_EHIP; }
+  if (rc != MDET_OK) return rc;
+  return finish_result(o, res);
+}
+
+}  // namespace mdet
+
+// ===========================================================================
+// extern "C"
+// ===========================================================================
+using namespace mdet;
+
+static bool params_ok(const mdet_params* p) {
+  return p && p->struct_size == sizeof(mdet_params) && p->n >= 0 && p->block_size >= 0 &&
+         (p->dtype == MDET_F32 || p->dtype == MDET_F64);
+}
+
+extern "C" {
+
+const char* mdet_strerror(int s) {
+  switch (s) {
+    case MDET_OK: return "ok";
+    case MDET_EINVAL: return "invalid argument";
+    case MDET_EBUDGET: return "memory budget below the minimum working set";
+    case MDET_ENOMEM_DEVICE: return "device memory allocation failed or workspace too small";
+    case MDET_ENOMEM_HOST: return "host memory allocation failed";
+    case MDET_EHIP: return "HIP runtime error (see result.hip_error)";
+    case MDET_ESINGULAR: return "matrix is singular: exact zero pivot";
+    case MDET_ENONFINITE: return "non-finite pivot";
+    case MDET_EPROVIDER: return "block provider failed";
+    default: return "unknown status";
+  }
+}
+
+const char* mdet_version(void) { return "memdet-mi355x 0.1 (gfx950)"; }
+
+int mdet_paper_block_rule(int64_t m, int32_t beta, uint64_t c, int64_t* n_b, int64_t* b) {
+  if (m <= 0 || beta <= 0 || c == 0 || !n_b || !b) return MDET_EINVAL;
+  long double r = (long double)m * sqrtl((long double)beta / (long double)c);
+  int64_t nb;
+  if (r <= 1.0L) nb = 1;
+  else if (r <= 2.0L / sqrtl(3.0L)) nb = 2;
+  else nb = (int64_t)ceill(2.0L * r);
+  *n_b = nb;
+  *b = 1 + (m - 1) / nb;
+  return MDET_OK;
+}
+
+double mdet_paper_fma_count(int64_t m) {
+  double x = (double)m;
+  return x * x * x / 6.0 - x * x / 4.0 + x / 12.0;
+}
+
+int64_t mdet_host_layout_offset(int64_t n, int64_t b, int64_t j) {
+  if (n < 0 || b <= 0 || b % 64 != 0 || j < 0) return -1;
+  Plan pl;
+  pl.n = n; pl.bs = b; pl.T = n > 0 ? (n + b - 1) / b : 0;
+  if (j > pl.T) return -1;
+  if (pl.T == 0) return 0;
+  return pl.col_offset(j);
+}
+
+int mdet_plan(const mdet_params* p, int for_device_input, mdet_plan_info* info) {
+  if (!params_ok(p) || !info) return MDET_EINVAL;
+  Plan pl;
+  int rc = make_plan(*p, for_device_input != 0, round_up(p->n > 0 ? p->n : 1, 4), pl);
+  std::memset(info, 0, sizeof(*info));
+  info->block_size_used = pl.bs;
+  info->num_blocks = pl.T;
+  if (rc != MDET_OK) return rc;
+  info->out_of_core = pl.out_of_core;
+  info->num_superpanels = (int32_t)pl.panels.size();
+  info->dev_bytes_needed = pl.dev_bytes;
+  info->host_bytes_needed = pl.host_bytes;
+  info->host_matrix_bytes = pl.layout_bytes;
+  info->stream_bytes_h2d = pl.h2d;
+  info->stream_bytes_d2h = pl.d2h;
+  paper_work_split(pl.T, (double)pl.bs, &info->fma_decomp, &info->fma_solve, &info->fma_gemm,
+                   &info->fma_syrk);
+  return MDET_OK;
+}
+
+int mdet_workspace_query(const mdet_params* p, int for_device_input, uint64_t* dev_bytes,
+                         uint64_t* host_bytes) {
+  mdet_plan_info info;
+  int rc = mdet_plan(p, for_device_input, &info);
+  if (rc != MDET_OK) return rc;
+  if (dev_bytes) *dev_bytes = info.dev_bytes_needed;
+  if (host_bytes) *host_bytes = info.host_bytes_needed;
+  return MDET_OK;
+}
+
+int mdet_logdet_device(const mdet_params* p, void* dA, int64_t ld, mdet_result* res, void* diag) {
+  if (!params_ok(p) || !res) return MDET_EINVAL;
+  if (p->n > 0 && (!dA || ld < p->n)) return MDET_EINVAL;
+  Plan pl;
+  int rc = make_plan(*p, true, ld, pl);
+  init_result(res, pl);
+  if (rc != MDET_OK) return rc;
+  if (p->n > 0 && ((uintptr_t)dA & 15u)) return MDET_EINVAL;
+  auto t0 = std::chrono::steady_clock::now();
+  if (p->dtype == MDET_F64) rc = logdet_device_t<double>(*p, pl, (double*)dA, ld, res, (double*)diag);
+  else rc = logdet_device_t<float>(*p, pl, (float*)dA, ld, res, (float*)diag);
+  res->t_total = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+  return rc;
+}
+
+int mdet_step_schur_update(int32_t dtype, void* C, int64_t ldc, const void* A, int64_t lda,
+                           const void* B, int64_t ldb, const void* d, int64_t M, int64_t N,
+                           int64_t K, int32_t lower, void* stream) {
+  if (!C || !A || !B || !d || M < 0 || N < 0 || K < 0) return MDET_EINVAL;
+  HipFail fail;
+  int rc;
+  if (dtype == MDET_F64) {
+    Launcher<double> L; L.fail = &fail;
+    rc = L.update((hipStream_t)stream, (double*)C, ldc, (const double*)A, lda, (const double*)B, ldb,
+                  (const double*)d, M, N, K, lower != 0);
+  } else if (dtype == MDET_F32) {
+    Launcher<float> L; L.fail = &fail;
+    rc = L.update((hipStream_t)stream, (float*)C, ldc, (const float*)A, lda, (const float*)B, ldb,
+                  (const float*)d, M, N, K, lower != 0);
+  } else return MDET_EINVAL;
+  if (!fail.ok()) return MDET_EHIP;
+  return rc;
+}
+
+int mdet_step_panel_factor(int32_t dtype, void* P, int64_t ld, int64_t m, int64_t w, void* d,
+                           void* dinv, int64_t pivot_index0, void* flags, void* stream) {
+  if (!P || !d || !dinv || !flags || m < 0 || w < 0 || w > m || ld < w) return MDET_EINVAL;
+  HipFail fail;
+  int rc;
+  if (dtype == MDET_F64) {
+    if (ld % 2 || ((uintptr_t)P & 15u)) return MDET_EINVAL;
+    Launcher<double> L; L.fail = &fail;
+    // the launcher indexes dvec/dinv by global pivot index
+    L.dvec = (double*)d - pivot_index0; L.dinv = (double*)dinv - pivot_index0; L.flags = (DevFlags*)flags;
+    rc = L.factor_cols((hipStream_t)stream, (double*)P, ld, m, w, pivot_index0);
+  } else if (dtype == MDET_F32) {
+    if (ld % 4 || ((uintptr_t)P & 15u)) return MDET_EINVAL;
+    Launcher<float> L; L.fail = &fail;
+    L.dvec = (float*)d - pivot_index0; L.dinv = (float*)dinv - pivot_index0; L.flags = (DevFlags*)flags;
+    rc = L.factor_cols((hipStream_t)stream, (float*)P, ld, m, w, pivot_index0);
+  } else return MDET_EINVAL;
+  if (!fail.ok()) return MDET_EHIP;
+  return rc;
+}
+
+int mdet_step_logdet_reduce(int32_t dtype, const void* d, int64_t n, double* out, void* stream) {
+  if (!d || !out || n < 0) return MDET_EINVAL;
+  HipFail fail;
+  // single block column: partial terms live right behind the three outputs
+  double* partial = out + 3;
+  if (dtype == MDET_F64) {
+    Launcher<double> L; L.fail = &fail; L.dvec = (double*)d;
+    L.reduce((hipStream_t)stream, n, n > 0 ? n : 1, n > 0 ? 1 : 0, partial, out, nullptr);
+  } else if (dtype == MDET_F32) {
+    Launcher<float> L; L.fail = &fail; L.dvec = (float*)d;
+    L.reduce((hipStream_t)stream, n, n > 0 ? n : 1, n > 0 ? 1 : 0, partial, out, nullptr);
+  } else return MDET_EINVAL;
+  return fail.ok() ? MDET_OK : MDET_EHIP;
+}
+
+}  // extern "C"
+
+// TEMPORARY stubs (replaced by the host scheduler)
+extern "C" int mdet_logdet_host(const mdet_params*, void*, mdet_result*, void*) { return MDET_EINVAL; }
+extern "C" int mdet_logdet_provider(const mdet_params*, mdet_block_provider, void*, mdet_result*, void*) { return MDET_EINVAL; }

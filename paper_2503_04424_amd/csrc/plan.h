@@ -1,0 +1,171 @@
+// Host-side planner: block grid, residency plan and traffic prediction.
+//
+// The paper picks the number of blocks n_b from a memory cap c with
+// r = m sqrt(beta/c) (App. D) and keeps 3-4 equal blocks in memory.  On a GPU with
+// a host link far slower than HBM, four equal blocks would leave the matrix cores
+// waiting; this planner instead keeps a *group of whole block columns* ("super
+// panel") resident and streams the already-factored block columns past it, so
+// that each streamed block is used for as many products as the group has columns.
+// The budget is still a hard cap: everything the call allocates on the device is
+// accounted for here.  Pure C++, no HIP.
+#pragma once
+#include <stdint.h>
+#include <vector>
+
+#include "../../include/memdet.h"
+
+namespace mdet {
+
+inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+struct SuperPanel {
+  int64_t j0, j1;            // block columns [j0, j1)
+  uint64_t resident_bytes;   // bytes of those columns (rows from their diagonal down)
+};
+
+struct Plan {
+  int64_t n = 0, bs = 0, T = 0;
+  int beta = 8;
+  bool device_input = false;
+  bool out_of_core = false;
+  bool need_copy = false;          // device input: work on a copy (overwrite = 0)
+  uint64_t small_bytes = 0;        // pivots, reciprocals, flags, reduction scratch
+  uint64_t layout_bytes = 0;       // packed lower block-column layout
+  uint64_t copy_bytes = 0;
+  uint64_t ring_tiles = 3;         // streamed row blocks in flight (out-of-core)
+  uint64_t tile_bytes = 0;
+  uint64_t dev_bytes = 0;          // total device bytes the call uses
+  uint64_t host_bytes = 0;
+  uint64_t h2d = 0, d2h = 0;
+  std::vector<SuperPanel> panels;
+
+  int64_t col_width(int64_t j) const { int64_t w = n - j * bs; return w < bs ? w : bs; }
+  int64_t col_rows(int64_t j) const { return n - j * bs; }
+  // element offset of block column j in the packed layout
+  int64_t col_offset(int64_t j) const {
+    // sum_{t<j} (n - t bs) * w_t ; all t < j <= T-1 have w_t = bs unless j == T
+    int64_t full = j < T ? j : T - 1;
+    int64_t off = full * n * bs - bs * bs * (full * (full - 1) / 2);
+    if (j == T && T > 0) off += col_rows(T - 1) * col_width(T - 1);
+    return off;
+  }
+  uint64_t col_bytes(int64_t j) const { return (uint64_t)col_rows(j) * col_width(j) * beta; }
+  uint64_t block_bytes(int64_t i, int64_t k) const {   // block (i, k), i >= k
+    return (uint64_t)col_width(i) * col_width(k) * beta;   // rows of block row i = w_i
+  }
+};
+
+inline int64_t default_block_size(int64_t n) {
+  int64_t b = round_up(n / 16 > 0 ? n / 16 : 1, 64);
+  if (b < 256) b = 256;
+  if (b > 4096) b = 4096;
+  return b;
+}
+
+inline uint64_t align256(uint64_t x) { return (x + 255) / 256 * 256; }
+
+// Layout of the small scratch area (offsets in bytes from its start).
+struct SmallArea {
+  uint64_t dvec, dinv, flags, partial, out, running, total;
+};
+inline SmallArea small_area(int64_t n, int64_t T, int beta) {
+  SmallArea a;
+  uint64_t o = 0;
+  a.dvec = o; o += align256((uint64_t)(n > 0 ? n : 1) * beta);
+  a.dinv = o; o += align256((uint64_t)(n > 0 ? n : 1) * beta);
+  a.flags = o; o += 256;
+  a.partial = o; o += align256((uint64_t)(T > 0 ? T : 1) * 3 * 8);
+  a.out = o; o += 256;
+  a.running = o; o += align256((uint64_t)(T > 0 ? T : 1) * 8);
+  a.total = o;
+  return a;
+}
+
+// Returns an mdet_status.
+inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& pl) {
+  if (p.n < 0 || p.block_size < 0) return MDET_EINVAL;
+  if (p.dtype != MDET_F32 && p.dtype != MDET_F64) return MDET_EINVAL;
+  pl.n = p.n;
+  pl.beta = p.dtype == MDET_F64 ? 8 : 4;
+  pl.bs = round_up(p.block_size > 0 ? p.block_size : default_block_size(p.n), 64);
+  pl.T = p.n > 0 ? (p.n + pl.bs - 1) / pl.bs : 0;
+  pl.device_input = device_input;
+  pl.tile_bytes = (uint64_t)pl.bs * pl.bs * pl.beta;
+  pl.small_bytes = small_area(pl.n, pl.T, pl.beta).total;
+  pl.layout_bytes = pl.T > 0 ? (uint64_t)pl.col_offset(pl.T) * pl.beta : 0;
+  pl.panels.clear();
+  pl.h2d = pl.d2h = 0;
+  pl.host_bytes = 0;
+  const uint64_t budget = p.mem_budget_bytes;
+
+  if (device_input) {
+    const int vec = 16 / pl.beta;
+    const bool aligned = ld % vec == 0;
+    pl.need_copy = !p.overwrite || !aligned;
+    if (pl.need_copy) {
+      int64_t ldp = round_up(p.n > 0 ? p.n : 1, vec);
+      pl.copy_bytes = align256((uint64_t)p.n * ldp * pl.beta);
+    }
+    pl.dev_bytes = pl.small_bytes + pl.copy_bytes;
+    pl.out_of_core = false;
+    if (budget && pl.dev_bytes > budget) return MDET_EBUDGET;
+    return MDET_OK;
+  }
+
+  const bool force_ooc = (p.flags & MDET_FLAG_FORCE_OUT_OF_CORE) != 0;
+  const uint64_t incore = pl.small_bytes + align256(pl.layout_bytes);
+  if (!force_ooc && (budget == 0 || incore <= budget)) {
+    pl.out_of_core = false;
+    pl.dev_bytes = incore;
+    pl.h2d = pl.layout_bytes;
+    pl.panels.push_back({0, pl.T, pl.layout_bytes});
+    return MDET_OK;
+  }
+
+  // ---- out-of-core: greedy groups of block columns ------------------------
+  pl.out_of_core = true;
+  // with no cap at all (forced streaming) behave as if a quarter of the layout were allowed
+  uint64_t cap = budget ? budget : (pl.small_bytes + pl.layout_bytes / 4 + 8 * pl.tile_bytes);
+  uint64_t peak = 0;
+  int64_t j0 = 0;
+  while (j0 < pl.T) {
+    uint64_t resident = 0;
+    int64_t j1 = j0;
+    while (j1 < pl.T) {
+      uint64_t cand = resident + align256(pl.col_bytes(j1));
+      uint64_t wc = (uint64_t)(j1 + 1 - j0);
+      // streamed factor blocks: two sets of wc row blocks of the group's own rows
+      // (operands reused by every streamed block) plus the ring
+      uint64_t stream = (j0 > 0) ? (2 * wc + pl.ring_tiles) * align256(pl.tile_bytes) : 0;
+      if (pl.small_bytes + cand + stream > cap) break;
+      resident = cand;
+      ++j1;
+    }
+    if (j1 == j0) return MDET_EBUDGET;   // not even one block column fits
+    uint64_t wc = (uint64_t)(j1 - j0);
+    uint64_t stream = (j0 > 0) ? (2 * wc + pl.ring_tiles) * align256(pl.tile_bytes) : 0;
+    uint64_t use = pl.small_bytes + resident + stream;
+    if (use > peak) peak = use;
+    pl.panels.push_back({j0, j1, resident});
+    // traffic: originals in, factors out, and every earlier column's rows from j0 down
+    for (int64_t j = j0; j < j1; ++j) { pl.h2d += pl.col_bytes(j); pl.d2h += pl.col_bytes(j); }
+    for (int64_t k = 0; k < j0; ++k)
+      pl.h2d += (uint64_t)pl.col_rows(j0) * pl.col_width(k) * pl.beta;
+    j0 = j1;
+  }
+  pl.dev_bytes = peak;
+  pl.host_bytes = p.overwrite ? 0 : pl.layout_bytes;
+  return MDET_OK;
+}
+
+// App. E.1 operation counts (fused multiply-adds) for n_b blocks of order b.
+inline void paper_work_split(int64_t nb, double b, double* decomp, double* solve, double* gemm,
+                             double* syrk) {
+  double N = (double)nb;
+  *decomp = N * (b * b * b / 6 - b * b / 4 + b / 12);
+  *solve = (N * N / 2 - N / 2) * (b * b * b / 2 - b * b / 2);
+  *gemm = (N * N * N / 6 - N * N / 2 + N / 3) * b * b * b;
+  *syrk = (N * N / 2 - N / 2) * (b * b * b / 2);
+}
+
+}  // namespace mdet

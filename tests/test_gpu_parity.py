@@ -1,0 +1,257 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle.
+
+Bars (the benchmark spec): relative error of logdet <= 1e-10 in fp64, <= 1e-4 in fp32,
+sign and singular/negative-pivot reporting exact.  Inputs are seeded and formed
+on the CPU so both sides read the same bits.
+"""
+import math
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f64": 1e-10, "f32": 1e-4}
+
+
+def rel(a, b):
+    return abs(a - b) / max(1.0, abs(b))
+
+
+@pytest.fixture(scope="module")
+def M():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2503_04424_amd as m
+    m.load()          # fails loudly if the HIP library is not built
+    return m
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+# ---------------------------------------------------------------------------
+# single steps
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("M_,N_,K_,lower", [
+    (128, 128, 64, False), (256, 128, 128, False), (300, 200, 64, False),
+    (1000, 517, 192, False), (64, 64, 64, True), (384, 384, 128, True),
+    (777, 333, 64, True), (1, 1, 64, False), (129, 1, 64, True), (2050, 1030, 256, True),
+])
+def test_schur_update_against_definition(M, dtype, M_, N_, K_, lower):
+    rng = np.random.default_rng(M_ * 7 + N_)
+    npdt = np.float64 if dtype == "f64" else np.float32
+    a = rng.standard_normal((M_, K_)).astype(npdt)
+    b = rng.standard_normal((N_, K_)).astype(npdt)
+    d = rng.uniform(0.5, 2.0, K_).astype(npdt) * rng.choice([-1, 1], K_).astype(npdt)
+    c = rng.standard_normal((M_, N_)).astype(npdt)
+    # definition, in float64 on the same bits
+    ref = c.astype(np.float64) - (a.astype(np.float64) * d.astype(np.float64)) @ b.astype(np.float64).T
+    cd = dev(c)
+    M.mdet_step_schur_update(cd, dev(a), dev(b), dev(d), lower=lower)
+    torch.cuda.synchronize()
+    got = cd.cpu().numpy().astype(np.float64)
+    tol = (1e-13 if dtype == "f64" else 1e-4) * math.sqrt(K_)
+    if lower:
+        i, j = np.indices((M_, N_))
+        low = j <= i
+        assert np.max(np.abs(got - ref)[low]) < tol * 10
+        # entries above the diagonal are left untouched
+        assert np.array_equal(got[~low], c.astype(np.float64)[~low])
+    else:
+        assert np.max(np.abs(got - ref)) < tol * 10
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("m,w", [(64, 64), (200, 64), (40, 40), (512, 256), (1000, 232), (130, 130)])
+def test_panel_factor_matches_oracle_factor(M, dtype, m, w):
+    """Block column of an SPD matrix: pivots and every entry of L vs the oracle."""
+    wl = W.scaled_down(W.config(1), m)
+    wl.dtype = dtype
+    a = wl.dense()
+    r = oracle.ldlt_logdet(a, want_diag=True, want_L=True)
+    # rows must stay 16-byte aligned for the step entry point: pad the leading dimension
+    ad = torch.zeros((m, (m + 3) // 4 * 4), dtype=dev(a).dtype, device="cuda")[:, :m]
+    ad.copy_(dev(a))
+    d = torch.zeros(w, dtype=ad.dtype, device="cuda")
+    dinv = torch.zeros_like(d)
+    flags = torch.full((4,), -1, dtype=torch.int64, device="cuda")
+    M.mdet_step_panel_factor(ad, w, d, dinv, flags)
+    torch.cuda.synchronize()
+    got = ad.cpu().numpy().astype(np.float64)
+    tol = 1e-11 if dtype == "f64" else 2e-3
+    dd = d.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(dd - r.diag[:w]) / np.abs(r.diag[:w])) < tol
+    assert np.max(np.abs(dinv.cpu().numpy().astype(np.float64) * r.diag[:w] - 1)) < tol
+    i, j = np.indices((m, w))
+    strict = i > j
+    assert np.max(np.abs(got[:, :w] - r.L[:, :w])[strict]) < tol
+    assert int(flags[0].item()) == -1
+
+
+# ---------------------------------------------------------------------------
+# whole path, device entry point
+# ---------------------------------------------------------------------------
+def run_device(M, a, bs, **kw):
+    ad = dev(a)
+    diag = torch.empty(a.shape[0], dtype=ad.dtype, device="cuda")
+    res = M.mdet_logdet_device(ad, block_size=bs, diag=diag, **kw)
+    return res, diag.cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("name,wl", [
+    ("cfg1", lambda: W.config(1)),
+    ("kms512", lambda: W.kms(512, 0.5, block_size=128)),
+    ("cfg2_1536", lambda: W.scaled_down(W.config(2), 1536, 256)),
+    ("cfg3_1280", lambda: W.scaled_down(W.config(3), 1280, 192)),
+    ("cfg4_1100", lambda: W.scaled_down(W.config(4), 1100, 256)),
+    ("cfg5_1024", lambda: W.scaled_down(W.config(5), 1024, 128)),
+])
+def test_logdet_device_fp64_matches_oracle(M, name, wl):
+    w = wl()
+    a = w.dense()
+    o = oracle.ldlt_logdet(a, want_diag=True)
+    res, diag = run_device(M, a, w.block_size)
+    assert res.status == 0 and res.sign == o.sign
+    assert rel(res.logabsdet, o.logabsdet) <= TOL["f64"]
+    assert res.negative_pivots == o.negative_pivots
+    # leading principal minors (App. D): running sums of log|d|
+    cum = np.cumsum(np.log(np.abs(diag)))
+    assert np.max(np.abs(cum - o.cum_logabs) / np.maximum(1, np.abs(o.cum_logabs))) <= TOL["f64"]
+    cf = w.closed_form_logdet()
+    if cf is not None:
+        assert rel(res.logabsdet, cf) <= TOL["f64"]
+
+
+@pytest.mark.parametrize("name,wl", [
+    ("cfg1", lambda: W.config(1)),
+    ("kms512", lambda: W.kms(512, 0.5, block_size=128)),
+    ("cfg1_2000", lambda: W.scaled_down(W.config(1), 2000, 256)),
+])
+def test_logdet_device_fp32_matches_oracle_on_same_bits(M, name, wl):
+    w = wl()
+    w.dtype = "f32"
+    a = w.dense()
+    assert a.dtype == np.float32
+    o = oracle.ldlt_logdet(a)            # oracle reads the fp32 bits exactly
+    res, _ = run_device(M, a, w.block_size)
+    assert res.status == 0 and res.sign == o.sign
+    assert rel(res.logabsdet, o.logabsdet) <= TOL["f32"]
+
+
+@pytest.mark.parametrize("n", [0, 1, 2, 63, 64, 65, 127, 129, 257, 777, 1001])
+def test_ragged_and_tiny_orders(M, n):
+    if n == 0:
+        a = torch.empty((0, 0), dtype=torch.float64, device="cuda")
+        res = M.mdet_logdet_device(a, block_size=64)
+        assert (res.status, res.sign, res.logabsdet) == (0, 1, 0.0)
+        return
+    a = W.scaled_down(W.config(1), n).dense()
+    o = oracle.ldlt_logdet(a)
+    for bs in (64, 128, 320):
+        res, _ = run_device(M, a, bs)
+        assert res.sign == o.sign and rel(res.logabsdet, o.logabsdet) <= TOL["f64"], (n, bs)
+
+
+def test_odd_leading_dimension_and_preserved_input(M):
+    n = 333
+    a = W.scaled_down(W.config(1), n).dense()
+    view = torch.zeros((n, 339), dtype=torch.float64, device="cuda")[:, :n]
+    view.copy_(torch.from_numpy(a))
+    before = view.clone()
+    o = oracle.ldlt_logdet(a)
+    res = M.mdet_logdet_device(view, block_size=128, overwrite=False)
+    assert rel(res.logabsdet, o.logabsdet) <= TOL["f64"]
+    assert torch.equal(view, before)
+    res = M.mdet_logdet_device(view, block_size=128, overwrite=True)   # misaligned ld: works on a copy
+    assert rel(res.logabsdet, o.logabsdet) <= TOL["f64"]
+
+
+def test_upper_triangle_is_never_read(M):
+    n = 300
+    a = W.scaled_down(W.config(1), n).dense()
+    o = oracle.ldlt_logdet(a)
+    b = np.tril(a) + np.triu(np.full((n, n), np.nan), 1)
+    res, _ = run_device(M, b, 128)
+    assert res.status == 0 and rel(res.logabsdet, o.logabsdet) <= TOL["f64"]
+
+
+def test_block_size_invariance_and_lookahead_bit_identity(M):
+    w = W.scaled_down(W.config(2), 2048, 256)
+    a = w.dense()
+    o = oracle.ldlt_logdet(a)
+    vals = []
+    for bs in (64, 128, 256, 512, 1024, 2048):
+        res, _ = run_device(M, a, bs)
+        assert rel(res.logabsdet, o.logabsdet) <= TOL["f64"]
+        vals.append(res.logabsdet)
+    assert max(vals) - min(vals) <= 1e-10 * abs(o.logabsdet)
+    r1, d1 = run_device(M, a, 256)
+    r2, d2 = run_device(M, a, 256, flags=M.FLAG_NO_LOOKAHEAD)
+    assert r1.logabsdet == r2.logabsdet and np.array_equal(d1, d2)
+
+
+def test_flop_counter_is_tiling_independent(M):
+    n = 1000
+    a = W.scaled_down(W.config(1), n).dense()
+    for bs in (64, 192, 512, 1024):
+        res, _ = run_device(M, a, bs)
+        assert res.flops == pytest.approx(2 * (n ** 3 - n) / 6, rel=1e-12)
+    # leading term of App. E.1's total m^3/6 - m^2/4 + m/12
+    assert M.mdet_paper_fma_count(n) == pytest.approx((n ** 3 - n) / 6, rel=2.0 / n)
+
+
+def test_indefinite_matrix_sign_and_negative_count(M):
+    rng = np.random.default_rng(42)
+    n = 500
+    g = rng.standard_normal((n, n))
+    a = g + g.T + np.diag(rng.choice([-40.0, 40.0], n))     # strongly indefinite, safe minors
+    o = oracle.ldlt_logdet(a)
+    res, _ = run_device(M, a, 128)
+    assert o.negative_pivots > 50
+    assert (res.sign, res.negative_pivots) == (o.sign, o.negative_pivots)
+    assert rel(res.logabsdet, o.logabsdet) <= TOL["f64"]
+
+
+def test_scaling_identity_on_gpu(M):
+    n = 600
+    a = W.scaled_down(W.config(1), n).dense()
+    base, _ = run_device(M, a, 128)
+    for c in (1e-30, 1e25):
+        res, _ = run_device(M, c * a, 128)
+        assert rel(res.logabsdet, n * math.log(c) + base.logabsdet) <= TOL["f64"]
+
+
+def test_singular_and_nonfinite_inputs_are_reported(M):
+    # Sec. 2.1 example: the stored Gram matrix [[1,1],[1,1]] is exactly singular
+    a = np.array([[1.0, 1.0], [1.0, 1.0]])
+    res = M.mdet_logdet_device(dev(a), block_size=64)
+    assert res.status == M.Status.ESINGULAR and res.sign == 0
+    assert res.logabsdet == -math.inf and res.bad_pivot_index == 1
+    n = 200
+    a = W.scaled_down(W.config(1), n).dense()
+    a[150, 150] = np.nan
+    res = M.mdet_logdet_device(dev(a), block_size=64)
+    assert res.status == M.Status.ENONFINITE and res.bad_pivot_index == 150
+    # a zero block later in the matrix: singular at its first column
+    a = np.eye(300)
+    a[170:, 170:] = 0.0
+    res = M.mdet_logdet_device(dev(a), block_size=128)
+    assert res.status == M.Status.ESINGULAR and res.bad_pivot_index == 170
+
+
+def test_budget_is_enforced_for_device_copy(M):
+    n = 512
+    a = dev(W.config(1).dense())
+    with pytest.raises(M.MemdetError) as ei:
+        M.mdet_logdet_device(a, block_size=128, overwrite=False, mem_budget=1 << 20)
+    assert ei.value.status == M.Status.EBUDGET
+    res = M.mdet_logdet_device(a, block_size=128, overwrite=True, mem_budget=1 << 20)
+    assert res.status == 0 and res.dev_bytes_high_water <= (1 << 20)

@@ -233,11 +233,23 @@ def kms(n: int, rho: float, dtype: str = "f64", block_size: int = 128,
 
 
 def scaled_down(w: Workload, n: int, block_size: Optional[int] = None) -> Workload:
-    """Same construction at a smaller order (keeps p/n, the budget/size ratio)."""
+    """Same construction at a smaller order.
+
+    Keeps p/n and the budget/size ratio.  For Gram matrices the shift is scaled
+    with the diagonal (mean_k k^(-2 decay) / p grows when p shrinks), so the ratio
+    of the trailing pivots to the matrix entries -- what decides how many digits
+    any double-precision factorisation can deliver -- stays that of the full-size
+    configuration.
+    """
     ratio = n / w.n
     p = max(1, int(round(w.p * ratio))) if w.p else 0
     budget = int(w.mem_budget * ratio * ratio) if w.mem_budget else 0
+    shift = w.shift
+    if w.kind == "gram" and w.p:
+        def diag_scale(q):
+            return float(np.sum(np.arange(1, q + 1, dtype=np.float64) ** (-2.0 * w.decay))) / q
+        shift = w.shift * diag_scale(p) / diag_scale(w.p)
     return Workload(f"{w.name}_scaled_n{n}", w.kind, n, w.dtype,
                     block_size or max(16, int(w.block_size * ratio)), seed=w.seed,
-                    p=p, decay=w.decay, shift=w.shift, dim=w.dim, ell=w.ell,
+                    p=p, decay=w.decay, shift=shift, dim=w.dim, ell=w.ell,
                     rho=w.rho, mem_budget=budget)
