@@ -25,63 +25,117 @@ struct DevFlags {
   unsigned long long bad_kind;    // 1 = zero, 2 = non-finite (kind of *some* bad pivot; refined on host)
 };
 
-__device__ __forceinline__ double lane_bcast(double v, int src) {
-  int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
-  int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
-  return __hiloint2double(hi, lo);
-}
-__device__ __forceinline__ float lane_bcast(float v, int src) {
-  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src));
-}
-
-// Coalesced copy of a rows x cols tile (<= 64 x 64) between global memory and an
-// LDS array with row stride LEAF_PAD.  Missing rows/columns read as `fill`
-// (diagonal entries of the padding read as 1 when unit_pad is set).
-template <typename T, int NTHREADS>
-__device__ __forceinline__ void tile_to_lds(T* lds, const T* g, int64_t ld, int rows, int cols,
-                                            bool unit_pad, int tid) {
-  for (int e = tid; e < LEAF * LEAF; e += NTHREADS) {
-    int r = e >> 6, c = e & 63;
-    T v = (r < rows && c < cols) ? g[(int64_t)r * ld + c] : ((unit_pad && r == c) ? T(1) : T(0));
-    lds[r * LEAF_PAD + c] = v;
+// Coalesced copy of a rows x cols tile (<= 64 x 64) from global memory into an LDS
+// array with row stride `stride`, by one wavefront.  Missing rows/columns read as 0
+// (diagonal entries of the padding as 1 when unit_pad is set).  With transpose the
+// element (r, c) lands at lds[c * stride + r].  Loads are issued in batches of 16
+// independent requests so that their latencies overlap.
+template <typename T, bool TRANSPOSE, bool STRICT_LOWER>
+__device__ __forceinline__ void tile_to_lds(T* lds, int stride, const T* g, int64_t ld, int rows,
+                                            int cols, bool unit_pad, int lane) {
+  constexpr int BATCH = 16;
+#pragma unroll 1
+  for (int e0 = 0; e0 < LEAF * LEAF; e0 += 64 * BATCH) {
+    T v[BATCH];
+#pragma unroll
+    for (int q = 0; q < BATCH; ++q) {
+      const int e = e0 + q * 64 + lane;
+      const int r = e >> 6, c = e & 63;
+      const bool in = r < rows && c < cols && (!STRICT_LOWER || c < r);
+      v[q] = in ? g[(int64_t)r * ld + c] : ((unit_pad && r == c) ? T(1) : T(0));
+    }
+#pragma unroll
+    for (int q = 0; q < BATCH; ++q) {
+      const int e = e0 + q * 64 + lane;
+      const int r = e >> 6, c = e & 63;
+      lds[TRANSPOSE ? c * stride + r : r * stride + c] = v[q];
+    }
   }
 }
 
-// One wavefront factors one leaf.  Lane i holds row i (64 registers); the pivot
-// column is broadcast lane by lane with v_readlane, so no barrier is needed.
+// One wavefront factors one leaf.  Lane i holds row i (64 registers).  At step j
+// every lane publishes its entry of the pivot column through a 64-element LDS
+// line; the pivot and the other lanes' entries come back as broadcast reads, and
+// the rank-1 update of the remaining columns is 63-j independent multiply-adds.
+// The steps are spelled out with templates so that every register index is a
+// compile-time constant.
+// a[c] -= lj * cj[c] for c in [C0, LEAF), eight columns per stage; the LDS reads of
+// the next stage are issued before the products of the current one.
+template <typename T, int C0>
+__device__ __forceinline__ void leaf_fetch(T (&v)[8], const T* cj) {
+#pragma unroll
+  for (int q = 0; q < 8; ++q)
+    if (C0 + q < LEAF) v[q] = cj[C0 + q];
+}
+template <typename T, int C0>
+__device__ __forceinline__ void leaf_rank1(T (&a)[LEAF], const T lj, const T* cj, T (&cur)[8]) {
+  if constexpr (C0 < LEAF) {
+    T nxt[8];
+    leaf_fetch<T, C0 + 8>(nxt, cj);
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+      if (C0 + q < LEAF) a[C0 + q] -= lj * cur[q];   // a_ic -= l_ij d_j l_cj
+    // stage boundary: nothing moves across it, so at most two stages of the pivot
+    // column are in registers at any time
+    __builtin_amdgcn_sched_barrier(0);
+    leaf_rank1<T, C0 + 8>(a, lj, cj, nxt);
+  }
+}
+
+template <typename T, int J>
+__device__ __forceinline__ void leaf_step(T (&a)[LEAF], T (*col)[LEAF], T* dsave, T* rsave,
+                                          const int lane) {
+  if constexpr (J < LEAF) {
+    const T wj = a[J];                         // lane i > J: unscaled w_iJ = l_iJ d_J
+    T* cj = col[J & 1];
+    cj[lane] = wj;
+    __syncthreads();
+    const T dj = cj[J];                        // pivot d_J (uniform)
+    const T rj = T(1) / dj;
+    const T lj = wj * rj;
+    dsave[J] = dj;                             // same value from every lane
+    rsave[J] = rj;
+    {
+      T first[8];
+      leaf_fetch<T, J + 1>(first, cj);
+      leaf_rank1<T, J + 1>(a, lj, cj, first);
+    }
+    a[J] = lane > J ? lj : a[J];
+    leaf_step<T, J + 1>(a, col, dsave, rsave, lane);
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(64) void leaf_factor_kernel(T* __restrict__ A, int64_t ld, int w,
                                                          T* __restrict__ dvec,
                                                          T* __restrict__ dinv,
                                                          long long pivot0, DevFlags* flags) {
   __shared__ T tile[LEAF * LEAF_PAD];
+  __shared__ __attribute__((aligned(16))) T col[2][LEAF];
+  __shared__ T dsave[LEAF], rsave[LEAF];
   const int lane = threadIdx.x;
-  tile_to_lds<T, 64>(tile, A, ld, w, w, true, lane);
+  tile_to_lds<T, false, false>(tile, LEAF_PAD, A, ld, w, w, true, lane);
   __syncthreads();
   T a[LEAF];
 #pragma unroll
   for (int j = 0; j < LEAF; ++j) a[j] = tile[lane * LEAF_PAD + j];
 
-  int bad_at = -1, bad_kind = 0;
-#pragma unroll
-  for (int j = 0; j < LEAF; ++j) {
-    const T dj = lane_bcast(a[j], j);          // pivot d_j (uniform)
-    if (bad_at < 0 && j < w) {
-      if (dj == T(0)) { bad_at = j; bad_kind = 1; }
-      else if (!(fabs((double)dj) <= 1.7976931348623157e308)) { bad_at = j; bad_kind = 2; }
+  leaf_step<T, 0>(a, col, dsave, rsave, lane);
+  __syncthreads();
+
+  // pivots out; first zero / non-finite pivot reported through the flags
+  const T myd = dsave[lane];
+  const bool zero = myd == T(0);
+  const bool bad = lane < w && (zero || !(fabs((double)myd) <= 1.7976931348623157e308));
+  if (lane < w) { dvec[lane] = myd; dinv[lane] = rsave[lane]; }
+  const unsigned long long mask = __ballot(bad);
+  if (mask != 0ull) {
+    const int first = __ffsll((long long)mask) - 1;
+    if (lane == first) {
+      unsigned long long idx = (unsigned long long)(pivot0 + first);
+      unsigned long long old = atomicMin(&flags->first_bad, idx);
+      if (idx <= old) atomicExch(&flags->bad_kind, zero ? 1ull : 2ull);
     }
-    const T rj = T(1) / dj;
-    const T wj = a[j];                         // lane i > j: unscaled w_ij = l_ij d_j
-    const T lj = wj * rj;
-    if (lane == j && j < w) { dvec[j] = dj; dinv[j] = rj; }
-#pragma unroll
-    for (int c = j + 1; c < LEAF; ++c) a[c] -= lj * lane_bcast(wj, c);   // a_ic -= l_ij d_j l_cj
-    if (lane > j) a[j] = lj;
-  }
-  if (bad_at >= 0 && lane == 0) {
-    unsigned long long idx = (unsigned long long)(pivot0 + bad_at);
-    unsigned long long old = atomicMin(&flags->first_bad, idx);
-    if (idx <= old) atomicExch(&flags->bad_kind, (unsigned long long)bad_kind);
   }
   // write back the lower triangle (L below the diagonal, D on it)
 #pragma unroll
@@ -93,50 +147,48 @@ __global__ __launch_bounds__(64) void leaf_factor_kernel(T* __restrict__ A, int6
   }
 }
 
-// Rows below a factored leaf.  Each wavefront takes 64 rows; lane = row.
-// X (m x w, in place) <- X L^-T D^-1 by forward substitution along the row:
-//    w_j = x_j - sum_{p<j} w_p L[j][p] ;  l_j = w_j / d_j  (as w_j * dinv_j).
-constexpr int SOLVE_WAVES = 2;
+// Rows below a factored leaf.  One wavefront per workgroup takes 64 rows; lane = row.
+// X (m x w, in place) <- X L^-T D^-1 by forward substitution along the row,
+//    w_j = x_j - sum_{p<j} w_p L[j][p] ;  l_j = w_j / d_j  (as w_j * dinv_j),
+// arranged column by column (once w_p is final it is subtracted from every later
+// entry), so the multiply-adds of one step are independent while each entry still
+// receives its terms in the order p = 0, 1, 2, ...  L is kept transposed in LDS and
+// read as broadcasts.
+constexpr int LT_STRIDE = LEAF + 2;   // even: rows stay 16-byte aligned
 
 template <typename T>
-__global__ __launch_bounds__(64 * SOLVE_WAVES) void leaf_solve_kernel(
+__global__ __launch_bounds__(64) void leaf_solve_kernel(
     T* __restrict__ X, int64_t ld, int m, int w, const T* __restrict__ Lleaf, int64_t ldl,
     const T* __restrict__ dinv) {
-  __shared__ T Ls[LEAF * LEAF];
+  __shared__ __attribute__((aligned(16))) T Lt[LEAF * LT_STRIDE];   // Lt[p][j] = L[j][p], j > p
   __shared__ T rinv[LEAF];
-  __shared__ T stage[SOLVE_WAVES][LEAF * LEAF_PAD];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  __shared__ T stage[LEAF * LEAF_PAD];
+  const int lane = threadIdx.x;
 
-  for (int e = tid; e < LEAF * LEAF; e += 64 * SOLVE_WAVES) {
-    int r = e >> 6, c = e & 63;
-    Ls[e] = (r < w && c < r) ? Lleaf[(int64_t)r * ldl + c] : T(0);
-  }
-  if (tid < LEAF) rinv[tid] = tid < w ? dinv[tid] : T(0);
+  tile_to_lds<T, true, true>(Lt, LT_STRIDE, Lleaf, ldl, w, w, false, lane);
+  rinv[lane] = lane < w ? dinv[lane] : T(0);
 
-  const int64_t r0 = ((int64_t)blockIdx.x * SOLVE_WAVES + wave) * LEAF;
+  const int64_t r0 = (int64_t)blockIdx.x * LEAF;
   int rows = m - r0 < LEAF ? (int)(m - r0) : LEAF;
-  if (rows < 0) rows = 0;
-  T* st = stage[wave];
   T* Xw = X + r0 * ld;
-  tile_to_lds<T, 64>(st, Xw, ld, rows, w, false, lane);
+  tile_to_lds<T, false, false>(stage, LEAF_PAD, Xw, ld, rows, w, false, lane);
   __syncthreads();
 
   T x[LEAF];
 #pragma unroll
-  for (int j = 0; j < LEAF; ++j) x[j] = st[lane * LEAF_PAD + j];
+  for (int j = 0; j < LEAF; ++j) x[j] = stage[lane * LEAF_PAD + j];
 #pragma unroll
-  for (int j = 1; j < LEAF; ++j) {
-    T s = x[j];
+  for (int p = 0; p < LEAF - 1; ++p) {
+    const T xp = x[p];
 #pragma unroll
-    for (int p = 0; p < j; ++p) s -= x[p] * Ls[j * LEAF + p];
-    x[j] = s;
+    for (int j = p + 1; j < LEAF; ++j) x[j] -= xp * Lt[p * LT_STRIDE + j];
   }
 #pragma unroll
-  for (int j = 0; j < LEAF; ++j) st[lane * LEAF_PAD + j] = x[j] * rinv[j];
+  for (int j = 0; j < LEAF; ++j) stage[lane * LEAF_PAD + j] = x[j] * rinv[j];
   __syncthreads();
   for (int e = lane; e < LEAF * LEAF; e += 64) {
     int r = e >> 6, c = e & 63;
-    if (r < rows && c < w) Xw[(int64_t)r * ld + c] = st[r * LEAF_PAD + c];
+    if (r < rows && c < w) Xw[(int64_t)r * ld + c] = stage[r * LEAF_PAD + c];
   }
 }
 

@@ -139,8 +139,8 @@ struct Launcher {
       int64_t below = m - w;
       if (below > 0) {
         if (below > INT32_MAX) return MDET_EINVAL;
-        int64_t nblk = (below + LEAF * SOLVE_WAVES - 1) / (LEAF * SOLVE_WAVES);
-        hipLaunchKernelGGL((leaf_solve_kernel<T>), dim3((unsigned)nblk), dim3(64 * SOLVE_WAVES), 0,
+        int64_t nblk = (below + LEAF - 1) / LEAF;
+        hipLaunchKernelGGL((leaf_solve_kernel<T>), dim3((unsigned)nblk), dim3(64), 0,
                            st, P + w * ld, ld, (int)below, (int)w, (const T*)P, ld,
                            (const T*)(dinv + d0));
         fail->check(hipGetLastError());
