@@ -17,6 +17,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <functional>
 #include <mutex>
 #include <vector>
 
@@ -190,18 +191,30 @@ struct ColRef {
 // cols[j] for j in [jb, je) must be resident and hold columns already updated by
 // every block column < jb.  `dense`: all columns live in one row-major array, so
 // the bulk of a trailing update can be a single launch.
+// Hooks let the out-of-core driver wait for a column's upload before its first use
+// on a stream and start its write-back as soon as it is final.
+struct ResidentHooks {
+  std::function<void(hipStream_t, int64_t)> before_touch;   // (stream, column)
+  std::function<void(int64_t)> column_final;                // column k factored (on s0)
+};
+
 template <typename T>
 static int factor_resident(Launcher<T>& L, const Plan& pl, std::vector<ColRef<T>>& cols, int64_t jb,
                            int64_t je, bool dense, bool lookahead, hipStream_t s0, hipStream_t s1,
-                           EventPool& events) {
+                           EventPool& events, const ResidentHooks* hooks = nullptr) {
   const int64_t bs = pl.bs, n = pl.n;
   hipEvent_t ev_bulk_prev = nullptr;
   if (!lookahead) s1 = s0;
+  auto touch = [&](hipStream_t st, int64_t j) {
+    if (hooks && hooks->before_touch) hooks->before_touch(st, j);
+  };
   for (int64_t k = jb; k < je; ++k) {
     const int64_t wk = pl.col_width(k);
     const int64_t mk = n - k * bs;
+    touch(s0, k);
     int rc = L.factor_cols(s0, cols[k].base, cols[k].ld, mk, wk, k * bs);
     if (rc != MDET_OK) return rc;
+    if (hooks && hooks->column_final) hooks->column_final(k);
     if (k + 1 >= je) break;
     hipEvent_t ev_panel = nullptr;
     if (lookahead && k + 2 < je) {
@@ -212,6 +225,7 @@ static int factor_resident(Launcher<T>& L, const Plan& pl, std::vector<ColRef<T>
     if (lookahead && ev_bulk_prev) L.fail->check(hipStreamWaitEvent(s0, ev_bulk_prev, 0));
     {
       const int64_t j = k + 1;
+      touch(s0, j);
       const T* A = cols[k].base + (j - k) * bs * cols[k].ld;
       rc = L.update(s0, cols[j].base, cols[j].ld, A, cols[k].ld, A, cols[k].ld, L.dvec + k * bs,
                     n - j * bs, pl.col_width(j), wk, true);
@@ -229,6 +243,7 @@ static int factor_resident(Launcher<T>& L, const Plan& pl, std::vector<ColRef<T>
         if (rc != MDET_OK) return rc;
       } else {
         for (int64_t j = k + 2; j < je; ++j) {
+          touch(s1, j);
           const T* A = cols[k].base + (j - k) * bs * cols[k].ld;
           rc = L.update(s1, cols[j].base, cols[j].ld, A, cols[k].ld, A, cols[k].ld,
                         L.dvec + k * bs, n - j * bs, pl.col_width(j), wk, true);
@@ -393,6 +408,280 @@ static int logdet_device_t(const mdet_params& p, const Plan& pl, T* dA, int64_t 
   return finish_result(o, res);
 }
 
+
+// ---------------------------------------------------------------------------
+// mdet_logdet_host: packed lower block-column layout in host memory
+// ---------------------------------------------------------------------------
+// Copy of rows [r0, r1) of block column j between the host layout (leading
+// dimension w_j) and its device image (leading dimension col_ld(j)).
+template <typename T>
+static void copy_col_rows(HipFail& fail, const Plan& pl, int64_t j, int64_t r0, int64_t r1, T* dev_col,
+                          T* host_col, bool to_device, hipStream_t st, uint64_t* bytes) {
+  if (r1 <= r0) return;
+  const int64_t w = pl.col_width(j), ldd = pl.col_ld(j);
+  T* d = dev_col + (r0 - j * pl.bs) * ldd;
+  T* h = host_col + (r0 - j * pl.bs) * w;
+  const size_t nbytes = (size_t)(r1 - r0) * w * sizeof(T);
+  if (ldd == w) {
+    fail.check(to_device ? hipMemcpyAsync(d, h, nbytes, hipMemcpyHostToDevice, st)
+                         : hipMemcpyAsync(h, d, nbytes, hipMemcpyDeviceToHost, st));
+  } else {
+    fail.check(to_device ? hipMemcpy2DAsync(d, ldd * sizeof(T), h, w * sizeof(T), w * sizeof(T),
+                                            (size_t)(r1 - r0), hipMemcpyHostToDevice, st)
+                         : hipMemcpy2DAsync(h, w * sizeof(T), d, ldd * sizeof(T), w * sizeof(T),
+                                            (size_t)(r1 - r0), hipMemcpyDeviceToHost, st));
+  }
+  *bytes += nbytes;
+}
+
+template <typename T>
+static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, mdet_result* res,
+                         T* diag_host) {
+  HipFail fail;
+  int dev = 0;
+  MDET_HIP(fail, hipGetDevice(&dev));
+  StreamSet* ss = nullptr;
+  MDET_HIP(fail, get_streams(dev, &ss));
+  if (!fail.ok()) { res->hip_error = fail.code; return MDET_EHIP; }
+
+  Workspace ws;
+  int rc = ws.acquire(p, pl.dev_bytes, fail);
+  if (rc != MDET_OK) { res->hip_error = fail.code; return rc; }
+  res->dev_bytes_high_water = pl.dev_bytes;
+
+  const SmallArea sa = small_area(pl.n, pl.T, pl.beta);
+  Launcher<T> L;
+  L.fail = &fail;
+  bind_small(L, ws.base, sa);
+  double* partial = (double*)(ws.base + sa.partial);
+  double* out = (double*)(ws.base + sa.out);
+  double* running = (double*)(ws.base + sa.running);
+  char* arena = ws.base + sa.total;
+
+  EventPool events(&fail);
+  hipStream_t s0 = ss->main, s1 = ss->side, sh = ss->h2d, sd = ss->d2h;
+  hipEvent_t ev_in = events.get();
+  MDET_HIP(fail, hipEventRecord(ev_in, (hipStream_t)p.stream));
+  MDET_HIP(fail, hipStreamWaitEvent(s0, ev_in, 0));
+  MDET_HIP(fail, hipStreamWaitEvent(sh, ev_in, 0));
+  reset_flags(L, s0);
+
+  const bool lookahead = !(p.flags & MDET_FLAG_NO_LOOKAHEAD);
+  const int64_t bs = pl.bs, n = pl.n, T_ = pl.T;
+  std::vector<ColRef<T>> cols((size_t)T_, ColRef<T>{nullptr, 0});
+  uint64_t h2d_bytes = 0, d2h_bytes = 0;
+  auto host_col = [&](T* base, int64_t j) { return base + pl.col_offset(j); };
+
+  if (!pl.out_of_core) {
+    // ---- everything resident: upload column by column, factor as columns arrive
+    uint64_t off = 0;
+    std::vector<hipEvent_t> ready((size_t)T_, nullptr);
+    for (int64_t j = 0; j < T_; ++j) {
+      cols[j] = {(T*)(arena + off), pl.col_ld(j)};
+      off += align256(pl.dev_col_bytes(j));
+      copy_col_rows(fail, pl, j, j * bs, n, cols[j].base, host_col(hA, j), true, sh, &h2d_bytes);
+      ready[j] = events.get();
+      MDET_HIP(fail, hipEventRecord(ready[j], sh));
+    }
+    std::vector<char> seen0((size_t)T_, 0), seen1((size_t)T_, 0);
+    ResidentHooks hooks;
+    hooks.before_touch = [&](hipStream_t st, int64_t j) {
+      std::vector<char>& seen = (st == s0) ? seen0 : seen1;
+      if (!seen[j]) { seen[j] = 1; fail.check(hipStreamWaitEvent(st, ready[j], 0)); }
+    };
+    rc = factor_resident(L, pl, cols, 0, T_, false, lookahead, s0, s1, events, &hooks);
+  } else {
+    // ---- out-of-core: resident groups of block columns, factored columns stream past
+    const uint64_t tile_al = align256(pl.tile_bytes);
+    hipEvent_t ev_arena_free = nullptr;   // previous group: compute finished and columns saved
+    std::vector<hipEvent_t> saved;        // write-back completion of the previous group
+    for (size_t g = 0; g < pl.panels.size() && rc == MDET_OK; ++g) {
+      const int64_t j0 = pl.panels[g].j0, j1 = pl.panels[g].j1;
+      const int64_t wc = j1 - j0;
+      // -- carve the arena
+      uint64_t off = 0;
+      for (int64_t j = j0; j < j1; ++j) {
+        cols[j] = {(T*)(arena + off), pl.col_ld(j)};
+        off += align256(pl.dev_col_bytes(j));
+      }
+      T* bpool[2] = {nullptr, nullptr};
+      std::vector<T*> ring;
+      if (j0 > 0) {
+        for (int q = 0; q < 2; ++q) { bpool[q] = (T*)(arena + off); off += (uint64_t)wc * tile_al; }
+        for (uint64_t q = 0; q < pl.ring_tiles; ++q) { ring.push_back((T*)(arena + off)); off += tile_al; }
+      }
+      // -- the arena may be reused once the previous group is saved and idle
+      if (ev_arena_free) MDET_HIP(fail, hipStreamWaitEvent(sh, ev_arena_free, 0));
+      for (hipEvent_t e : saved) MDET_HIP(fail, hipStreamWaitEvent(sh, e, 0));
+      saved.clear();
+
+      const int64_t rows_end_J = (j1 < T_) ? j1 * bs : n;   // first row below the group's own rows
+      if (j0 == 0) {
+        // first group: nothing to stream; upload column by column and factor as they arrive
+        std::vector<hipEvent_t> ready((size_t)T_, nullptr);
+        for (int64_t j = j0; j < j1; ++j) {
+          copy_col_rows(fail, pl, j, j * bs, n, cols[j].base, host_col(hA, j), true, sh, &h2d_bytes);
+          ready[j] = events.get();
+          MDET_HIP(fail, hipEventRecord(ready[j], sh));
+        }
+        std::vector<char> seen0((size_t)T_, 0), seen1((size_t)T_, 0);
+        ResidentHooks hooks;
+        hooks.before_touch = [&](hipStream_t st, int64_t j) {
+          std::vector<char>& seen = (st == s0) ? seen0 : seen1;
+          if (!seen[j]) { seen[j] = 1; fail.check(hipStreamWaitEvent(st, ready[j], 0)); }
+        };
+        hooks.column_final = [&](int64_t k) {
+          hipEvent_t fin = events.get();
+          fail.check(hipEventRecord(fin, s0));
+          fail.check(hipStreamWaitEvent(sd, fin, 0));
+          copy_col_rows(fail, pl, k, k * bs, n, cols[k].base, host_col(hOut, k), false, sd, &d2h_bytes);
+          hipEvent_t sv = events.get();
+          fail.check(hipEventRecord(sv, sd));
+          saved.push_back(sv);
+        };
+        if (j1 == T_) hooks.column_final = nullptr;   // single group: nothing streams it again
+        rc = factor_resident(L, pl, cols, j0, j1, false, lookahead, s0, s1, events, &hooks);
+      } else {
+        // The group's original blocks are uploaded one block row at a time, each just
+        // ahead of the first streamed block that needs it (uploads share one stream, so
+        // issue order is arrival order).
+        std::vector<hipEvent_t> row_ready((size_t)T_, nullptr);
+        auto upload_row = [&](int64_t i) {
+          const int64_t r0 = i * bs, r1 = (i + 1) * bs < n ? (i + 1) * bs : n;
+          for (int64_t j = j0; j < j1 && j <= i; ++j)
+            copy_col_rows(fail, pl, j, r0, r1, cols[j].base, host_col(hA, j), true, sh, &h2d_bytes);
+          row_ready[i] = events.get();
+          MDET_HIP(fail, hipEventRecord(row_ready[i], sh));
+        };
+        std::vector<hipEvent_t> slot_ready(ring.size(), nullptr), slot_free(ring.size(), nullptr);
+        hipEvent_t b_ready[2] = {nullptr, nullptr}, b_free[2] = {nullptr, nullptr};
+        size_t slot_next = 0;
+        for (int64_t k = 0; k < j0 && rc == MDET_OK; ++k) {
+          const int q = (int)(k & 1);
+          T* hk = host_col(hOut, k);          // factored column k (bs wide, ld = bs)
+          const T* dk = L.dvec + k * bs;
+          // operands for the group's own rows: rows [j0*bs, rows_end_J) of column k
+          if (b_free[q]) MDET_HIP(fail, hipStreamWaitEvent(sh, b_free[q], 0));
+          if (k == 0)
+            for (int64_t i = j0; i < j1; ++i) upload_row(i);
+          {
+            const size_t nbytes = (size_t)(rows_end_J - j0 * bs) * bs * sizeof(T);
+            MDET_HIP(fail, hipMemcpyAsync(bpool[q], hk + (j0 - k) * bs * bs, nbytes, hipMemcpyHostToDevice, sh));
+            h2d_bytes += nbytes;
+          }
+          if (!b_ready[q]) b_ready[q] = events.get();
+          MDET_HIP(fail, hipEventRecord(b_ready[q], sh));
+          MDET_HIP(fail, hipStreamWaitEvent(s0, b_ready[q], 0));
+          // group rows: each target column j gets rows [j*bs, rows_end_J) in one launch
+          for (int64_t j = j0; j < j1 && rc == MDET_OK; ++j) {
+            if (k == 0)
+              for (int64_t i = j; i < j1; ++i) MDET_HIP(fail, hipStreamWaitEvent(s0, row_ready[i], 0));
+            const T* A = bpool[q] + (j - j0) * bs * bs;
+            rc = L.update(s0, cols[j].base, cols[j].ld, A, bs, A, bs, dk, rows_end_J - j * bs,
+                          pl.col_width(j), bs, true);
+          }
+          // rows below the group: one streamed block per block row
+          for (int64_t i = j1; i < T_ && rc == MDET_OK; ++i) {
+            const size_t sl = slot_next++ % ring.size();
+            const int64_t wi = pl.col_width(i);
+            if (k == 0) upload_row(i);
+            if (slot_free[sl]) MDET_HIP(fail, hipStreamWaitEvent(sh, slot_free[sl], 0));
+            const size_t nbytes = (size_t)wi * bs * sizeof(T);
+            MDET_HIP(fail, hipMemcpyAsync(ring[sl], hk + (i - k) * bs * bs, nbytes, hipMemcpyHostToDevice, sh));
+            h2d_bytes += nbytes;
+            if (!slot_ready[sl]) slot_ready[sl] = events.get();
+            MDET_HIP(fail, hipEventRecord(slot_ready[sl], sh));
+            MDET_HIP(fail, hipStreamWaitEvent(s0, slot_ready[sl], 0));
+            if (k == 0) MDET_HIP(fail, hipStreamWaitEvent(s0, row_ready[i], 0));
+            for (int64_t j = j0; j < j1 && rc == MDET_OK; ++j) {
+              T* C = cols[j].base + (i - j) * bs * cols[j].ld;
+              rc = L.update(s0, C, cols[j].ld, ring[sl], bs, bpool[q] + (j - j0) * bs * bs, bs, dk, wi,
+                            pl.col_width(j), bs, false);
+            }
+            if (!slot_free[sl]) slot_free[sl] = events.get();
+            MDET_HIP(fail, hipEventRecord(slot_free[sl], s0));
+          }
+          if (!b_free[q]) b_free[q] = events.get();
+          MDET_HIP(fail, hipEventRecord(b_free[q], s0));
+        }
+        if (rc == MDET_OK) {
+          ResidentHooks hooks;
+          hooks.column_final = [&](int64_t k) {
+            hipEvent_t fin = events.get();
+            fail.check(hipEventRecord(fin, s0));
+            fail.check(hipStreamWaitEvent(sd, fin, 0));
+            copy_col_rows(fail, pl, k, k * bs, n, cols[k].base, host_col(hOut, k), false, sd, &d2h_bytes);
+            hipEvent_t sv = events.get();
+            fail.check(hipEventRecord(sv, sd));
+            saved.push_back(sv);
+          };
+          // the last group need not be written back: nothing will stream it again
+          if (j1 == T_) hooks.column_final = nullptr;
+          rc = factor_resident(L, pl, cols, j0, j1, false, lookahead, s0, s1, events, &hooks);
+        }
+      }
+      ev_arena_free = events.get();
+      MDET_HIP(fail, hipEventRecord(ev_arena_free, s0));   // s1 was joined into s0
+    }
+  }
+
+  if (rc == MDET_OK) L.reduce(s0, n, bs, T_, partial, out, running);
+  DeviceOut o;
+  std::memset(&o, 0, sizeof(o));
+  if (rc == MDET_OK) {
+    MDET_HIP(fail, hipMemcpyAsync(o.out, out, sizeof(o.out), hipMemcpyDeviceToHost, s0));
+    MDET_HIP(fail, hipMemcpyAsync(&o.flags, L.flags, sizeof(DevFlags), hipMemcpyDeviceToHost, s0));
+    if (diag_host && n > 0)
+      MDET_HIP(fail, hipMemcpyAsync(diag_host, L.dvec, n * sizeof(T), hipMemcpyDeviceToHost, s0));
+  }
+  MDET_HIP(fail, hipStreamSynchronize(sh));
+  MDET_HIP(fail, hipStreamSynchronize(s1));
+  MDET_HIP(fail, hipStreamSynchronize(s0));
+  MDET_HIP(fail, hipStreamSynchronize(sd));
+  res->flops = 2.0 * L.fma;
+  res->kernel_launches = L.launches;
+  res->bytes_h2d = h2d_bytes;
+  res->bytes_d2h = d2h_bytes;
+  if (!fail.ok()) { res->hip_error = fail.code; return MDET_EHIP; }
+  if (rc != MDET_OK) return rc;
+  return finish_result(o, res);
+}
+
+// Pinned host buffer owned by the library.
+struct PinnedBuf {
+  void* p = nullptr;
+  int alloc(size_t bytes) {
+    hipError_t e = hipHostMalloc(&p, bytes ? bytes : 1, hipHostMallocDefault);
+    if (e != hipSuccess) { (void)hipGetLastError(); p = nullptr; return MDET_ENOMEM_HOST; }
+    return MDET_OK;
+  }
+  ~PinnedBuf() { if (p) (void)hipHostFree(p); }
+};
+
+static int logdet_host_any(const mdet_params* p, void* hA, mdet_result* res, void* diag) {
+  Plan pl;
+  int rc = make_plan(*p, false, 0, pl);
+  init_result(res, pl);
+  if (rc != MDET_OK) return rc;
+  PinnedBuf scratch;
+  void* hOut = hA;
+  if (pl.out_of_core && !p->overwrite) {
+    if (p->host_scratch) {
+      if (p->host_scratch_bytes < pl.layout_bytes) return MDET_ENOMEM_HOST;
+      hOut = p->host_scratch;
+    } else {
+      rc = scratch.alloc(pl.layout_bytes);
+      if (rc != MDET_OK) return rc;
+      hOut = scratch.p;
+    }
+  }
+  auto t0 = std::chrono::steady_clock::now();
+  if (p->dtype == MDET_F64) rc = logdet_host_t<double>(*p, pl, (double*)hA, (double*)hOut, res, (double*)diag);
+  else rc = logdet_host_t<float>(*p, pl, (float*)hA, (float*)hOut, res, (float*)diag);
+  res->t_total = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+  return rc;
+}
+
 }  // namespace mdet
 
 // ===========================================================================
@@ -552,6 +841,33 @@ int mdet_step_logdet_reduce(int32_t dtype, const void* d, int64_t n, double* out
 
 }  // extern "C"
 
-// TEMPORARY stubs (replaced by the host scheduler)
-extern "C" int mdet_logdet_host(const mdet_params*, void*, mdet_result*, void*) { return MDET_EINVAL; }
-extern "C" int mdet_logdet_provider(const mdet_params*, mdet_block_provider, void*, mdet_result*, void*) { return MDET_EINVAL; }
+extern "C" int mdet_logdet_host(const mdet_params* p, void* hA, mdet_result* res, void* diag) {
+  if (!params_ok(p) || !res) return MDET_EINVAL;
+  if (p->n > 0 && !hA) return MDET_EINVAL;
+  return logdet_host_any(p, hA, res, diag);
+}
+
+extern "C" int mdet_logdet_provider(const mdet_params* p, mdet_block_provider provider, void* user,
+                                    mdet_result* res, void* diag) {
+  if (!params_ok(p) || !res || !provider) return MDET_EINVAL;
+  Plan pl;
+  int rc = make_plan(*p, false, 0, pl);
+  init_result(res, pl);
+  if (rc != MDET_OK) return rc;
+  PinnedBuf buf;
+  rc = buf.alloc(pl.layout_bytes);
+  if (rc != MDET_OK) return rc;
+  const int64_t bs = pl.bs;
+  for (int64_t j = 0; j < pl.T; ++j) {
+    const int64_t wj = pl.col_width(j);
+    char* col = (char*)buf.p + (uint64_t)pl.col_offset(j) * pl.beta;
+    for (int64_t i = j; i < pl.T; ++i) {
+      const int64_t wi = pl.col_width(i);
+      void* dst = col + (uint64_t)(i - j) * bs * wj * pl.beta;
+      if (provider(user, i, j, wi, wj, dst, wj) != 0) return MDET_EPROVIDER;
+    }
+  }
+  mdet_params q = *p;
+  q.overwrite = 1;        // the staging buffer is ours
+  return logdet_host_any(&q, buf.p, res, diag);
+}

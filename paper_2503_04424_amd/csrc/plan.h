@@ -50,6 +50,10 @@ struct Plan {
     return off;
   }
   uint64_t col_bytes(int64_t j) const { return (uint64_t)col_rows(j) * col_width(j) * beta; }
+  // on the device a block column keeps a leading dimension that is a multiple of 4
+  // elements (16-byte rows); only a ragged last column differs from the host layout
+  int64_t col_ld(int64_t j) const { return round_up(col_width(j), 4); }
+  uint64_t dev_col_bytes(int64_t j) const { return (uint64_t)col_rows(j) * col_ld(j) * beta; }
   uint64_t block_bytes(int64_t i, int64_t k) const {   // block (i, k), i >= k
     return (uint64_t)col_width(i) * col_width(k) * beta;   // rows of block row i = w_i
   }
@@ -113,7 +117,9 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
   }
 
   const bool force_ooc = (p.flags & MDET_FLAG_FORCE_OUT_OF_CORE) != 0;
-  const uint64_t incore = pl.small_bytes + align256(pl.layout_bytes);
+  uint64_t dev_layout = 0;
+  for (int64_t j = 0; j < pl.T; ++j) dev_layout += align256(pl.dev_col_bytes(j));
+  const uint64_t incore = pl.small_bytes + dev_layout;
   if (!force_ooc && (budget == 0 || incore <= budget)) {
     pl.out_of_core = false;
     pl.dev_bytes = incore;
@@ -132,7 +138,7 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
     uint64_t resident = 0;
     int64_t j1 = j0;
     while (j1 < pl.T) {
-      uint64_t cand = resident + align256(pl.col_bytes(j1));
+      uint64_t cand = resident + align256(pl.dev_col_bytes(j1));
       uint64_t wc = (uint64_t)(j1 + 1 - j0);
       // streamed factor blocks: two sets of wc row blocks of the group's own rows
       // (operands reused by every streamed block) plus the ring

@@ -1,0 +1,181 @@
+"""GPU parity for the host entry points: packed block-column layout, in-core and
+out-of-core (streamed) runs, block provider.  Same bars as test_gpu_parity."""
+import ctypes
+import math
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+TOL = {"f64": 1e-10, "f32": 1e-4}
+
+
+def rel(a, b):
+    return abs(a - b) / max(1.0, abs(b))
+
+
+@pytest.fixture(scope="module")
+def M():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2503_04424_amd as m
+    m.load()
+    return m
+
+
+def packed(M, a, bs, pin=True):
+    return M.pack_lower_block_columns(torch.from_numpy(a), bs, pin=pin)
+
+
+def min_budget(M, n, dtype, bs):
+    """Smallest budget the planner accepts (bisection on mdet_plan)."""
+    lo, hi = 0, 1 << 40
+    while hi - lo > 4096:
+        mid = (lo + hi) // 2
+        try:
+            M.mdet_plan(n, dtype, bs, mid, flags=M.FLAG_FORCE_OUT_OF_CORE)
+            hi = mid
+        except M.MemdetError:
+            lo = mid
+    return hi
+
+
+@pytest.mark.parametrize("n,bs", [(512, 128), (1000, 256), (777, 64), (64, 64), (1, 64), (1300, 192)])
+def test_host_in_core_matches_oracle(M, n, bs):
+    a = W.scaled_down(W.config(1), n).dense()
+    o = oracle.ldlt_logdet(a, want_diag=True)
+    diag = torch.empty(n, dtype=torch.float64)
+    res = M.mdet_logdet_host(packed(M, a, bs), n, bs, diag=diag)
+    assert not res.out_of_core and res.status == 0
+    assert res.sign == o.sign and rel(res.logabsdet, o.logabsdet) <= TOL["f64"]
+    assert np.max(np.abs(diag.numpy() - o.diag) / np.abs(o.diag)) < 1e-9
+    assert res.bytes_h2d == M.mdet_plan(n, "f64", bs).host_matrix_bytes
+
+
+@pytest.mark.parametrize("cfg,n,bs", [(1, 1024, 128), (2, 1536, 256), (3, 1280, 128), (4, 1100, 192),
+                                      (5, 1024, 64), (1, 2000, 256)])
+def test_out_of_core_matches_oracle_and_in_core(M, cfg, n, bs):
+    w = W.scaled_down(W.config(cfg), n, bs)
+    a = w.dense()
+    o = oracle.ldlt_logdet(a)
+    ref = M.mdet_logdet_device(torch.from_numpy(a).cuda(), block_size=bs)
+    lo = min_budget(M, n, "f64", bs)
+    full = M.mdet_plan(n, "f64", bs).dev_bytes_needed
+    seen_groups = set()
+    for budget in (lo, (lo + full) // 2, int(lo * 1.3)):
+        h = packed(M, a, bs)
+        res = M.mdet_logdet_host(h, n, bs, mem_budget=budget, flags=M.FLAG_FORCE_OUT_OF_CORE)
+        assert res.out_of_core and res.status == 0
+        assert res.dev_bytes_high_water <= budget
+        assert res.sign == o.sign and rel(res.logabsdet, o.logabsdet) <= TOL["f64"]
+        # the streamed schedule applies the same products to every entry in the same order
+        assert rel(res.logabsdet, ref.logabsdet) <= 1e-13
+        plan = M.mdet_plan(n, "f64", bs, budget, flags=M.FLAG_FORCE_OUT_OF_CORE)
+        assert (res.bytes_h2d, res.num_superpanels) == (plan.stream_bytes_h2d, plan.num_superpanels)
+        assert res.flops == pytest.approx(2 * (n ** 3 - n) / 6, rel=1e-12)
+        seen_groups.add(res.num_superpanels)
+    assert max(seen_groups) >= 3
+
+
+def test_out_of_core_fp32_and_kms_closed_form(M):
+    n, bs = 2048, 256
+    w = W.kms(n, 0.9, dtype="f32", block_size=bs)
+    a = w.dense()
+    lo = min_budget(M, n, "f32", bs)
+    res = M.mdet_logdet_host(packed(M, a, bs), n, bs, mem_budget=int(lo * 1.5), flags=M.FLAG_FORCE_OUT_OF_CORE)
+    o = oracle.ldlt_logdet(a)
+    assert res.out_of_core and rel(res.logabsdet, o.logabsdet) <= TOL["f32"]
+    w = W.kms(n, 0.9, dtype="f64", block_size=bs)
+    a = w.dense()
+    lo = min_budget(M, n, "f64", bs)
+    res = M.mdet_logdet_host(packed(M, a, bs), n, bs, mem_budget=lo, flags=M.FLAG_FORCE_OUT_OF_CORE)
+    assert res.num_superpanels >= 4
+    assert rel(res.logabsdet, w.closed_form_logdet()) <= TOL["f64"]
+
+
+def test_overwrite_false_preserves_input_and_uses_scratch(M):
+    n, bs = 1200, 128
+    a = W.scaled_down(W.config(1), n).dense()
+    o = oracle.ldlt_logdet(a)
+    h = packed(M, a, bs)
+    keep = h.clone()
+    lo = min_budget(M, n, "f64", bs)
+    plan = M.mdet_plan(n, "f64", bs, lo, overwrite=False, flags=M.FLAG_FORCE_OUT_OF_CORE)
+    assert plan.host_bytes_needed == plan.host_matrix_bytes
+    scratch = torch.empty(plan.host_bytes_needed // 8, dtype=torch.float64, pin_memory=True)
+    res = M.mdet_logdet_host(h, n, bs, mem_budget=lo, overwrite=False, host_scratch=scratch,
+                             flags=M.FLAG_FORCE_OUT_OF_CORE)
+    assert rel(res.logabsdet, o.logabsdet) <= TOL["f64"]
+    assert torch.equal(h, keep)
+    res = M.mdet_logdet_host(h, n, bs, mem_budget=lo, overwrite=False, flags=M.FLAG_FORCE_OUT_OF_CORE)
+    assert rel(res.logabsdet, o.logabsdet) <= TOL["f64"] and torch.equal(h, keep)
+
+
+def test_pageable_host_memory_and_caller_workspace(M):
+    n, bs = 900, 128
+    a = W.scaled_down(W.config(1), n).dense()
+    o = oracle.ldlt_logdet(a)
+    lo = min_budget(M, n, "f64", bs)
+    dev_bytes, _ = M.mdet_workspace_query(n, "f64", bs, lo, flags=M.FLAG_FORCE_OUT_OF_CORE)
+    ws = torch.empty(dev_bytes, dtype=torch.uint8, device="cuda")
+    res = M.mdet_logdet_host(packed(M, a, bs, pin=False), n, bs, mem_budget=lo, workspace=ws,
+                             flags=M.FLAG_FORCE_OUT_OF_CORE)
+    assert rel(res.logabsdet, o.logabsdet) <= TOL["f64"]
+    small = torch.empty(dev_bytes // 2, dtype=torch.uint8, device="cuda")
+    with pytest.raises(M.MemdetError) as ei:
+        M.mdet_logdet_host(packed(M, a, bs), n, bs, mem_budget=lo, workspace=small,
+                           flags=M.FLAG_FORCE_OUT_OF_CORE)
+    assert ei.value.status == M.Status.ENOMEM_DEVICE
+
+
+def test_budget_below_minimum_working_set(M):
+    n, bs = 1024, 128
+    lo = min_budget(M, n, "f64", bs)
+    a = W.scaled_down(W.config(1), n).dense()
+    with pytest.raises(M.MemdetError) as ei:
+        M.mdet_logdet_host(packed(M, a, bs), n, bs, mem_budget=lo - 8192)
+    assert ei.value.status == M.Status.EBUDGET
+
+
+def test_out_of_core_reports_singular_and_negative_pivots(M):
+    n, bs = 768, 128
+    rng = np.random.default_rng(9)
+    g = rng.standard_normal((n, n))
+    a = g + g.T + np.diag(rng.choice([-50.0, 50.0], n))
+    o = oracle.ldlt_logdet(a)
+    lo = min_budget(M, n, "f64", bs)
+    res = M.mdet_logdet_host(packed(M, a, bs), n, bs, mem_budget=lo, flags=M.FLAG_FORCE_OUT_OF_CORE)
+    assert (res.sign, res.negative_pivots) == (o.sign, o.negative_pivots)
+    assert rel(res.logabsdet, o.logabsdet) <= TOL["f64"]
+    a = np.eye(n)
+    a[500:, 500:] = 0.0
+    res = M.mdet_logdet_host(packed(M, a, bs), n, bs, mem_budget=lo, flags=M.FLAG_FORCE_OUT_OF_CORE)
+    assert res.status == M.Status.ESINGULAR and res.bad_pivot_index == 500 and res.sign == 0
+
+
+def test_block_provider(M):
+    n, bs = 1000, 128
+    w = W.scaled_down(W.config(4), n, bs)
+    a = w.dense()
+    o = oracle.ldlt_logdet(a)
+    calls = []
+
+    def provider(bi, bj, rows, cols, dst, ld):
+        calls.append((bi, bj))
+        buf = (ctypes.c_double * (rows * ld)).from_address(dst)
+        view = np.frombuffer(buf, dtype=np.float64).reshape(rows, ld)
+        view[:, :cols] = a[bi * bs:bi * bs + rows, bj * bs:bj * bs + cols]
+        return 0
+
+    lo = min_budget(M, n, "f64", bs)
+    res = M.mdet_logdet_provider(provider, n, "f64", bs, mem_budget=lo * 2, flags=M.FLAG_FORCE_OUT_OF_CORE)
+    T = (n + bs - 1) // bs
+    assert len(calls) == T * (T + 1) // 2 and all(bi >= bj for bi, bj in calls)
+    assert res.out_of_core and rel(res.logabsdet, o.logabsdet) <= TOL["f64"]
+    bad = M.mdet_logdet_provider(lambda *args: 7, n, "f64", bs, raise_on_error=False)
+    assert bad.status == M.Status.EPROVIDER
