@@ -64,7 +64,7 @@ typedef struct mdet_params {
                                 factor: unit-lower L below the diagonal, D on it).
                                 0: the input is preserved (paper's overwrite=False:
                                 Schur-updated blocks go to scratch space instead).  */
-  int32_t lookahead;         /* 1 (default when 0 is passed with flags==0) ...      */
+  int32_t reserved0;         /* must be 0                                           */
   uint32_t flags;            /* MDET_FLAG_* bits                                    */
   void* stream;              /* hipStream_t to order the work after (borrowed, e.g.
                                 from PyTorch); NULL = the default stream.  The call
@@ -84,6 +84,9 @@ typedef struct mdet_params {
                                      (results are bit-identical either way)        */
 #define MDET_FLAG_FORCE_OUT_OF_CORE 2u /* host entry points: stream blocks even if the
                                      whole triangle would fit in the budget         */
+#define MDET_FLAG_PROFILE 4u      /* bracket every trailing-update launch with HIP
+                                     events on its own stream and report the sums in
+                                     result->t_trailing_update etc.                 */
 
 typedef struct mdet_result {
   double logabsdet;            /* log|det A|; -inf when sign == 0                    */
@@ -102,6 +105,10 @@ typedef struct mdet_result {
   uint64_t bytes_d2h;          /* device -> host bytes moved                         */
   uint64_t dev_bytes_high_water; /* device bytes in use at the peak (<= budget)      */
   uint64_t kernel_launches;
+  /* filled when MDET_FLAG_PROFILE is set: the Schur updates of the trailing matrix */
+  uint64_t trailing_update_launches;
+  double t_trailing_update;      /* seconds, sum of the launches' event-timed durations */
+  double trailing_update_flops;  /* 2 x multiply-adds those launches performed          */
 } mdet_result;
 
 /*
@@ -214,14 +221,15 @@ int mdet_step_schur_update(int32_t dtype, void* C, int64_t ldc, const void* A,
  * m rows and w <= m columns.  On return the top w x w block holds L (strictly
  * lower) and D (diagonal), the rows below hold L_ik = A_ik L_kk^-T D_k^-1, and
  * d[w], dinv[w] hold the pivots and their reciprocals.  flags: device pointer to
- * 4 int64 (zero it first): [0] first bad pivot index + 1 as a negative... see
- * memdet_api.hip; pass the buffer returned by the workspace helpers in tests. */
+ * two uint64, preset to all-ones: [0] receives the smallest index (pivot_index0 +
+ * column) of a zero or non-finite pivot, [1] its kind (1 zero, 2 non-finite). */
 int mdet_step_panel_factor(int32_t dtype, void* P, int64_t ld, int64_t m, int64_t w,
                            void* d, void* dinv, int64_t pivot_index0, void* flags,
                            void* stream);
 
 /* sum log|d_j|, sign and negative count of d[0..n) -> out[0] = logabsdet (double),
- * out[1] = sign (as double), out[2] = negative count (as double).  out: DEVICE. */
+ * out[1] = sign (as double), out[2] = negative count (as double).  out: DEVICE
+ * pointer to at least 8 doubles (the tail is scratch). */
 int mdet_step_logdet_reduce(int32_t dtype, const void* d, int64_t n, double* out,
                             void* stream);
 

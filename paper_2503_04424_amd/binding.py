@@ -17,6 +17,7 @@ from . import build as _build
 MDET_F32, MDET_F64 = 0, 1
 FLAG_NO_LOOKAHEAD = 1
 FLAG_FORCE_OUT_OF_CORE = 2
+FLAG_PROFILE = 4
 
 
 class Status:
@@ -42,7 +43,8 @@ class _Result(C.Structure):
         ("out_of_core", C.c_int32), ("num_superpanels", C.c_int32),
         ("flops", C.c_double), ("t_total", C.c_double), ("bytes_h2d", C.c_uint64),
         ("bytes_d2h", C.c_uint64), ("dev_bytes_high_water", C.c_uint64),
-        ("kernel_launches", C.c_uint64),
+        ("kernel_launches", C.c_uint64), ("trailing_update_launches", C.c_uint64),
+        ("t_trailing_update", C.c_double), ("trailing_update_flops", C.c_double),
     ]
 
 
@@ -140,6 +142,9 @@ class LogdetResult:
     dev_bytes_high_water: int
     kernel_launches: int
     hip_error: int = 0
+    trailing_update_launches: int = 0
+    t_trailing_update: float = 0.0
+    trailing_update_flops: float = 0.0
 
 
 @dataclass
@@ -194,7 +199,8 @@ def _result(status: int, r: _Result) -> LogdetResult:
     return LogdetResult(r.logabsdet, r.sign, status, r.bad_pivot_index, r.negative_pivots,
                         r.block_size_used, r.num_blocks, bool(r.out_of_core), r.num_superpanels,
                         r.flops, r.t_total, r.bytes_h2d, r.bytes_d2h, r.dev_bytes_high_water,
-                        r.kernel_launches, r.hip_error)
+                        r.kernel_launches, r.hip_error, r.trailing_update_launches,
+                        r.t_trailing_update, r.trailing_update_flops)
 
 
 _SOFT = (Status.OK, Status.ESINGULAR, Status.ENONFINITE)

@@ -62,7 +62,7 @@ static inline int64_t update_num_blocks(int64_t M, int64_t N, bool lower) {
 }
 
 template <typename T, bool LOWER>
-__global__ __launch_bounds__(UPD_THREADS) void schur_update_kernel(
+__device__ __forceinline__ void schur_update_body(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K,
     int nbn) {
@@ -213,6 +213,22 @@ __global__ __launch_bounds__(UPD_THREADS) void schur_update_kernel(
       }
     }
   }
+}
+
+// Two names for the same body: the update of the trailing matrix by a finished
+// block column (the bulk of all work) and the updates inside a block column's own
+// recursive factorisation.
+template <typename T, bool LOWER>
+__global__ __launch_bounds__(UPD_THREADS) void trailing_update_kernel(
+    T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
+    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nbn) {
+  schur_update_body<T, LOWER>(C, ldc, A, lda, B, ldb, d, M, N, K, nbn);
+}
+template <typename T, bool LOWER>
+__global__ __launch_bounds__(UPD_THREADS) void panel_update_kernel(
+    T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
+    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nbn) {
+  schur_update_body<T, LOWER>(C, ldc, A, lda, B, ldb, d, M, N, K, nbn);
 }
 
 }  // namespace mdet

@@ -94,12 +94,19 @@ struct Launcher {
   DevFlags* flags = nullptr;
   double fma = 0.0;
   uint64_t launches = 0;
+  // optional timing of the trailing-update launches (MDET_FLAG_PROFILE)
+  bool profile = false;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
+  double prof_fma = 0.0;
 
   static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
   // C[M x N] -= A[M x K] diag(d) B[N x K]^T ; lower: only column <= row.
+  // trailing = true marks the Schur update of the trailing matrix by a whole block
+  // column (as opposed to the updates inside a block column's own factorisation);
+  // it runs the same code under its own kernel name so profiles tell them apart.
   int update(hipStream_t st, T* C, int64_t ldc, const T* A, int64_t lda, const T* B, int64_t ldb,
-             const T* d, int64_t M, int64_t N, int64_t K, bool lower) {
+             const T* d, int64_t M, int64_t N, int64_t K, bool lower, bool trailing = false) {
     if (M <= 0 || N <= 0 || K <= 0) return MDET_OK;
     constexpr int vec = 16 / (int)sizeof(T);
     if (K % 64 != 0 || lda % vec != 0 || ldb % vec != 0 || !aligned16(A) || !aligned16(B) ||
@@ -109,20 +116,43 @@ struct Launcher {
     int64_t nblk = update_num_blocks(M, N, lower);
     if (nblk > INT32_MAX) return MDET_EINVAL;
     dim3 grid((unsigned)nblk), block(UPD_THREADS);
-    if (lower)
-      hipLaunchKernelGGL((schur_update_kernel<T, true>), grid, block, 0, st, C, ldc, A, lda, B, ldb,
-                         d, (int)M, (int)N, (int)K, (int)nbn);
-    else
-      hipLaunchKernelGGL((schur_update_kernel<T, false>), grid, block, 0, st, C, ldc, A, lda, B,
-                         ldb, d, (int)M, (int)N, (int)K, (int)nbn);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    const bool timed = profile && trailing;
+    if (timed) {
+      fail->check(hipEventCreate(&e0));
+      fail->check(hipEventCreate(&e1));
+      fail->check(hipEventRecord(e0, st));
+    }
+    if (trailing) {
+      if (lower)
+        hipLaunchKernelGGL((trailing_update_kernel<T, true>), grid, block, 0, st, C, ldc, A, lda, B,
+                           ldb, d, (int)M, (int)N, (int)K, (int)nbn);
+      else
+        hipLaunchKernelGGL((trailing_update_kernel<T, false>), grid, block, 0, st, C, ldc, A, lda, B,
+                           ldb, d, (int)M, (int)N, (int)K, (int)nbn);
+    } else {
+      if (lower)
+        hipLaunchKernelGGL((panel_update_kernel<T, true>), grid, block, 0, st, C, ldc, A, lda, B,
+                           ldb, d, (int)M, (int)N, (int)K, (int)nbn);
+      else
+        hipLaunchKernelGGL((panel_update_kernel<T, false>), grid, block, 0, st, C, ldc, A, lda, B,
+                           ldb, d, (int)M, (int)N, (int)K, (int)nbn);
+    }
     fail->check(hipGetLastError());
     ++launches;
+    double f;
     if (lower) {
       // entries (r, c), c <= r, of an M x N trapezoid whose (0,0) is on the diagonal
       double t = (double)(M < N ? M : N);
-      fma += (t * (t + 1) / 2 + (double)(M - (int64_t)t) * (double)N) * (double)K;
+      f = (t * (t + 1) / 2 + (double)(M - (int64_t)t) * (double)N) * (double)K;
     } else {
-      fma += (double)M * (double)N * (double)K;
+      f = (double)M * (double)N * (double)K;
+    }
+    fma += f;
+    if (timed) {
+      fail->check(hipEventRecord(e1, st));
+      prof_events.emplace_back(e0, e1);
+      prof_fma += f;
     }
     return MDET_OK;
   }
@@ -161,6 +191,21 @@ struct Launcher {
     rc = update(st, C, ld, A, ld, A, ld, dvec + d0, m - w1, w - w1, w1, true);
     if (rc != MDET_OK) return rc;
     return factor_cols(st, C, ld, m - w1, w - w1, d0 + w1);
+  }
+
+  // After all streams are idle: sum of the timed launches' durations (seconds).
+  void collect_profile(mdet_result* res) {
+    double ms_total = 0.0;
+    for (auto& pr : prof_events) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) ms_total += ms;
+      (void)hipEventDestroy(pr.first);
+      (void)hipEventDestroy(pr.second);
+    }
+    res->trailing_update_launches = prof_events.size();
+    res->t_trailing_update = ms_total * 1e-3;
+    res->trailing_update_flops = 2.0 * prof_fma;
+    prof_events.clear();
   }
 
   void reduce(hipStream_t st, int64_t n, int64_t bs, int64_t T_, double* partial, double* out,
@@ -228,7 +273,7 @@ static int factor_resident(Launcher<T>& L, const Plan& pl, std::vector<ColRef<T>
       touch(s0, j);
       const T* A = cols[k].base + (j - k) * bs * cols[k].ld;
       rc = L.update(s0, cols[j].base, cols[j].ld, A, cols[k].ld, A, cols[k].ld, L.dvec + k * bs,
-                    n - j * bs, pl.col_width(j), wk, true);
+                    n - j * bs, pl.col_width(j), wk, true, true);
       if (rc != MDET_OK) return rc;
     }
     if (k + 2 < je) {
@@ -239,14 +284,14 @@ static int factor_resident(Launcher<T>& L, const Plan& pl, std::vector<ColRef<T>
         // all remaining resident columns in one launch (they are contiguous in memory)
         int64_t ncols = (je < pl.T ? je * bs : n) - j * bs;
         rc = L.update(s1, cols[j].base, cols[j].ld, A, cols[k].ld, A, cols[k].ld, L.dvec + k * bs,
-                      n - j * bs, ncols, wk, true);
+                      n - j * bs, ncols, wk, true, true);
         if (rc != MDET_OK) return rc;
       } else {
         for (int64_t j = k + 2; j < je; ++j) {
           touch(s1, j);
           const T* A = cols[k].base + (j - k) * bs * cols[k].ld;
           rc = L.update(s1, cols[j].base, cols[j].ld, A, cols[k].ld, A, cols[k].ld,
-                        L.dvec + k * bs, n - j * bs, pl.col_width(j), wk, true);
+                        L.dvec + k * bs, n - j * bs, pl.col_width(j), wk, true, true);
           if (rc != MDET_OK) return rc;
         }
       }
@@ -360,6 +405,7 @@ static int logdet_device_t(const mdet_params& p, const Plan& pl, T* dA, int64_t 
   const SmallArea sa = small_area(pl.n, pl.T, pl.beta);
   Launcher<T> L;
   L.fail = &fail;
+  L.profile = (p.flags & MDET_FLAG_PROFILE) != 0;
   bind_small(L, ws.base, sa);
   double* partial = (double*)(ws.base + sa.partial);
   double* out = (double*)(ws.base + sa.out);
@@ -403,6 +449,7 @@ static int logdet_device_t(const mdet_params& p, const Plan& pl, T* dA, int64_t 
   MDET_HIP(fail, hipStreamSynchronize(s0));
   res->flops = 2.0 * L.fma;
   res->kernel_launches = L.launches;
+  L.collect_profile(res);
   if (!fail.ok()) { res->hip_error = fail.code; return MDET_EHIP; }
   if (rc != MDET_OK) return rc;
   return finish_result(o, res);
@@ -452,6 +499,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
   const SmallArea sa = small_area(pl.n, pl.T, pl.beta);
   Launcher<T> L;
   L.fail = &fail;
+  L.profile = (p.flags & MDET_FLAG_PROFILE) != 0;
   bind_small(L, ws.base, sa);
   double* partial = (double*)(ws.base + sa.partial);
   double* out = (double*)(ws.base + sa.out);
@@ -578,7 +626,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
               for (int64_t i = j; i < j1; ++i) MDET_HIP(fail, hipStreamWaitEvent(s0, row_ready[i], 0));
             const T* A = bpool[q] + (j - j0) * bs * bs;
             rc = L.update(s0, cols[j].base, cols[j].ld, A, bs, A, bs, dk, rows_end_J - j * bs,
-                          pl.col_width(j), bs, true);
+                          pl.col_width(j), bs, true, true);
           }
           // rows below the group: one streamed block per block row
           for (int64_t i = j1; i < T_ && rc == MDET_OK; ++i) {
@@ -596,7 +644,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
             for (int64_t j = j0; j < j1 && rc == MDET_OK; ++j) {
               T* C = cols[j].base + (i - j) * bs * cols[j].ld;
               rc = L.update(s0, C, cols[j].ld, ring[sl], bs, bpool[q] + (j - j0) * bs * bs, bs, dk, wi,
-                            pl.col_width(j), bs, false);
+                            pl.col_width(j), bs, false, true);
             }
             if (!slot_free[sl]) slot_free[sl] = events.get();
             MDET_HIP(fail, hipEventRecord(slot_free[sl], s0));
@@ -640,6 +688,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
   MDET_HIP(fail, hipStreamSynchronize(sd));
   res->flops = 2.0 * L.fma;
   res->kernel_launches = L.launches;
+  L.collect_profile(res);
   res->bytes_h2d = h2d_bytes;
   res->bytes_d2h = d2h_bytes;
   if (!fail.ok()) { res->hip_error = fail.code; return MDET_EHIP; }
@@ -793,11 +842,11 @@ int mdet_step_schur_update(int32_t dtype, void* C, int64_t ldc, const void* A, i
   if (dtype == MDET_F64) {
     Launcher<double> L; L.fail = &fail;
     rc = L.update((hipStream_t)stream, (double*)C, ldc, (const double*)A, lda, (const double*)B, ldb,
-                  (const double*)d, M, N, K, lower != 0);
+                  (const double*)d, M, N, K, lower != 0, true);
   } else if (dtype == MDET_F32) {
     Launcher<float> L; L.fail = &fail;
     rc = L.update((hipStream_t)stream, (float*)C, ldc, (const float*)A, lda, (const float*)B, ldb,
-                  (const float*)d, M, N, K, lower != 0);
+                  (const float*)d, M, N, K, lower != 0, true);
   } else return MDET_EINVAL;
   if (!fail.ok()) return MDET_EHIP;
   return rc;

@@ -1,0 +1,128 @@
+"""CPU-only checks: the C-ABI library loads and exports every declared symbol, and
+the host-side planner / helper logic (no GPU call is made)."""
+import math
+import os
+import re
+
+import pytest
+
+from conftest import ROOT, read_golden
+
+
+@pytest.fixture(scope="module")
+def M():
+    import paper_2503_04424_amd as m
+    if not os.path.exists(m.lib_path()):
+        from paper_2503_04424_amd import build
+        build.build()
+    m.load()
+    return m
+
+
+def test_library_exports_every_symbol_the_header_declares(M):
+    hdr = open(os.path.join(ROOT, "include", "memdet.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(mdet_[a-z_0-9]+)\s*\(", hdr))
+    declared -= {"mdet_block_provider"}
+    assert len(declared) >= 13
+    import ctypes
+    lib = ctypes.CDLL(M.lib_path())
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert set(M.binding.EXPORTS) == declared
+    assert "gfx950" in M.mdet_version()
+    assert M.mdet_strerror(M.Status.EBUDGET).startswith("memory budget")
+
+
+def test_struct_size_guard(M):
+    import ctypes as C
+    p = M.binding._Params()
+    p.struct_size = 8
+    info = M.binding._PlanInfo()
+    assert M.lib().mdet_plan(C.byref(p), 0, C.byref(info)) == M.Status.EINVAL
+
+
+def test_paper_block_rule_worked_values(M):
+    # Table of notation (App. A): m = 500 000 with n_b = 16 gives b = 31 250
+    assert 1 + (500000 - 1) // 16 == 31250
+    # r = m sqrt(beta/c): c = m^2 beta -> r = 1 -> one block
+    m, beta = 4096, 8
+    assert M.mdet_paper_block_rule(m, beta, m * m * beta) == (1, m)
+    # r <= 2/sqrt(3) -> two blocks (three b x b blocks resident)
+    c = int(m * m * beta * 0.76)
+    assert M.mdet_paper_block_rule(m, beta, c) == (2, m // 2)
+    # otherwise n_b = ceil(2 r); four blocks of order b fit the cap
+    for c in (m * m * beta // 5, m * m * beta // 50, 12345678):
+        nb, b = M.mdet_paper_block_rule(m, beta, c)
+        r = m * math.sqrt(beta / c)
+        assert nb == math.ceil(2 * r) and b == 1 + (m - 1) // nb
+        assert 4 * b * b * beta <= c * 1.02
+    # Table 1: the 500 000-order NTK was run with n_b = 32 blocks
+    nb, b = M.mdet_paper_block_rule(500000, 8, 4 * 15625 ** 2 * 8)
+    assert (nb, b) == (32, 15625)
+
+
+def test_paper_operation_count(M):
+    # App. E.1: total m^3/6 - m^2/4 + m/12 multiply-adds, independent of n_b:
+    # summing the table's per-operation counts x costs reproduces it
+    for m, nb in ((1024, 1), (1024, 4), (4096, 8), (6000, 12)):
+        info = M.mdet_plan(m, "f64", m // nb if (m // nb) % 64 == 0 else 0)
+        if info.block_size_used * info.num_blocks != m:
+            continue
+        total = info.fma_decomp + info.fma_solve + info.fma_gemm + info.fma_syrk
+        assert total == pytest.approx(M.mdet_paper_fma_count(m), rel=1e-12)
+    # Table 1 prints 41 667 TFLOP for m = 500 000 (= m^3/3, two flops per multiply-add)
+    assert 2 * M.mdet_paper_fma_count(500000) / 1e12 == pytest.approx(41667, rel=1e-4)
+
+
+def test_host_layout_offsets(M):
+    for n, b in ((1000, 256), (512, 128), (64, 64), (1, 64), (4097, 1024)):
+        T = (n + b - 1) // b
+        acc = 0
+        for j in range(T + 1):
+            assert M.mdet_host_layout_offset(n, b, j) == acc
+            if j < T:
+                acc += (n - j * b) * min(b, n - j * b)
+    assert M.mdet_host_layout_offset(1000, 100, 0) == -1      # b must be a multiple of 64
+    assert M.mdet_host_layout_offset(1000, 256, 9) == -1
+
+
+def test_plan_in_core_vs_out_of_core_and_budget(M):
+    n, b = 131072, 4096
+    full = M.mdet_plan(n, "f64", b, 0)
+    assert not full.out_of_core and full.num_blocks == 32
+    assert full.host_matrix_bytes == 8 * M.mdet_host_layout_offset(n, b, 32)
+    p = M.mdet_plan(n, "f64", b, 16 << 30)
+    assert p.out_of_core and p.dev_bytes_needed <= 16 << 30 and p.num_superpanels >= 2
+    # originals in once + every factored column streamed past every later group
+    assert p.stream_bytes_h2d > p.host_matrix_bytes and p.stream_bytes_d2h == p.host_matrix_bytes
+    # a bigger budget means fewer groups and less traffic
+    q = M.mdet_plan(n, "f64", b, 32 << 30)
+    assert q.num_superpanels < p.num_superpanels and q.stream_bytes_h2d < p.stream_bytes_h2d
+    with pytest.raises(M.MemdetError) as ei:
+        M.mdet_plan(n, "f64", b, 1 << 30)
+    assert ei.value.status == M.Status.EBUDGET
+    # configuration 5: n = 196608, b = 8192, 32 GiB
+    p5 = M.mdet_plan(196608, "f64", 8192, 32 << 30)
+    assert p5.out_of_core and p5.num_blocks == 24 and p5.dev_bytes_needed <= 32 << 30
+
+
+def test_plan_rounds_block_size_and_handles_edges(M):
+    assert M.mdet_plan(1000, "f32", 100).block_size_used == 128
+    assert M.mdet_plan(0, "f64", 64).num_blocks == 0
+    assert M.mdet_plan(1, "f64", 0).num_blocks == 1
+    with pytest.raises(M.MemdetError):
+        M.mdet_plan(-1, "f64", 64)
+    with pytest.raises(ValueError):
+        M.mdet_plan(10, "f16", 64)
+    # device input: only a small scratch unless a copy is needed
+    a = M.mdet_plan(8192, "f64", 1024, 0, overwrite=True, for_device_input=True)
+    b = M.mdet_plan(8192, "f64", 1024, 0, overwrite=False, for_device_input=True)
+    assert a.dev_bytes_needed < 1 << 20 and b.dev_bytes_needed >= 8192 * 8192 * 8
+
+
+def test_kms_golden_values_are_the_closed_form():
+    gold = read_golden("kms_closed_form.txt")
+    for key, val in gold.items():
+        n, rho = key.split("_")
+        assert float(val) == pytest.approx((int(n) - 1) * math.log1p(-float(rho) ** 2), rel=1e-15)
