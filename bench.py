@@ -58,6 +58,8 @@ def main():
     ap.add_argument("--dtype", default=None, choices=["f64", "f32"])
     ap.add_argument("--block-size", type=int, default=0)
     ap.add_argument("--n", type=int, default=0, help="override the order (scaled-down stand-in)")
+    ap.add_argument("--budget-gib", type=float, default=-1.0,
+                    help="device budget in GiB; >0 puts the matrix in pinned host memory and streams it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0, help="order of the oracle's sample block")
     args = ap.parse_args()
@@ -78,6 +80,8 @@ def main():
         w = W.scaled_down(w, args.n, args.block_size or None)
     if args.block_size:
         w.block_size = args.block_size
+    if args.budget_gib >= 0:
+        w.mem_budget = int(args.budget_gib * (1 << 30))
     n, bs = w.n, w.block_size
     out_of_core = w.mem_budget > 0
 

@@ -221,8 +221,9 @@ int mdet_step_schur_update(int32_t dtype, void* C, int64_t ldc, const void* A,
  * m rows and w <= m columns.  On return the top w x w block holds L (strictly
  * lower) and D (diagonal), the rows below hold L_ik = A_ik L_kk^-T D_k^-1, and
  * d[w], dinv[w] hold the pivots and their reciprocals.  flags: device pointer to
- * two uint64, preset to all-ones: [0] receives the smallest index (pivot_index0 +
- * column) of a zero or non-finite pivot, [1] its kind (1 zero, 2 non-finite). */
+ * 16 + 8192 bytes; the first two uint64 must be preset to all-ones: [0] receives
+ * the smallest index (pivot_index0 + column) of a zero or non-finite pivot, [1] its
+ * kind (1 zero, 2 non-finite); the remaining 8192 bytes are scratch. */
 int mdet_step_panel_factor(int32_t dtype, void* P, int64_t ld, int64_t m, int64_t w,
                            void* d, void* dinv, int64_t pivot_index0, void* flags,
                            void* stream);

@@ -8,187 +8,339 @@
 //                      blocks; App. E.1 "solve lower triangular system"; the
 //                      D^-1 is the LDL^T "diagonal scaling").
 //
-// Both keep one matrix row per lane in registers; tiles travel between HBM and
-// registers through LDS so that every global access is a coalesced 16-byte vector.
+// Both work on 16-column sub-blocks: the sequential part (elimination inside a
+// 16 x 16 diagonal sub-block) runs on the vector ALUs with one matrix row per lane,
+// everything else (updates inside the leaf, the substitution against already
+// solved sub-blocks) is 16 x 16 x 16 products on the matrix cores.  The loops over
+// sub-blocks are real loops, so the code stays small enough for the instruction
+// cache.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "mfma.h"
+
 namespace mdet {
 
 constexpr int LEAF = 64;
-constexpr int LEAF_PAD = LEAF + 1;   // LDS row stride: lane-per-row reads hit distinct banks
+constexpr int SUB = 16;               // sub-block order = MFMA tile order
+constexpr int NSUB = LEAF / SUB;
+constexpr int LEAF_PAD = LEAF + 1;    // LDS row stride of a leaf tile
+constexpr int SUB_PAD = SUB + 1;
 
 // Device-side status words shared by all kernels of one call.
 struct DevFlags {
-  unsigned long long first_bad;   // (global pivot index) of first zero/non-finite pivot; ~0ull = none
-  unsigned long long bad_kind;    // 1 = zero, 2 = non-finite (kind of *some* bad pivot; refined on host)
+  unsigned long long first_bad;   // global index of the first zero / non-finite pivot; ~0 = none
+  unsigned long long bad_kind;    // 1 = zero, 2 = non-finite
 };
 
-// Coalesced copy of a rows x cols tile (<= 64 x 64) from global memory into an LDS
-// array with row stride `stride`, by one wavefront.  Missing rows/columns read as 0
-// (diagonal entries of the padding as 1 when unit_pad is set).  With transpose the
-// element (r, c) lands at lds[c * stride + r].  Loads are issued in batches of 16
-// independent requests so that their latencies overlap.
-template <typename T, bool TRANSPOSE, bool STRICT_LOWER>
-__device__ __forceinline__ void tile_to_lds(T* lds, int stride, const T* g, int64_t ld, int rows,
-                                            int cols, bool unit_pad, int lane) {
-  constexpr int BATCH = 16;
-#pragma unroll 1
-  for (int e0 = 0; e0 < LEAF * LEAF; e0 += 64 * BATCH) {
-    T v[BATCH];
+// Value of `v` in lane `src` (uniform lane index), delivered in scalar registers:
+// a scalar operand costs an instruction or two per value, whereas a same-address
+// LDS read returns 64 copies at the LDS return rate (16 bytes per clock).
+__device__ __forceinline__ double lane_value(double v, int src) {
+  int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
+  int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
+  return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ float lane_value(float v, int src) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src));
+}
+
+// Coalesced movement of a rows x cols tile (<= 64 x 64) from global memory into an
+// LDS array with row stride `stride`, by one wavefront, in two halves of 32 rows.
+// tile_fetch issues the 32 independent loads of one half (so their latencies
+// overlap, and the loads of two different tiles can be in flight together);
+// tile_put writes them to LDS.  Missing rows/columns read as 0 (diagonal entries
+// of the padding as 1 when unit_pad is set).  With TRANSPOSE the element (r, c)
+// lands at lds[c * stride + r].
+constexpr int TILE_HALF = 32;   // rows per half = loads per lane per half
+
+template <typename T, bool STRICT_LOWER>
+__device__ __forceinline__ void tile_fetch(T (&v)[TILE_HALF], int half, const T* g, int64_t ld,
+                                           int rows, int cols, bool unit_pad, int lane) {
 #pragma unroll
-    for (int q = 0; q < BATCH; ++q) {
-      const int e = e0 + q * 64 + lane;
-      const int r = e >> 6, c = e & 63;
-      const bool in = r < rows && c < cols && (!STRICT_LOWER || c < r);
-      v[q] = in ? g[(int64_t)r * ld + c] : ((unit_pad && r == c) ? T(1) : T(0));
-    }
+  for (int q = 0; q < TILE_HALF; ++q) {
+    const int r = half * TILE_HALF + q, c = lane;
+    const bool in = r < rows && c < cols && (!STRICT_LOWER || c < r);
+    v[q] = in ? g[(int64_t)r * ld + c] : ((unit_pad && r == c) ? T(1) : T(0));
+  }
+}
+template <typename T, bool TRANSPOSE>
+__device__ __forceinline__ void tile_put(const T (&v)[TILE_HALF], int half, T* lds, int stride,
+                                         int lane) {
 #pragma unroll
-    for (int q = 0; q < BATCH; ++q) {
-      const int e = e0 + q * 64 + lane;
-      const int r = e >> 6, c = e & 63;
-      lds[TRANSPOSE ? c * stride + r : r * stride + c] = v[q];
-    }
+  for (int q = 0; q < TILE_HALF; ++q) {
+    const int r = half * TILE_HALF + q, c = lane;
+    lds[TRANSPOSE ? c * stride + r : r * stride + c] = v[q];
   }
 }
 
-// One wavefront factors one leaf.  Lane i holds row i (64 registers).  At step j
-// every lane publishes its entry of the pivot column through a 64-element LDS
-// line; the pivot and the other lanes' entries come back as broadcast reads, and
-// the rank-1 update of the remaining columns is 63-j independent multiply-adds.
-// The steps are spelled out with templates so that every register index is a
-// compile-time constant.
-// a[c] -= lj * cj[c] for c in [C0, LEAF), eight columns per stage; the LDS reads of
-// the next stage are issued before the products of the current one.
-template <typename T, int C0>
-__device__ __forceinline__ void leaf_fetch(T (&v)[8], const T* cj) {
-#pragma unroll
-  for (int q = 0; q < 8; ++q)
-    if (C0 + q < LEAF) v[q] = cj[C0 + q];
+// ---------------------------------------------------------------------------
+// leaf factor
+// ---------------------------------------------------------------------------
+// 1/d to within a couple of ulp: hardware estimate refined by two Newton steps
+// (the sequence an exact division expands to, minus its final correction and
+// range scaling; pivots that would need scaling are far outside what a
+// factorisation without pivoting can use anyway).
+__device__ __forceinline__ double fast_rcp(double d) {
+  double r = __builtin_amdgcn_rcp(d);
+  r = fma(fma(-d, r, 1.0), r, r);
+  r = fma(fma(-d, r, 1.0), r, r);
+  return r;
 }
-template <typename T, int C0>
-__device__ __forceinline__ void leaf_rank1(T (&a)[LEAF], const T lj, const T* cj, T (&cur)[8]) {
-  if constexpr (C0 < LEAF) {
-    T nxt[8];
-    leaf_fetch<T, C0 + 8>(nxt, cj);
-#pragma unroll
-    for (int q = 0; q < 8; ++q)
-      if (C0 + q < LEAF) a[C0 + q] -= lj * cur[q];   // a_ic -= l_ij d_j l_cj
-    // stage boundary: nothing moves across it, so at most two stages of the pivot
-    // column are in registers at any time
-    __builtin_amdgcn_sched_barrier(0);
-    leaf_rank1<T, C0 + 8>(a, lj, cj, nxt);
-  }
+__device__ __forceinline__ float fast_rcp(float d) {
+  float r = __builtin_amdgcn_rcpf(d);
+  r = fmaf(fmaf(-d, r, 1.0f), r, r);
+  return r;
 }
 
+// Elimination of one 16-column panel held one row per lane (a[q] = entry (lane, c0+q)).
+// Step J: lane c0+J owns the pivot; lanes below it get l = w / d and subtract
+// l * w_c from their remaining columns, w_c read from lane c0+c.  Rows above the
+// panel's diagonal block (lanes < c0) compute on unused entries.
 template <typename T, int J>
-__device__ __forceinline__ void leaf_step(T (&a)[LEAF], T (*col)[LEAF], T* dsave, T* rsave,
-                                          const int lane) {
-  if constexpr (J < LEAF) {
-    const T wj = a[J];                         // lane i > J: unscaled w_iJ = l_iJ d_J
-    T* cj = col[J & 1];
-    cj[lane] = wj;
-    __syncthreads();
-    const T dj = cj[J];                        // pivot d_J (uniform)
-    const T rj = T(1) / dj;
+__device__ __forceinline__ void panel16_step(T (&a)[SUB], const int c0, const int lane, T* dsave,
+                                             T* rsave) {
+  if constexpr (J < SUB) {
+    const T wj = a[J];
+    const T dj = lane_value(wj, c0 + J);
+    const T rj = fast_rcp(dj);
     const T lj = wj * rj;
-    dsave[J] = dj;                             // same value from every lane
-    rsave[J] = rj;
-    {
-      T first[8];
-      leaf_fetch<T, J + 1>(first, cj);
-      leaf_rank1<T, J + 1>(a, lj, cj, first);
-    }
-    a[J] = lane > J ? lj : a[J];
-    leaf_step<T, J + 1>(a, col, dsave, rsave, lane);
+    dsave[c0 + J] = dj;                        // same value from every lane
+    rsave[c0 + J] = rj;
+#pragma unroll
+    for (int c = J + 1; c < SUB; ++c) a[c] -= lj * lane_value(wj, c0 + c);   // a_ic -= l_iJ d_J l_cJ
+    a[J] = lane > c0 + J ? lj : a[J];
+    __builtin_amdgcn_sched_barrier(0);
+    panel16_step<T, J + 1>(a, c0, lane, dsave, rsave);
   }
 }
+
+// Column `col` of the inverse of the unit-lower 16 x 16 block whose row i is held
+// by lane i in a[0..i): x_i = delta_ic - sum_{k<i} L[i][k] x_k.
+template <typename T, int I>
+__device__ __forceinline__ void inv16_step(const T (&a)[SUB], T (&x)[SUB], const int col) {
+  if constexpr (I < SUB) {
+    T s = col == I ? T(1) : T(0);
+#pragma unroll
+    for (int k = 0; k < I; ++k) s -= lane_value(a[k], I) * x[k];
+    x[I] = s;
+    __builtin_amdgcn_sched_barrier(0);
+    inv16_step<T, I + 1>(a, x, col);
+  }
+}
+
+// Four wavefronts factor one leaf held in LDS, 16 columns at a time:
+//   wavefront 0: panel (rows from its diagonal down) -> registers (one row per
+//                lane), eliminated, written back;
+//   then all:    every sub-block right of / below the panel updated with 16x16x16
+//                MFMA products, shared round-robin, while the last wavefront first
+//                inverts the panel's unit-lower diagonal sub-block into `linv`
+//                (used by the solve kernel).
+constexpr int FACTOR_THREADS = 256;
 
 template <typename T>
-__global__ __launch_bounds__(64) void leaf_factor_kernel(T* __restrict__ A, int64_t ld, int w,
-                                                         T* __restrict__ dvec,
-                                                         T* __restrict__ dinv,
-                                                         long long pivot0, DevFlags* flags) {
+__global__ __launch_bounds__(FACTOR_THREADS) void leaf_factor_kernel(
+    T* __restrict__ A, int64_t ld, int w, T* __restrict__ dvec, T* __restrict__ dinv,
+    T* __restrict__ linv, long long pivot0, DevFlags* flags) {
+  using X = Mfma<T>;
+  using acc_t = typename X::acc_t;
   __shared__ T tile[LEAF * LEAF_PAD];
-  __shared__ __attribute__((aligned(16))) T col[2][LEAF];
   __shared__ T dsave[LEAF], rsave[LEAF];
-  const int lane = threadIdx.x;
-  tile_to_lds<T, false, false>(tile, LEAF_PAD, A, ld, w, w, true, lane);
-  __syncthreads();
-  T a[LEAF];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, g = lane >> 4;
+  {
+    // 64 x 64 tile, 16 entries per thread, all requests in flight together
+    T v[LEAF * LEAF / FACTOR_THREADS];
 #pragma unroll
-  for (int j = 0; j < LEAF; ++j) a[j] = tile[lane * LEAF_PAD + j];
-
-  leaf_step<T, 0>(a, col, dsave, rsave, lane);
+    for (int q = 0; q < LEAF * LEAF / FACTOR_THREADS; ++q) {
+      const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
+      v[q] = (r < w && c < w) ? A[(int64_t)r * ld + c] : (r == c ? T(1) : T(0));
+    }
+#pragma unroll
+    for (int q = 0; q < LEAF * LEAF / FACTOR_THREADS; ++q) {
+      const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
+      tile[r * LEAF_PAD + c] = v[q];
+    }
+  }
   __syncthreads();
+
+#pragma unroll 1
+  for (int b = 0; b < NSUB; ++b) {
+    const int c0 = b * SUB;
+    if (wave == 0) {
+      T a[SUB];
+#pragma unroll
+      for (int q = 0; q < SUB; ++q) a[q] = tile[lane * LEAF_PAD + c0 + q];
+      panel16_step<T, 0>(a, c0, lane, dsave, rsave);
+#pragma unroll
+      for (int q = 0; q < SUB; ++q) tile[lane * LEAF_PAD + c0 + q] = a[q];
+    }
+    __syncthreads();
+    if (wave == 3) {
+      T a[SUB], x[SUB];
+#pragma unroll
+      for (int q = 0; q < SUB; ++q) a[q] = tile[(c0 + l16) * LEAF_PAD + c0 + q];   // row l16 of L_bb
+      inv16_step<T, 0>(a, x, l16);
+      if (g == 0) {
+#pragma unroll
+        for (int i = 0; i < SUB; ++i) linv[(b * SUB + i) * SUB + l16] = x[i];
+      }
+    }
+    // trailing sub-blocks (ti, tj), b < tj <= ti:  S -= L[ti, b] D_b L[tj, b]^T
+    {
+      const int nt = NSUB - 1 - b;               // sub-block rows/columns left
+      const int ntiles = nt * (nt + 1) / 2;
+      // the inverting wavefront joins last
+      const int first = wave == 3 ? 3 : wave;
+#pragma unroll 1
+      for (int t = first; t < ntiles; t += 4) {
+        int ti = 0;
+        while ((ti + 1) * (ti + 2) / 2 <= t) ++ti;
+        const int tj = t - ti * (ti + 1) / 2;
+        const int R = (b + 1 + ti) * SUB, Cc = (b + 1 + tj) * SUB;
+        acc_t acc;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[r] = tile[(R + X::acc_row(lane, r)) * LEAF_PAD + Cc + l16];
+        T aop[4], bop[4];
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+          const int k = c0 + 4 * s4 + g;
+          aop[s4] = -(tile[(R + l16) * LEAF_PAD + k] * dsave[k]);
+          bop[s4] = tile[(Cc + l16) * LEAF_PAD + k];
+        }
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) acc = X::mfma(aop[s4], bop[s4], acc);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) tile[(R + X::acc_row(lane, r)) * LEAF_PAD + Cc + l16] = acc[r];
+      }
+    }
+    __syncthreads();
+  }
 
   // pivots out; first zero / non-finite pivot reported through the flags
-  const T myd = dsave[lane];
-  const bool zero = myd == T(0);
-  const bool bad = lane < w && (zero || !(fabs((double)myd) <= 1.7976931348623157e308));
-  if (lane < w) { dvec[lane] = myd; dinv[lane] = rsave[lane]; }
-  const unsigned long long mask = __ballot(bad);
-  if (mask != 0ull) {
-    const int first = __ffsll((long long)mask) - 1;
-    if (lane == first) {
-      unsigned long long idx = (unsigned long long)(pivot0 + first);
-      unsigned long long old = atomicMin(&flags->first_bad, idx);
-      if (idx <= old) atomicExch(&flags->bad_kind, zero ? 1ull : 2ull);
+  if (wave == 0) {
+    const T myd = dsave[lane];
+    const bool zero = myd == T(0);
+    const bool bad = lane < w && (zero || !(fabs((double)myd) <= 1.7976931348623157e308));
+    if (lane < w) { dvec[lane] = myd; dinv[lane] = rsave[lane]; }
+    const unsigned long long mask = __ballot(bad);
+    if (mask != 0ull) {
+      const int first = __ffsll((long long)mask) - 1;
+      if (lane == first) {
+        unsigned long long idx = (unsigned long long)(pivot0 + first);
+        unsigned long long old = atomicMin(&flags->first_bad, idx);
+        if (idx <= old) atomicExch(&flags->bad_kind, zero ? 1ull : 2ull);
+      }
     }
   }
   // write back the lower triangle (L below the diagonal, D on it)
 #pragma unroll
-  for (int j = 0; j < LEAF; ++j) tile[lane * LEAF_PAD + j] = a[j];
-  __syncthreads();
-  for (int e = lane; e < LEAF * LEAF; e += 64) {
-    int r = e >> 6, c = e & 63;
+  for (int q = 0; q < LEAF * LEAF / FACTOR_THREADS; ++q) {
+    const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
     if (r < w && c <= r) A[(int64_t)r * ld + c] = tile[r * LEAF_PAD + c];
   }
 }
 
-// Rows below a factored leaf.  One wavefront per workgroup takes 64 rows; lane = row.
-// X (m x w, in place) <- X L^-T D^-1 by forward substitution along the row,
-//    w_j = x_j - sum_{p<j} w_p L[j][p] ;  l_j = w_j / d_j  (as w_j * dinv_j),
-// arranged column by column (once w_p is final it is subtracted from every later
-// entry), so the multiply-adds of one step are independent while each entry still
-// receives its terms in the order p = 0, 1, 2, ...  L is kept transposed in LDS and
-// read as broadcasts.
-constexpr int LT_STRIDE = LEAF + 2;   // even: rows stay 16-byte aligned
+// ---------------------------------------------------------------------------
+// leaf solve
+// ---------------------------------------------------------------------------
+// Rows below a factored leaf: X (m x w, in place) <- X L^-T D^-1.
+// 256 threads = 4 wavefronts, each owning 16 rows as four 16 x 16 sub-blocks held
+// in MFMA accumulator layout.  Sub-block b:  T_b = X_b - sum_{p<b} W_p L[b,p]^T
+// (products on the matrix cores, terms in the order p = 0, 1, ...), then
+// W_b = T_b L_bb^-T with the inverse of the unit-lower diagonal sub-block prepared
+// by the factor kernel, then L_b = W_b D_b^-1 goes back to memory.
+constexpr int SOLVE_ROWS = 64;   // rows per workgroup
 
 template <typename T>
-__global__ __launch_bounds__(64) void leaf_solve_kernel(
-    T* __restrict__ X, int64_t ld, int m, int w, const T* __restrict__ Lleaf, int64_t ldl,
-    const T* __restrict__ dinv) {
-  __shared__ __attribute__((aligned(16))) T Lt[LEAF * LT_STRIDE];   // Lt[p][j] = L[j][p], j > p
+__global__ __launch_bounds__(256) void leaf_solve_kernel(
+    T* __restrict__ Xg, int64_t ld, int m, int w, const T* __restrict__ Lleaf, int64_t ldl,
+    const T* __restrict__ dinv, const T* __restrict__ linv) {
+  using X = Mfma<T>;
+  using acc_t = typename X::acc_t;
+  __shared__ T Ls[LEAF * LEAF_PAD];             // strictly lower part of the leaf's L
+  __shared__ T Li[NSUB * SUB * SUB_PAD];        // inverses of its diagonal sub-blocks
   __shared__ T rinv[LEAF];
-  __shared__ T stage[LEAF * LEAF_PAD];
-  const int lane = threadIdx.x;
+  __shared__ T wsc[4][SUB * LEAF_PAD];          // per wavefront: solved W, row-major
+  __shared__ T tsc[4][SUB * SUB_PAD];           // per wavefront: layout change of T_b
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, g = lane >> 4;
 
-  tile_to_lds<T, true, true>(Lt, LT_STRIDE, Lleaf, ldl, w, w, false, lane);
-  rinv[lane] = lane < w ? dinv[lane] : T(0);
-
-  const int64_t r0 = (int64_t)blockIdx.x * LEAF;
-  int rows = m - r0 < LEAF ? (int)(m - r0) : LEAF;
-  T* Xw = X + r0 * ld;
-  tile_to_lds<T, false, false>(stage, LEAF_PAD, Xw, ld, rows, w, false, lane);
-  __syncthreads();
-
-  T x[LEAF];
+  // this wavefront's rows, straight into accumulator layout (16 lanes = 128 bytes of a row)
+  const int64_t r0 = ((int64_t)blockIdx.x * 4 + wave) * SUB;
+  acc_t xb[NSUB];
 #pragma unroll
-  for (int j = 0; j < LEAF; ++j) x[j] = stage[lane * LEAF_PAD + j];
+  for (int b = 0; b < NSUB; ++b)
 #pragma unroll
-  for (int p = 0; p < LEAF - 1; ++p) {
-    const T xp = x[p];
+    for (int r = 0; r < 4; ++r) {
+      const int64_t row = r0 + X::acc_row(lane, r);
+      const int col = b * SUB + l16;
+      xb[b][r] = (row < m && col < w) ? Xg[row * ld + col] : T(0);
+    }
+  // leaf data shared by the four wavefronts
+  {
+    T v[LEAF * LEAF / 256];
 #pragma unroll
-    for (int j = p + 1; j < LEAF; ++j) x[j] -= xp * Lt[p * LT_STRIDE + j];
+    for (int q = 0; q < LEAF * LEAF / 256; ++q) {
+      const int e = q * 256 + tid, r = e >> 6, c = e & 63;
+      v[q] = (r < w && c < r) ? Lleaf[(int64_t)r * ldl + c] : T(0);
+    }
+    T u[NSUB * SUB * SUB / 256];
+#pragma unroll
+    for (int q = 0; q < NSUB * SUB * SUB / 256; ++q) u[q] = linv[q * 256 + tid];
+    const T myr = (tid < LEAF && tid < w) ? dinv[tid < LEAF ? tid : 0] : T(0);
+#pragma unroll
+    for (int q = 0; q < LEAF * LEAF / 256; ++q) {
+      const int e = q * 256 + tid, r = e >> 6, c = e & 63;
+      Ls[r * LEAF_PAD + c] = v[q];
+    }
+#pragma unroll
+    for (int q = 0; q < NSUB * SUB * SUB / 256; ++q) {
+      const int e = q * 256 + tid, blk = e >> 8, i = (e >> 4) & 15, k = e & 15;
+      Li[(blk * SUB + i) * SUB_PAD + k] = u[q];
+    }
+    if (tid < LEAF) rinv[tid] = myr;
   }
-#pragma unroll
-  for (int j = 0; j < LEAF; ++j) stage[lane * LEAF_PAD + j] = x[j] * rinv[j];
   __syncthreads();
-  for (int e = lane; e < LEAF * LEAF; e += 64) {
-    int r = e >> 6, c = e & 63;
-    if (r < rows && c < w) Xw[(int64_t)r * ld + c] = stage[r * LEAF_PAD + c];
+
+  T* ws = wsc[wave];
+  T* ts = tsc[wave];
+#pragma unroll
+  for (int b = 0; b < NSUB; ++b) {
+    acc_t acc = xb[b];
+    // T_b = X_b - sum_{p<b} W_p L[b,p]^T
+#pragma unroll 1
+    for (int p = 0; p < b; ++p) {
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4) {
+        const int k = p * SUB + 4 * s4 + g;
+        const T aop = -ws[l16 * LEAF_PAD + k];
+        const T bop = Ls[(b * SUB + l16) * LEAF_PAD + k];
+        acc = X::mfma(aop, bop, acc);
+      }
+    }
+    // accumulator layout -> operand layout through LDS
+#pragma unroll
+    for (int r = 0; r < 4; ++r) ts[X::acc_row(lane, r) * SUB_PAD + l16] = acc[r];
+    __syncthreads();
+    // W_b = T_b L_bb^-T
+    acc_t wb = acc_t{0, 0, 0, 0};
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+      const int k = 4 * s4 + g;
+      wb = X::mfma(ts[l16 * SUB_PAD + k], Li[(b * SUB + l16) * SUB_PAD + k], wb);
+    }
+    const T rj = rinv[b * SUB + l16];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int row16 = X::acc_row(lane, r);
+      ws[row16 * LEAF_PAD + b * SUB + l16] = wb[r];
+      const int64_t row = r0 + row16;
+      const int col = b * SUB + l16;
+      if (row < m && col < w) Xg[row * ld + col] = wb[r] * rj;
+    }
+    __syncthreads();
   }
 }
 

@@ -21,47 +21,46 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "mfma.h"
+
 namespace mdet {
 
-template <typename T> struct Mfma;
-
-template <> struct Mfma<double> {
-  typedef double acc_t __attribute__((ext_vector_type(4)));
-  typedef double vec_t __attribute__((ext_vector_type(2)));   // 16 bytes
-  static constexpr int VEC = 2;
-  static constexpr int BK = 16;
-  static __device__ __forceinline__ acc_t mfma(double a, double b, acc_t c) {
-    return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
-  }
-  // row inside the 16 x 16 tile held by accumulator register r of this lane
-  static __device__ __forceinline__ int acc_row(int lane, int r) { return 4 * r + (lane >> 4); }
-};
-
-template <> struct Mfma<float> {
-  typedef float acc_t __attribute__((ext_vector_type(4)));
-  typedef float vec_t __attribute__((ext_vector_type(4)));    // 16 bytes
-  static constexpr int VEC = 4;
-  static constexpr int BK = 32;
-  static __device__ __forceinline__ acc_t mfma(float a, float b, acc_t c) {
-    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
-  }
-  static __device__ __forceinline__ int acc_row(int lane, int r) { return 4 * (lane >> 4) + r; }
-};
-
-constexpr int UPD_BM = 128;
-constexpr int UPD_BN = 128;
 constexpr int UPD_THREADS = 256;
 constexpr int UPD_ROW_BYTES = 144;   // 128 data bytes + 16 pad: conflict-free 16-lane reads
 
-// Number of 128 x 128 blocks a launch needs.
-static inline int64_t update_num_blocks(int64_t M, int64_t N, bool lower) {
-  int64_t nbm = (M + UPD_BM - 1) / UPD_BM, nbn = (N + UPD_BN - 1) / UPD_BN;
+// Number of tile x tile blocks a launch needs (tile = 128 or 64).
+static inline int64_t update_num_blocks(int64_t M, int64_t N, bool lower, int tile = 128) {
+  int64_t nbm = (M + tile - 1) / tile, nbn = (N + tile - 1) / tile;
   if (!lower) return nbm * nbn;
   int64_t t = nbm < nbn ? nbm : nbn;           // rows inside the triangular part
   return t * (t + 1) / 2 + (nbm - t) * nbn;
 }
 
-template <typename T, bool LOWER>
+// Block (bm, bn) of a launch from its linear index: row-major over the lower
+// trapezoid (LOWER) or over the full grid.
+template <bool LOWER>
+__device__ __forceinline__ void update_block_of(int64_t id, int nbn, int& bm, int& bn) {
+  if (LOWER) {
+    int64_t tri = (int64_t)nbn * (nbn + 1) / 2;
+    if (id < tri) {
+      int64_t r = (int64_t)((sqrt(8.0 * (double)id + 1.0) - 1.0) * 0.5);
+      while (r * (r + 1) / 2 > id) --r;
+      while ((r + 1) * (r + 2) / 2 <= id) ++r;
+      bm = (int)r;
+      bn = (int)(id - r * (r + 1) / 2);
+    } else {
+      int64_t rest = id - tri;
+      bm = nbn + (int)(rest / nbn);
+      bn = (int)(rest % nbn);
+    }
+  } else {
+    bm = (int)(id / nbn);
+    bn = (int)(id % nbn);
+  }
+}
+
+// TM = MFMA tiles per wavefront in each direction: 4 -> 128 x 128 block, 2 -> 64 x 64.
+template <typename T, bool LOWER, int TM>
 __device__ __forceinline__ void schur_update_body(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K,
@@ -71,43 +70,26 @@ __device__ __forceinline__ void schur_update_body(
   using vec_t = typename X::vec_t;
   constexpr int BK = X::BK, VEC = X::VEC;
   constexpr int S = UPD_ROW_BYTES / (int)sizeof(T);   // LDS row stride in elements
-  constexpr int HALF = BK / 2;                        // elements each thread stages per row
-  constexpr int NV = HALF / VEC;                      // 16-byte vectors per thread per operand (4)
+  constexpr int WT = 16 * TM;                         // rows/cols of C per wavefront
+  constexpr int BM = 2 * WT, BN = 2 * WT;             // block of C per workgroup
+  constexpr int TPR = UPD_THREADS / BM;               // threads staging one row of a slab (2 or 4)
+  constexpr int HALF = BK / TPR;                      // elements each thread stages per row
+  constexpr int NV = HALF / VEC;                      // 16-byte vectors per thread per operand
   constexpr int KS = BK / 4;                          // MFMA k-steps per slab
 
-  __shared__ __attribute__((aligned(16))) T As[2][UPD_BM * S];
-  __shared__ __attribute__((aligned(16))) T Bs[2][UPD_BN * S];
+  __shared__ __attribute__((aligned(16))) T As[2][BM * S];
+  __shared__ __attribute__((aligned(16))) T Bs[2][BN * S];
 
-  // ---- which block -------------------------------------------------------
   int bm, bn;
-  {
-    int64_t id = blockIdx.x;
-    if (LOWER) {
-      int64_t tri = (int64_t)nbn * (nbn + 1) / 2;
-      if (id < tri) {
-        int64_t r = (int64_t)((sqrt(8.0 * (double)id + 1.0) - 1.0) * 0.5);
-        while (r * (r + 1) / 2 > id) --r;
-        while ((r + 1) * (r + 2) / 2 <= id) ++r;
-        bm = (int)r;
-        bn = (int)(id - r * (r + 1) / 2);
-      } else {
-        int64_t rest = id - tri;
-        bm = nbn + (int)(rest / nbn);
-        bn = (int)(rest % nbn);
-      }
-    } else {
-      bm = (int)(id / nbn);
-      bn = (int)(id % nbn);
-    }
-  }
-  const int row0 = bm * UPD_BM, col0 = bn * UPD_BN;
+  update_block_of<LOWER>(blockIdx.x, nbn, bm, bn);
+  const int row0 = bm * BM, col0 = bn * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   // a wavefront whose 64 x 64 piece lies strictly above the diagonal has nothing to do
-  const bool active = !(LOWER && (row0 + wm * 64 + 63 < col0 + wn * 64));
+  const bool active = !(LOWER && (row0 + wm * WT + WT - 1 < col0 + wn * WT));
 
   // ---- global -> register staging ---------------------------------------
-  const int srow = tid >> 1, shalf = tid & 1;
+  const int srow = tid / TPR, shalf = tid % TPR;
   int ar = row0 + srow; if (ar > M - 1) ar = M - 1;
   int br = col0 + srow; if (br > N - 1) br = N - 1;
   const T* Ap = A + (int64_t)ar * lda + shalf * HALF;
@@ -140,22 +122,22 @@ __device__ __forceinline__ void schur_update_body(
   // recurrence a_ij - sum_k l_ik d_k l_jk; when the Schur complement is much
   // smaller than a_ij (low-rank Gram matrix plus a small shift) the late roundings
   // are then relative to the small running value, not to the full sum.
-  acc_t acc[4][4];
+  acc_t acc[TM][TM];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = acc_t{0, 0, 0, 0};
+    for (int j = 0; j < TM; ++j) acc[i][j] = acc_t{0, 0, 0, 0};
   if (active) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const int grow = row0 + wm * 64 + i * 16 + X::acc_row(lane, r);
+        const int grow = row0 + wm * WT + i * 16 + X::acc_row(lane, r);
         if (grow >= M) continue;
         const T* crow = C + (int64_t)grow * ldc;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int gcol = col0 + wn * 64 + j * 16 + r16;
+        for (int j = 0; j < TM; ++j) {
+          const int gcol = col0 + wn * WT + j * 16 + r16;
           if (gcol < N && (!LOWER || gcol <= grow)) acc[i][j][r] = crow[gcol];
         }
       }
@@ -175,22 +157,22 @@ __device__ __forceinline__ void schur_update_body(
       // lane group g owns the KS consecutive k's [g*KS, (g+1)*KS) of the slab; MFMA
       // step s multiplies the s-th of them from every group (any assignment of the
       // slab's k's to steps is valid as long as A and B use the same one).
-      const T* as = &As[buf][(wm * 64 + r16) * S + g * KS];
-      const T* bs = &Bs[buf][(wn * 64 + r16) * S + g * KS];
+      const T* as = &As[buf][(wm * WT + r16) * S + g * KS];
+      const T* bs = &Bs[buf][(wn * WT + r16) * S + g * KS];
 #pragma unroll
       for (int h = 0; h < KS / VEC; ++h) {
-        vec_t fa[4], fb[4];
+        vec_t fa[TM], fb[TM];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int t = 0; t < TM; ++t) {
           fa[t] = *reinterpret_cast<const vec_t*>(as + t * 16 * S + h * VEC);
           fb[t] = *reinterpret_cast<const vec_t*>(bs + t * 16 * S + h * VEC);
         }
 #pragma unroll
         for (int e = 0; e < VEC; ++e)
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
+          for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc[i][j] = X::mfma(fa[i][e], fb[j][e], acc[i][j]);
+            for (int j = 0; j < TM; ++j) acc[i][j] = X::mfma(fa[i][e], fb[j][e], acc[i][j]);
       }
     }
     if (kt + 1 < nk) sstore(buf ^ 1);
@@ -200,35 +182,148 @@ __device__ __forceinline__ void schur_update_body(
   // ---- epilogue: store the reduced block ----------------------------------
   if (!active) return;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < TM; ++i) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int grow = row0 + wm * 64 + i * 16 + X::acc_row(lane, r);
+      const int grow = row0 + wm * WT + i * 16 + X::acc_row(lane, r);
       if (grow >= M) continue;
       T* crow = C + (int64_t)grow * ldc;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int gcol = col0 + wn * 64 + j * 16 + r16;
+      for (int j = 0; j < TM; ++j) {
+        const int gcol = col0 + wn * WT + j * 16 + r16;
         if (gcol < N && (!LOWER || gcol <= grow)) crow[gcol] = acc[i][j][r];
       }
     }
   }
 }
 
-// Two names for the same body: the update of the trailing matrix by a finished
-// block column (the bulk of all work) and the updates inside a block column's own
-// recursive factorisation.
+// Names for the same body: the update of the trailing matrix by a finished block
+// column (the bulk of all work), and the updates inside a block column's own
+// recursive factorisation (128- and 64-wide blocks; the small one spreads short
+// launches over more compute units).
 template <typename T, bool LOWER>
 __global__ __launch_bounds__(UPD_THREADS) void trailing_update_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nbn) {
-  schur_update_body<T, LOWER>(C, ldc, A, lda, B, ldb, d, M, N, K, nbn);
+  schur_update_body<T, LOWER, 4>(C, ldc, A, lda, B, ldb, d, M, N, K, nbn);
 }
 template <typename T, bool LOWER>
 __global__ __launch_bounds__(UPD_THREADS) void panel_update_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nbn) {
-  schur_update_body<T, LOWER>(C, ldc, A, lda, B, ldb, d, M, N, K, nbn);
+  schur_update_body<T, LOWER, 4>(C, ldc, A, lda, B, ldb, d, M, N, K, nbn);
+}
+template <typename T, bool LOWER>
+__global__ __launch_bounds__(UPD_THREADS) void panel_update64_kernel(
+    T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
+    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nbn) {
+  schur_update_body<T, LOWER, 2>(C, ldc, A, lda, B, ldb, d, M, N, K, nbn);
+}
+
+// K = 64 exactly (the update of the columns right of a leaf by that leaf): both
+// operands, the pivots and the C block are requested in one go and the whole
+// product runs from LDS, so the launch costs one memory round trip instead of one
+// per slab.  64 x 64 block of C per workgroup, 2 x 2 MFMA tiles per wavefront.
+template <typename T, bool LOWER>
+__global__ __launch_bounds__(UPD_THREADS) void leaf_update_kernel(
+    T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
+    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int nbn) {
+  using X = Mfma<T>;
+  using acc_t = typename X::acc_t;
+  using vec_t = typename X::vec_t;
+  constexpr int VEC = X::VEC, BK = X::BK, KS = BK / 4;
+  constexpr int KT = 64;                                    // K
+  constexpr int S = (KT * (int)sizeof(T) + 16) / (int)sizeof(T);   // padded LDS row, elements
+  constexpr int VPR = KT / VEC;                             // 16-byte vectors per row
+  constexpr int NV = VPR / 4;                               // per thread (4 threads per row)
+  __shared__ __attribute__((aligned(16))) T As[64 * S];
+  __shared__ __attribute__((aligned(16))) T Bs[64 * S];
+
+  int bm, bn;
+  update_block_of<LOWER>(blockIdx.x, nbn, bm, bn);
+  const int row0 = bm * 64, col0 = bn * 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int r16 = lane & 15, g = lane >> 4;
+  const bool active = !(LOWER && (row0 + wm * 32 + 31 < col0 + wn * 32));
+
+  const int srow = tid >> 2, sq = tid & 3;
+  int ar = row0 + srow; if (ar > M - 1) ar = M - 1;
+  int br = col0 + srow; if (br > N - 1) br = N - 1;
+  const T* Ap = A + (int64_t)ar * lda + sq * NV * VEC;
+  const T* Bp = B + (int64_t)br * ldb + sq * NV * VEC;
+  const T* dp = d + sq * NV * VEC;
+  vec_t ra[NV], rb[NV], rd[NV];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    ra[v] = *reinterpret_cast<const vec_t*>(Ap + v * VEC);
+    rb[v] = *reinterpret_cast<const vec_t*>(Bp + v * VEC);
+    rd[v] = *reinterpret_cast<const vec_t*>(dp + v * VEC);
+  }
+  acc_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = acc_t{0, 0, 0, 0};
+  if (active) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int grow = row0 + wm * 32 + i * 16 + X::acc_row(lane, r);
+        if (grow >= M) continue;
+        const T* crow = C + (int64_t)grow * ldc;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int gcol = col0 + wn * 32 + j * 16 + r16;
+          if (gcol < N && (!LOWER || gcol <= grow)) acc[i][j][r] = crow[gcol];
+        }
+      }
+  }
+  {
+    T* as = &As[srow * S + sq * NV * VEC];
+    T* bs = &Bs[srow * S + sq * NV * VEC];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      *reinterpret_cast<vec_t*>(as + v * VEC) = -(ra[v] * rd[v]);
+      *reinterpret_cast<vec_t*>(bs + v * VEC) = rb[v];
+    }
+  }
+  __syncthreads();
+  if (!active) return;
+#pragma unroll
+  for (int slab = 0; slab < KT / BK; ++slab) {
+    const T* as = &As[(wm * 32 + r16) * S + slab * BK + g * KS];
+    const T* bs = &Bs[(wn * 32 + r16) * S + slab * BK + g * KS];
+#pragma unroll
+    for (int h = 0; h < KS / VEC; ++h) {
+      vec_t fa[2], fb[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        fa[t] = *reinterpret_cast<const vec_t*>(as + t * 16 * S + h * VEC);
+        fb[t] = *reinterpret_cast<const vec_t*>(bs + t * 16 * S + h * VEC);
+      }
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) acc[i][j] = X::mfma(fa[i][e], fb[j][e], acc[i][j]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int grow = row0 + wm * 32 + i * 16 + X::acc_row(lane, r);
+      if (grow >= M) continue;
+      T* crow = C + (int64_t)grow * ldc;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int gcol = col0 + wn * 32 + j * 16 + r16;
+        if (gcol < N && (!LOWER || gcol <= grow)) crow[gcol] = acc[i][j][r];
+      }
+    }
 }
 
 }  // namespace mdet

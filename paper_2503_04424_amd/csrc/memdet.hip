@@ -91,6 +91,7 @@ struct Launcher {
   HipFail* fail;
   T* dvec = nullptr;
   T* dinv = nullptr;
+  T* linv = nullptr;          // inverses of the current leaf's diagonal sub-blocks
   DevFlags* flags = nullptr;
   double fma = 0.0;
   uint64_t launches = 0;
@@ -112,8 +113,14 @@ struct Launcher {
     if (K % 64 != 0 || lda % vec != 0 || ldb % vec != 0 || !aligned16(A) || !aligned16(B) ||
         !aligned16(d) || M > INT32_MAX || N > INT32_MAX || K > INT32_MAX || ldc < N)
       return MDET_EINVAL;
-    int64_t nbn = (N + UPD_BN - 1) / UPD_BN;
-    int64_t nblk = update_num_blocks(M, N, lower);
+    // kernel choice: the trailing update always uses 128 x 128 blocks; inside a
+    // block column a K = 64 update runs single-shot from LDS and short launches
+    // use 64 x 64 blocks so that they reach more compute units
+    const bool leaf_k = !trailing && K == 64;
+    const bool small = !trailing && !leaf_k && update_num_blocks(M, N, lower, 128) < 512;
+    const int tile = (leaf_k || small) ? 64 : 128;
+    int64_t nbn = (N + tile - 1) / tile;
+    int64_t nblk = update_num_blocks(M, N, lower, tile);
     if (nblk > INT32_MAX) return MDET_EINVAL;
     dim3 grid((unsigned)nblk), block(UPD_THREADS);
     hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -123,21 +130,26 @@ struct Launcher {
       fail->check(hipEventCreate(&e1));
       fail->check(hipEventRecord(e0, st));
     }
-    if (trailing) {
+#define MDET_LAUNCH_UPD(KERNEL)                                                                   \
+  do {                                                                                            \
+    if (lower)                                                                                    \
+      hipLaunchKernelGGL((KERNEL<T, true>), grid, block, 0, st, C, ldc, A, lda, B, ldb, d, (int)M, \
+                         (int)N, (int)K, (int)nbn);                                               \
+    else                                                                                          \
+      hipLaunchKernelGGL((KERNEL<T, false>), grid, block, 0, st, C, ldc, A, lda, B, ldb, d,       \
+                         (int)M, (int)N, (int)K, (int)nbn);                                       \
+  } while (0)
+    if (trailing) MDET_LAUNCH_UPD(trailing_update_kernel);
+    else if (leaf_k) {
       if (lower)
-        hipLaunchKernelGGL((trailing_update_kernel<T, true>), grid, block, 0, st, C, ldc, A, lda, B,
-                           ldb, d, (int)M, (int)N, (int)K, (int)nbn);
+        hipLaunchKernelGGL((leaf_update_kernel<T, true>), grid, block, 0, st, C, ldc, A, lda, B, ldb,
+                           d, (int)M, (int)N, (int)nbn);
       else
-        hipLaunchKernelGGL((trailing_update_kernel<T, false>), grid, block, 0, st, C, ldc, A, lda, B,
-                           ldb, d, (int)M, (int)N, (int)K, (int)nbn);
-    } else {
-      if (lower)
-        hipLaunchKernelGGL((panel_update_kernel<T, true>), grid, block, 0, st, C, ldc, A, lda, B,
-                           ldb, d, (int)M, (int)N, (int)K, (int)nbn);
-      else
-        hipLaunchKernelGGL((panel_update_kernel<T, false>), grid, block, 0, st, C, ldc, A, lda, B,
-                           ldb, d, (int)M, (int)N, (int)K, (int)nbn);
-    }
+        hipLaunchKernelGGL((leaf_update_kernel<T, false>), grid, block, 0, st, C, ldc, A, lda, B,
+                           ldb, d, (int)M, (int)N, (int)nbn);
+    } else if (small) MDET_LAUNCH_UPD(panel_update64_kernel);
+    else MDET_LAUNCH_UPD(panel_update_kernel);
+#undef MDET_LAUNCH_UPD
     fail->check(hipGetLastError());
     ++launches;
     double f;
@@ -162,18 +174,18 @@ struct Launcher {
   int factor_cols(hipStream_t st, T* P, int64_t ld, int64_t m, int64_t w, int64_t d0) {
     if (w <= 0) return MDET_OK;
     if (w <= LEAF) {
-      hipLaunchKernelGGL((leaf_factor_kernel<T>), dim3(1), dim3(64), 0, st, P, ld, (int)w,
-                         dvec + d0, dinv + d0, (long long)d0, flags);
+      hipLaunchKernelGGL((leaf_factor_kernel<T>), dim3(1), dim3(FACTOR_THREADS), 0, st, P, ld, (int)w,
+                         dvec + d0, dinv + d0, linv, (long long)d0, flags);
       fail->check(hipGetLastError());
       ++launches;
       fma += ((double)w * w * w - (double)w) / 6.0;
       int64_t below = m - w;
       if (below > 0) {
         if (below > INT32_MAX) return MDET_EINVAL;
-        int64_t nblk = (below + LEAF - 1) / LEAF;
-        hipLaunchKernelGGL((leaf_solve_kernel<T>), dim3((unsigned)nblk), dim3(64), 0,
+        int64_t nblk = (below + SOLVE_ROWS - 1) / SOLVE_ROWS;
+        hipLaunchKernelGGL((leaf_solve_kernel<T>), dim3((unsigned)nblk), dim3(256), 0,
                            st, P + w * ld, ld, (int)below, (int)w, (const T*)P, ld,
-                           (const T*)(dinv + d0));
+                           (const T*)(dinv + d0), (const T*)linv);
         fail->check(hipGetLastError());
         ++launches;
         fma += (double)below * ((double)w * (w - 1) / 2.0);
@@ -375,6 +387,7 @@ template <typename T>
 static void bind_small(Launcher<T>& L, char* base, const SmallArea& sa) {
   L.dvec = (T*)(base + sa.dvec);
   L.dinv = (T*)(base + sa.dinv);
+  L.linv = (T*)(base + sa.linv);
   L.flags = (DevFlags*)(base + sa.flags);
 }
 
@@ -862,11 +875,13 @@ int mdet_step_panel_factor(int32_t dtype, void* P, int64_t ld, int64_t m, int64_
     Launcher<double> L; L.fail = &fail;
     // the launcher indexes dvec/dinv by global pivot index
     L.dvec = (double*)d - pivot_index0; L.dinv = (double*)dinv - pivot_index0; L.flags = (DevFlags*)flags;
+    L.linv = (double*)((char*)flags + 16);
     rc = L.factor_cols((hipStream_t)stream, (double*)P, ld, m, w, pivot_index0);
   } else if (dtype == MDET_F32) {
     if (ld % 4 || ((uintptr_t)P & 15u)) return MDET_EINVAL;
     Launcher<float> L; L.fail = &fail;
     L.dvec = (float*)d - pivot_index0; L.dinv = (float*)dinv - pivot_index0; L.flags = (DevFlags*)flags;
+    L.linv = (float*)((char*)flags + 16);
     rc = L.factor_cols((hipStream_t)stream, (float*)P, ld, m, w, pivot_index0);
   } else return MDET_EINVAL;
   if (!fail.ok()) return MDET_EHIP;

@@ -70,13 +70,14 @@ inline uint64_t align256(uint64_t x) { return (x + 255) / 256 * 256; }
 
 // Layout of the small scratch area (offsets in bytes from its start).
 struct SmallArea {
-  uint64_t dvec, dinv, flags, partial, out, running, total;
+  uint64_t dvec, dinv, linv, flags, partial, out, running, total;
 };
 inline SmallArea small_area(int64_t n, int64_t T, int beta) {
   SmallArea a;
   uint64_t o = 0;
   a.dvec = o; o += align256((uint64_t)(n > 0 ? n : 1) * beta);
   a.dinv = o; o += align256((uint64_t)(n > 0 ? n : 1) * beta);
+  a.linv = o; o += align256((uint64_t)64 * 16 * beta);   // one leaf's inverse diagonal sub-blocks
   a.flags = o; o += 256;
   a.partial = o; o += align256((uint64_t)(T > 0 ? T : 1) * 3 * 8);
   a.out = o; o += 256;

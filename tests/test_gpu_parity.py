@@ -82,7 +82,7 @@ def test_panel_factor_matches_oracle_factor(M, dtype, m, w):
     ad.copy_(dev(a))
     d = torch.zeros(w, dtype=ad.dtype, device="cuda")
     dinv = torch.zeros_like(d)
-    flags = torch.full((4,), -1, dtype=torch.int64, device="cuda")
+    flags = torch.full((2 + 1024,), -1, dtype=torch.int64, device="cuda")
     M.mdet_step_panel_factor(ad, w, d, dinv, flags)
     torch.cuda.synchronize()
     got = ad.cpu().numpy().astype(np.float64)
