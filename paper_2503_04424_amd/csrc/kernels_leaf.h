@@ -111,7 +111,6 @@ __device__ __forceinline__ void panel16_step(T (&a)[SUB], const int c0, const in
 #pragma unroll
     for (int c = J + 1; c < SUB; ++c) a[c] -= lj * lane_value(wj, c0 + c);   // a_ic -= l_iJ d_J l_cJ
     a[J] = lane > c0 + J ? lj : a[J];
-    __builtin_amdgcn_sched_barrier(0);
     panel16_step<T, J + 1>(a, c0, lane, dsave, rsave);
   }
 }
@@ -130,13 +129,28 @@ __device__ __forceinline__ void inv16_step(const T (&a)[SUB], T (&x)[SUB], const
   }
 }
 
+// Inverse of the unit-lower diagonal sub-block b of the leaf in `tile` -> linv.
+template <typename T>
+__device__ __forceinline__ void leaf_invert_sub(const T* tile, T* __restrict__ linv, const int b,
+                                                const int l16, const int g) {
+  const int c0 = b * SUB;
+  T a[SUB], x[SUB];
+#pragma unroll
+  for (int q = 0; q < SUB; ++q) a[q] = tile[(c0 + l16) * LEAF_PAD + c0 + q];   // row l16 of L_bb
+  inv16_step<T, 0>(a, x, l16);
+  if (g == 0) {
+#pragma unroll
+    for (int i = 0; i < SUB; ++i) linv[(b * SUB + i) * SUB + l16] = x[i];
+  }
+}
+
 // Four wavefronts factor one leaf held in LDS, 16 columns at a time:
 //   wavefront 0: panel (rows from its diagonal down) -> registers (one row per
 //                lane), eliminated, written back;
 //   then all:    every sub-block right of / below the panel updated with 16x16x16
-//                MFMA products, shared round-robin, while the last wavefront first
-//                inverts the panel's unit-lower diagonal sub-block into `linv`
-//                (used by the solve kernel).
+//                MFMA products, shared round-robin;
+//   wavefront 3: while wavefront 0 eliminates panel b, inverts panel b-1's
+//                unit-lower diagonal sub-block into `linv` (used by the solve kernel).
 constexpr int FACTOR_THREADS = 256;
 
 template <typename T>
@@ -175,26 +189,17 @@ __global__ __launch_bounds__(FACTOR_THREADS) void leaf_factor_kernel(
       panel16_step<T, 0>(a, c0, lane, dsave, rsave);
 #pragma unroll
       for (int q = 0; q < SUB; ++q) tile[lane * LEAF_PAD + c0 + q] = a[q];
+    } else if (wave == 3 && b > 0) {
+      // meanwhile: inverse of the previous panel's diagonal sub-block
+      leaf_invert_sub<T>(tile, linv, b - 1, l16, g);
     }
     __syncthreads();
-    if (wave == 3) {
-      T a[SUB], x[SUB];
-#pragma unroll
-      for (int q = 0; q < SUB; ++q) a[q] = tile[(c0 + l16) * LEAF_PAD + c0 + q];   // row l16 of L_bb
-      inv16_step<T, 0>(a, x, l16);
-      if (g == 0) {
-#pragma unroll
-        for (int i = 0; i < SUB; ++i) linv[(b * SUB + i) * SUB + l16] = x[i];
-      }
-    }
     // trailing sub-blocks (ti, tj), b < tj <= ti:  S -= L[ti, b] D_b L[tj, b]^T
     {
       const int nt = NSUB - 1 - b;               // sub-block rows/columns left
       const int ntiles = nt * (nt + 1) / 2;
-      // the inverting wavefront joins last
-      const int first = wave == 3 ? 3 : wave;
 #pragma unroll 1
-      for (int t = first; t < ntiles; t += 4) {
+      for (int t = wave; t < ntiles; t += 4) {
         int ti = 0;
         while ((ti + 1) * (ti + 2) / 2 <= t) ++ti;
         const int tj = t - ti * (ti + 1) / 2;
@@ -217,6 +222,7 @@ __global__ __launch_bounds__(FACTOR_THREADS) void leaf_factor_kernel(
     }
     __syncthreads();
   }
+  if (wave == 3) leaf_invert_sub<T>(tile, linv, NSUB - 1, l16, g);
 
   // pivots out; first zero / non-finite pivot reported through the flags
   if (wave == 0) {
