@@ -26,7 +26,6 @@
 namespace mdet {
 
 constexpr int UPD_THREADS = 256;
-constexpr int UPD_ROW_BYTES = 144;   // 128 data bytes + 16 pad: conflict-free 16-lane reads
 
 // Number of tile x tile blocks a launch needs (tile = 128 or 64).
 static inline int64_t update_num_blocks(int64_t M, int64_t N, bool lower, int tile = 128) {
@@ -60,7 +59,11 @@ __device__ __forceinline__ void update_block_of(int64_t id, int nbn, int& bm, in
 }
 
 // TM = MFMA tiles per wavefront in each direction: 4 -> 128 x 128 block, 2 -> 64 x 64.
-template <typename T, bool LOWER, int TM>
+// SLABS = number of 128-byte K slabs staged per pipeline step (1 or 2).  A longer
+// step lets each accumulator take more consecutive MFMAs: on gfx950 every switch
+// of the fp64 MFMA accumulator costs about one extra MFMA time, so 16 tiles x 8
+// chained products waste 1/9 of the matrix pipe where 16 x 4 waste 1/5.
+template <typename T, bool LOWER, int TM, int SLABS>
 __device__ __forceinline__ void schur_update_body(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K,
@@ -68,13 +71,13 @@ __device__ __forceinline__ void schur_update_body(
   using X = Mfma<T>;
   using acc_t = typename X::acc_t;
   using vec_t = typename X::vec_t;
-  constexpr int BK = X::BK, VEC = X::VEC;
-  constexpr int S = UPD_ROW_BYTES / (int)sizeof(T);   // LDS row stride in elements
+  constexpr int BK = X::BK * SLABS, VEC = X::VEC;
+  constexpr int S = (128 * SLABS + 16) / (int)sizeof(T);   // LDS row stride in elements (padded)
   constexpr int WT = 16 * TM;                         // rows/cols of C per wavefront
   constexpr int BM = 2 * WT, BN = 2 * WT;             // block of C per workgroup
-  constexpr int TPR = UPD_THREADS / BM;               // threads staging one row of a slab (2 or 4)
-  constexpr int HALF = BK / TPR;                      // elements each thread stages per row
-  constexpr int NV = HALF / VEC;                      // 16-byte vectors per thread per operand
+  constexpr int VPR = BK / VEC;                       // 16-byte vectors per staged row
+  constexpr int RPS = UPD_THREADS / VPR;              // rows staged per step by the workgroup
+  constexpr int NV = BM / RPS;                        // steps (= vectors per thread per operand)
   constexpr int KS = BK / 4;                          // MFMA k-steps per slab
 
   __shared__ __attribute__((aligned(16))) T As[2][BM * S];
@@ -89,29 +92,30 @@ __device__ __forceinline__ void schur_update_body(
   const bool active = !(LOWER && (row0 + wm * WT + WT - 1 < col0 + wn * WT));
 
   // ---- global -> register staging ---------------------------------------
-  const int srow = tid / TPR, shalf = tid % TPR;
-  int ar = row0 + srow; if (ar > M - 1) ar = M - 1;
-  int br = col0 + srow; if (br > N - 1) br = N - 1;
-  const T* Ap = A + (int64_t)ar * lda + shalf * HALF;
-  const T* Bp = B + (int64_t)br * ldb + shalf * HALF;
-  const T* dp = d + shalf * HALF;
-  vec_t ra[NV], rb[NV], rd[NV];
+  // VPR consecutive lanes read one whole staged row (BK elements, 128 or 256
+  // contiguous bytes), so every load instruction consumes complete cache lines.
+  const int scol = (tid % VPR) * VEC, srow = tid / VPR;
+  const T* Ac = A + scol;
+  const T* Bc = B + scol;
+  vec_t ra[NV], rb[NV], rd;
 
   auto gload = [&](int kt) {
+    rd = *reinterpret_cast<const vec_t*>(d + scol + (int64_t)kt * BK);
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
-      ra[v] = *reinterpret_cast<const vec_t*>(Ap + (int64_t)kt * BK + v * VEC);
-      rb[v] = *reinterpret_cast<const vec_t*>(Bp + (int64_t)kt * BK + v * VEC);
-      rd[v] = *reinterpret_cast<const vec_t*>(dp + (int64_t)kt * BK + v * VEC);
+      int ar = row0 + v * RPS + srow; if (ar > M - 1) ar = M - 1;
+      int br = col0 + v * RPS + srow; if (br > N - 1) br = N - 1;
+      ra[v] = *reinterpret_cast<const vec_t*>(Ac + (int64_t)ar * lda + (int64_t)kt * BK);
+      rb[v] = *reinterpret_cast<const vec_t*>(Bc + (int64_t)br * ldb + (int64_t)kt * BK);
     }
   };
   auto sstore = [&](int buf) {
-    T* as = &As[buf][srow * S + shalf * HALF];
-    T* bs = &Bs[buf][srow * S + shalf * HALF];
+    T* as = &As[buf][srow * S + scol];
+    T* bs = &Bs[buf][srow * S + scol];
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
-      *reinterpret_cast<vec_t*>(as + v * VEC) = -(ra[v] * rd[v]);
-      *reinterpret_cast<vec_t*>(bs + v * VEC) = rb[v];
+      *reinterpret_cast<vec_t*>(as + v * RPS * S) = -(ra[v] * rd);
+      *reinterpret_cast<vec_t*>(bs + v * RPS * S) = rb[v];
     }
   };
 
@@ -159,20 +163,32 @@ __device__ __forceinline__ void schur_update_body(
       // slab's k's to steps is valid as long as A and B use the same one).
       const T* as = &As[buf][(wm * WT + r16) * S + g * KS];
       const T* bs = &Bs[buf][(wn * WT + r16) * S + g * KS];
+      // Fragments are fetched one 16-row strip at a time, each fetch issued one
+      // stage ahead of its first use, so that LDS latency hides behind the chain
+      // of MFMAs of the stage before.  Stage (i, j): all KS products of
+      // accumulator (i, j) back to back.
+      T fa[2][KS], fb[TM][KS];
+      auto fetch = [&](T (&f)[KS], const T* base) {
 #pragma unroll
-      for (int h = 0; h < KS / VEC; ++h) {
-        vec_t fa[TM], fb[TM];
+        for (int h = 0; h < KS / VEC; ++h) {
+          const vec_t v = *reinterpret_cast<const vec_t*>(base + h * VEC);
 #pragma unroll
-        for (int t = 0; t < TM; ++t) {
-          fa[t] = *reinterpret_cast<const vec_t*>(as + t * 16 * S + h * VEC);
-          fb[t] = *reinterpret_cast<const vec_t*>(bs + t * 16 * S + h * VEC);
+          for (int e = 0; e < VEC; ++e) f[h * VEC + e] = v[e];
         }
+      };
+      fetch(fa[0], as);
+      fetch(fb[0], bs);
 #pragma unroll
-        for (int e = 0; e < VEC; ++e)
+      for (int i = 0; i < TM; ++i) {
 #pragma unroll
-          for (int i = 0; i < TM; ++i)
+        for (int j = 0; j < TM; ++j) {
+          if (i == 0 && j + 1 < TM) fetch(fb[j + 1], bs + (j + 1) * 16 * S);
+          if (j == TM - 1 && i + 1 < TM) fetch(fa[(i + 1) & 1], as + (i + 1) * 16 * S);
+          __builtin_amdgcn_sched_barrier(0);   // fetches go out before this stage's products
 #pragma unroll
-            for (int j = 0; j < TM; ++j) acc[i][j] = X::mfma(fa[i][e], fb[j][e], acc[i][j]);
+          for (int e = 0; e < KS; ++e) acc[i][j] = X::mfma(fa[i & 1][e], fb[j][e], acc[i][j]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
     }
     if (kt + 1 < nk) sstore(buf ^ 1);
@@ -205,19 +221,19 @@ template <typename T, bool LOWER>
 __global__ __launch_bounds__(UPD_THREADS) void trailing_update_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nbn) {
-  schur_update_body<T, LOWER, 4>(C, ldc, A, lda, B, ldb, d, M, N, K, nbn);
+  schur_update_body<T, LOWER, 4, 1>(C, ldc, A, lda, B, ldb, d, M, N, K, nbn);
 }
 template <typename T, bool LOWER>
 __global__ __launch_bounds__(UPD_THREADS) void panel_update_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nbn) {
-  schur_update_body<T, LOWER, 4>(C, ldc, A, lda, B, ldb, d, M, N, K, nbn);
+  schur_update_body<T, LOWER, 4, 1>(C, ldc, A, lda, B, ldb, d, M, N, K, nbn);
 }
 template <typename T, bool LOWER>
 __global__ __launch_bounds__(UPD_THREADS) void panel_update64_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nbn) {
-  schur_update_body<T, LOWER, 2>(C, ldc, A, lda, B, ldb, d, M, N, K, nbn);
+  schur_update_body<T, LOWER, 2, 1>(C, ldc, A, lda, B, ldb, d, M, N, K, nbn);
 }
 
 // K = 64 exactly (the update of the columns right of a leaf by that leaf): both
