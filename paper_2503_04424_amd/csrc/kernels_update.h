@@ -27,35 +27,65 @@ namespace mdet {
 
 constexpr int UPD_THREADS = 256;
 
-// Number of tile x tile blocks a launch needs (tile = 128 or 64).
-static inline int64_t update_num_blocks(int64_t M, int64_t N, bool lower, int tile = 128) {
+// Block scheduling.  The C blocks of a launch are grouped into 8 x 8 "super-tiles"
+// (64 blocks that share 8 row strips of A and 8 row strips of B).  Workgroups are
+// dispatched round-robin over the 8 XCDs by linear id, each XCD with its own L2;
+// the map below hands every XCD a contiguous range of super-tiles, so the 64 or so
+// blocks an XCD runs at one time re-use each operand strip eight times out of its
+// L2 instead of fetching it once per block.  Slots of a super-tile that fall
+// outside the matrix or (LOWER) above the diagonal exit at once.
+constexpr int UPD_SUPER = 8;
+
+struct UpdGrid {
+  int64_t nblocks;   // workgroups to launch (multiple of 64)
+  int nsm, nsn;      // super-tile rows / columns
+};
+static inline UpdGrid update_grid(int64_t M, int64_t N, bool lower, int tile) {
   int64_t nbm = (M + tile - 1) / tile, nbn = (N + tile - 1) / tile;
-  if (!lower) return nbm * nbn;
-  int64_t t = nbm < nbn ? nbm : nbn;           // rows inside the triangular part
-  return t * (t + 1) / 2 + (nbm - t) * nbn;
+  UpdGrid g;
+  g.nsm = (int)((nbm + UPD_SUPER - 1) / UPD_SUPER);
+  g.nsn = (int)((nbn + UPD_SUPER - 1) / UPD_SUPER);
+  int64_t nst;
+  if (!lower) nst = (int64_t)g.nsm * g.nsn;
+  else {
+    int64_t t = g.nsm < g.nsn ? g.nsm : g.nsn;          // super-tile rows inside the triangular part
+    nst = t * (t + 1) / 2 + (int64_t)(g.nsm - t) * g.nsn;
+  }
+  g.nblocks = nst * UPD_SUPER * UPD_SUPER;
+  return g;
 }
 
-// Block (bm, bn) of a launch from its linear index: row-major over the lower
-// trapezoid (LOWER) or over the full grid.
+// (bm, bn) of this workgroup, or false if its slot is empty.
 template <bool LOWER>
-__device__ __forceinline__ void update_block_of(int64_t id, int nbn, int& bm, int& bn) {
+__device__ __forceinline__ bool update_block_of(int64_t id, int64_t nblocks, int nbm, int nbn,
+                                                int nsn, int& bm, int& bn) {
+  // contiguous range of slots per XCD
+  const int xcd = (int)(id & 7);
+  const int64_t k = id >> 3, per = nblocks >> 3;        // nblocks is a multiple of 64
+  const int64_t slot = (int64_t)xcd * per + k;
+  const int64_t st = slot >> 6;
+  const int loc = (int)(slot & 63);
+  int sm, sn;
   if (LOWER) {
-    int64_t tri = (int64_t)nbn * (nbn + 1) / 2;
-    if (id < tri) {
-      int64_t r = (int64_t)((sqrt(8.0 * (double)id + 1.0) - 1.0) * 0.5);
-      while (r * (r + 1) / 2 > id) --r;
-      while ((r + 1) * (r + 2) / 2 <= id) ++r;
-      bm = (int)r;
-      bn = (int)(id - r * (r + 1) / 2);
+    int64_t tri = (int64_t)nsn * (nsn + 1) / 2;
+    if (st < tri) {
+      int64_t r = (int64_t)((sqrt(8.0 * (double)st + 1.0) - 1.0) * 0.5);
+      while (r * (r + 1) / 2 > st) --r;
+      while ((r + 1) * (r + 2) / 2 <= st) ++r;
+      sm = (int)r;
+      sn = (int)(st - r * (r + 1) / 2);
     } else {
-      int64_t rest = id - tri;
-      bm = nbn + (int)(rest / nbn);
-      bn = (int)(rest % nbn);
+      int64_t rest = st - tri;
+      sm = nsn + (int)(rest / nsn);
+      sn = (int)(rest % nsn);
     }
   } else {
-    bm = (int)(id / nbn);
-    bn = (int)(id % nbn);
+    sm = (int)(st / nsn);
+    sn = (int)(st % nsn);
   }
+  bm = sm * UPD_SUPER + (loc >> 3);
+  bn = sn * UPD_SUPER + (loc & 7);
+  return bm < nbm && bn < nbn && (!LOWER || bn <= bm);
 }
 
 // TM = MFMA tiles per wavefront in each direction: 4 -> 128 x 128 block, 2 -> 64 x 64.
@@ -67,7 +97,7 @@ template <typename T, bool LOWER, int TM, int SLABS>
 __device__ __forceinline__ void schur_update_body(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K,
-    int nbn) {
+    int nsn) {
   using X = Mfma<T>;
   using acc_t = typename X::acc_t;
   using vec_t = typename X::vec_t;
@@ -84,7 +114,8 @@ __device__ __forceinline__ void schur_update_body(
   __shared__ __attribute__((aligned(16))) T Bs[2][BN * S];
 
   int bm, bn;
-  update_block_of<LOWER>(blockIdx.x, nbn, bm, bn);
+  if (!update_block_of<LOWER>(blockIdx.x, gridDim.x, (M + BM - 1) / BM, (N + BN - 1) / BN, nsn, bm, bn))
+    return;
   const int row0 = bm * BM, col0 = bn * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -220,20 +251,20 @@ __device__ __forceinline__ void schur_update_body(
 template <typename T, bool LOWER>
 __global__ __launch_bounds__(UPD_THREADS) void trailing_update_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
-    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nbn) {
-  schur_update_body<T, LOWER, 4, 1>(C, ldc, A, lda, B, ldb, d, M, N, K, nbn);
+    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nsn) {
+  schur_update_body<T, LOWER, 4, 1>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn);
 }
 template <typename T, bool LOWER>
 __global__ __launch_bounds__(UPD_THREADS) void panel_update_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
-    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nbn) {
-  schur_update_body<T, LOWER, 4, 1>(C, ldc, A, lda, B, ldb, d, M, N, K, nbn);
+    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nsn) {
+  schur_update_body<T, LOWER, 4, 1>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn);
 }
 template <typename T, bool LOWER>
 __global__ __launch_bounds__(UPD_THREADS) void panel_update64_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
-    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nbn) {
-  schur_update_body<T, LOWER, 2, 1>(C, ldc, A, lda, B, ldb, d, M, N, K, nbn);
+    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nsn) {
+  schur_update_body<T, LOWER, 2, 1>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn);
 }
 
 // K = 64 exactly (the update of the columns right of a leaf by that leaf): both
@@ -243,7 +274,7 @@ __global__ __launch_bounds__(UPD_THREADS) void panel_update64_kernel(
 template <typename T, bool LOWER>
 __global__ __launch_bounds__(UPD_THREADS) void leaf_update_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
-    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int nbn) {
+    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int nsn) {
   using X = Mfma<T>;
   using acc_t = typename X::acc_t;
   using vec_t = typename X::vec_t;
@@ -256,7 +287,7 @@ __global__ __launch_bounds__(UPD_THREADS) void leaf_update_kernel(
   __shared__ __attribute__((aligned(16))) T Bs[64 * S];
 
   int bm, bn;
-  update_block_of<LOWER>(blockIdx.x, nbn, bm, bn);
+  if (!update_block_of<LOWER>(blockIdx.x, gridDim.x, (M + 63) / 64, (N + 63) / 64, nsn, bm, bn)) return;
   const int row0 = bm * 64, col0 = bn * 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;

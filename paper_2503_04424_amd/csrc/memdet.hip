@@ -109,6 +109,7 @@ struct Launcher {
   int update(hipStream_t st, T* C, int64_t ldc, const T* A, int64_t lda, const T* B, int64_t ldb,
              const T* d, int64_t M, int64_t N, int64_t K, bool lower, bool trailing = false) {
     if (M <= 0 || N <= 0 || K <= 0) return MDET_OK;
+    if (lower && N > M) N = M;     // columns right of the last row lie above the diagonal
     constexpr int vec = 16 / (int)sizeof(T);
     if (K % 64 != 0 || lda % vec != 0 || ldb % vec != 0 || !aligned16(A) || !aligned16(B) ||
         !aligned16(d) || M > INT32_MAX || N > INT32_MAX || K > INT32_MAX || ldc < N)
@@ -117,10 +118,11 @@ struct Launcher {
     // block column a K = 64 update runs single-shot from LDS and short launches
     // use 64 x 64 blocks so that they reach more compute units
     const bool leaf_k = !trailing && K == 64;
-    const bool small = !trailing && !leaf_k && update_num_blocks(M, N, lower, 128) < 512;
+    const bool small = !trailing && !leaf_k && update_grid(M, N, lower, 128).nblocks < 1024;
     const int tile = (leaf_k || small) ? 64 : 128;
-    int64_t nbn = (N + tile - 1) / tile;
-    int64_t nblk = update_num_blocks(M, N, lower, tile);
+    const UpdGrid ug = update_grid(M, N, lower, tile);
+    const int nbn = ug.nsn;          // super-tile columns (kernel argument)
+    const int64_t nblk = ug.nblocks;
     if (nblk > INT32_MAX) return MDET_EINVAL;
     dim3 grid((unsigned)nblk), block(UPD_THREADS);
     hipEvent_t e0 = nullptr, e1 = nullptr;
