@@ -56,6 +56,25 @@ def form_matrix_host_packed(w, torch, M, out=None):
     return out
 
 
+def measured_traffic(workload):
+    """HBM-side bytes per launch of the trailing update kernel for this workload, from the
+    committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE, scaled by what the same
+    counters read for a plain copy), or None when no summary covers the workload."""
+    path = os.path.join(ROOT, "profiles", "trailing_update_hbm_traffic_cfg2.txt")
+    try:
+        kv = {}
+        for line in open(path):
+            if line.startswith("#") or not line.strip():
+                continue
+            k, v = line.split(None, 1)
+            kv[k] = v.strip()
+        if kv.get("workload") == workload:
+            return float(kv["traffic_bytes_per_dispatch"])
+    except (OSError, KeyError, ValueError):
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -185,7 +204,8 @@ def main():
         "roofline": {
             "kernel": "trailing_update_kernel (Schur update A_ij -= L_ik D_k L_jk^T on MFMA)",
             "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-            "frac": (achieved / peak) if achieved else None, "traffic": None,
+            "frac": (achieved / peak) if achieved else None,
+            "traffic": measured_traffic(w.name) if not (args.n or args.block_size) else None,
             "launches_timed": upd_n,
             "avg_launch_ms": (upd_t / upd_n * 1e3) if upd_n else None,
             "flop_per_launch_avg": (upd_f / upd_n) if upd_n else None,
