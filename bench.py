@@ -86,6 +86,8 @@ def main():
     ap.add_argument("--n", type=int, default=0, help="override the order (scaled-down stand-in)")
     ap.add_argument("--budget-gib", type=float, default=-1.0,
                     help="device budget in GiB; >0 puts the matrix in pinned host memory and streams it")
+    ap.add_argument("--no-lookahead", action="store_true",
+                    help="diagnostic: run every kernel on one stream, nothing overlapped")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0, help="order of the oracle's sample block")
     args = ap.parse_args()
@@ -112,6 +114,7 @@ def main():
     out_of_core = w.mem_budget > 0
 
     steps, warmup = args.steps, args.warmup
+    xflags = M.FLAG_NO_LOOKAHEAD if args.no_lookahead else 0
     results = []
     if not out_of_core:
         a = form_matrix_device(w, torch)
@@ -154,7 +157,7 @@ def main():
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for _ in range(batch):
-                results.append(run(done, flags=M.FLAG_PROFILE, want_diag=True)); done += 1
+                results.append(run(done, flags=M.FLAG_PROFILE | xflags, want_diag=True)); done += 1
             torch.cuda.synchronize()
             t_total += time.perf_counter() - t0
             k += batch
@@ -173,7 +176,7 @@ def main():
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             r = M.mdet_logdet_host(h, n, bs, mem_budget=w.mem_budget, overwrite=True,
-                                   flags=M.FLAG_PROFILE, diag=diag)
+                                   flags=M.FLAG_PROFILE | xflags, diag=diag)
             torch.cuda.synchronize()
             if i >= warmup:
                 t_total += time.perf_counter() - t0

@@ -153,14 +153,27 @@ __device__ __forceinline__ void leaf_invert_sub(const T* tile, T* __restrict__ l
 //                unit-lower diagonal sub-block into `linv` (used by the solve kernel).
 constexpr int FACTOR_THREADS = 256;
 
+// LDS the factorisation needs, in elements: the leaf, its pivots, their reciprocals.
+constexpr int FACTOR_LDS_ELEMS = LEAF * LEAF_PAD + 2 * LEAF;
+
+// The work of all FACTOR_THREADS threads of one workgroup; `lds` points at
+// FACTOR_LDS_ELEMS elements of shared memory nobody else uses.  The update
+// kernels call it too: the workgroup that has just reduced the top-left 64 x 64
+// block of its launch factors that block straight away, which takes one kernel
+// (and its launch-to-launch latency) off the chain of dependent launches.
 template <typename T>
-__global__ __launch_bounds__(FACTOR_THREADS) void leaf_factor_kernel(
+__device__ __forceinline__ void leaf_factor_body(
     T* __restrict__ A, int64_t ld, int w, T* __restrict__ dvec, T* __restrict__ dinv,
-    T* __restrict__ linv, long long pivot0, DevFlags* flags) {
+    T* __restrict__ linv, long long pivot0, DevFlags* flags, T* __restrict__ lds) {
   using X = Mfma<T>;
   using acc_t = typename X::acc_t;
-  __shared__ T tile[LEAF * LEAF_PAD];
-  __shared__ T dsave[LEAF], rsave[LEAF];
+  T* tile = lds;
+  T* dsave = lds + LEAF * LEAF_PAD;
+  T* rsave = dsave + LEAF;
+  // The elimination is one long chain of dependent instructions; beside a
+  // workgroup of the trailing update on the same SIMDs it would otherwise get an
+  // issue slot only now and then.
+  __builtin_amdgcn_s_setprio(3);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
   {
@@ -246,6 +259,15 @@ __global__ __launch_bounds__(FACTOR_THREADS) void leaf_factor_kernel(
     const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
     if (r < w && c <= r) A[(int64_t)r * ld + c] = tile[r * LEAF_PAD + c];
   }
+  __builtin_amdgcn_s_setprio(0);
+}
+
+template <typename T>
+__global__ __launch_bounds__(FACTOR_THREADS) void leaf_factor_kernel(
+    T* __restrict__ A, int64_t ld, int w, T* __restrict__ dvec, T* __restrict__ dinv,
+    T* __restrict__ linv, long long pivot0, DevFlags* flags) {
+  __shared__ T lds[FACTOR_LDS_ELEMS];
+  leaf_factor_body<T>(A, ld, w, dvec, dinv, linv, pivot0, flags, lds);
 }
 
 // ---------------------------------------------------------------------------
@@ -270,6 +292,7 @@ __global__ __launch_bounds__(256) void leaf_solve_kernel(
   __shared__ T rinv[LEAF];
   __shared__ T wsc[4][SUB * LEAF_PAD];          // per wavefront: solved W, row-major
   __shared__ T tsc[4][SUB * SUB_PAD];           // per wavefront: layout change of T_b
+  __builtin_amdgcn_s_setprio(2);                // on the chain of dependent launches
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
 

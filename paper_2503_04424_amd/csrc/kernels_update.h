@@ -21,6 +21,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "kernels_leaf.h"
 #include "mfma.h"
 
 namespace mdet {
@@ -28,76 +29,144 @@ namespace mdet {
 constexpr int UPD_THREADS = 256;
 
 // Block scheduling.  The C blocks of a launch are grouped into 8 x 8 "super-tiles"
-// (64 blocks that share 8 row strips of A and 8 row strips of B).  Workgroups are
-// dispatched round-robin over the 8 XCDs by linear id, each XCD with its own L2;
-// the map below hands every XCD a contiguous range of super-tiles, so the 64 or so
-// blocks an XCD runs at one time re-use each operand strip eight times out of its
-// L2 instead of fetching it once per block.  Slots of a super-tile that fall
-// outside the matrix or (LOWER) above the diagonal exit at once.
+// (64 blocks that share 8 row strips of A and 8 row strips of B) and numbered
+// super-tile by super-tile; of a lower-triangular launch only the blocks on or
+// below the diagonal get a number (36 of a super-tile on the diagonal).
+// Workgroups are dispatched round-robin over the 8 XCDs by linear id, each XCD
+// with its own L2; the map below hands every XCD a contiguous range of block
+// numbers, so the 64 or so blocks an XCD runs at one time re-use each operand
+// strip eight times out of its L2 instead of fetching it once per block.  Numbers
+// that fall outside a ragged edge exit at once.  A launch at most four blocks wide
+// (the updates inside a block column) has no use for super-tiles: its blocks are
+// numbered row by row.
+//
+// A launch may cover only part of the numbers: workgroup id takes number
+// xcd * per + k0 + (id >> 3) with xcd = id & 7, so that a sequence of launches with
+// growing k0 walks every XCD's range in order (used to keep part of the device
+// free for the kernels of another stream).
 constexpr int UPD_SUPER = 8;
+constexpr int UPD_SUPER_LOG2 = 3;
+constexpr int UPD_SUPER_TRI = UPD_SUPER * (UPD_SUPER + 1) / 2;   // blocks of a diagonal super-tile
 
 struct UpdGrid {
-  int64_t nblocks;   // workgroups to launch (multiple of 64)
-  int nsm, nsn;      // super-tile rows / columns
+  int64_t per;       // block numbers per XCD; a full launch has 8 * per workgroups
+  int nsn;           // super-tile columns (super-tile mode)
+  int swl;           // 3: 8 x 8 super-tiles; 0..2: rows of 1 << swl blocks, no super-tiles
 };
 static inline UpdGrid update_grid(int64_t M, int64_t N, bool lower, int tile) {
   int64_t nbm = (M + tile - 1) / tile, nbn = (N + tile - 1) / tile;
   UpdGrid g;
-  g.nsm = (int)((nbm + UPD_SUPER - 1) / UPD_SUPER);
-  g.nsn = (int)((nbn + UPD_SUPER - 1) / UPD_SUPER);
-  int64_t nst;
-  if (!lower) nst = (int64_t)g.nsm * g.nsn;
-  else {
-    int64_t t = g.nsm < g.nsn ? g.nsm : g.nsn;          // super-tile rows inside the triangular part
-    nst = t * (t + 1) / 2 + (int64_t)(g.nsm - t) * g.nsn;
+  int64_t count;
+  if (nbn <= 4) {
+    g.swl = nbn <= 1 ? 0 : (nbn <= 2 ? 1 : 2);
+    g.nsn = 1;
+    count = nbm << g.swl;
+  } else {
+    g.swl = UPD_SUPER_LOG2;
+    const int64_t nsm = (nbm + UPD_SUPER - 1) / UPD_SUPER;
+    g.nsn = (int)((nbn + UPD_SUPER - 1) / UPD_SUPER);
+    if (!lower) count = nsm * g.nsn * 64;
+    else {
+      const int64_t t = nsm < g.nsn ? nsm : g.nsn;      // super-tile rows that reach the diagonal
+      count = 32 * t * t + 4 * t + (nsm - t) * g.nsn * 64;
+    }
   }
-  g.nblocks = nst * UPD_SUPER * UPD_SUPER;
+  g.per = (count + 7) / 8;
   return g;
 }
 
-// (bm, bn) of this workgroup, or false if its slot is empty.
-template <bool LOWER>
-__device__ __forceinline__ bool update_block_of(int64_t id, int64_t nblocks, int nbm, int nbn,
-                                                int nsn, int& bm, int& bn) {
-  // contiguous range of slots per XCD
-  const int xcd = (int)(id & 7);
-  const int64_t k = id >> 3, per = nblocks >> 3;        // nblocks is a multiple of 64
-  const int64_t slot = (int64_t)xcd * per + k;
-  const int64_t st = slot >> 6;
-  const int loc = (int)(slot & 63);
-  int sm, sn;
-  if (LOWER) {
-    int64_t tri = (int64_t)nsn * (nsn + 1) / 2;
-    if (st < tri) {
-      int64_t r = (int64_t)((sqrt(8.0 * (double)st + 1.0) - 1.0) * 0.5);
-      while (r * (r + 1) / 2 > st) --r;
-      while ((r + 1) * (r + 2) / 2 <= st) ++r;
-      sm = (int)r;
-      sn = (int)(st - r * (r + 1) / 2);
+// (bm, bn) of block number t, or false if there is no such block.  Number 0 is
+// block (0, 0).
+__host__ __device__ __forceinline__ bool update_block_of_number(const bool lower, const int64_t t, int nbm,
+                                                       int nbn, int nsn, int swl, int& bm, int& bn) {
+  if (swl < UPD_SUPER_LOG2) {
+    bm = (int)(t >> swl);
+    bn = (int)(t & ((1 << swl) - 1));
+    return bm < nbm && bn < nbn && (!lower || bn <= bm);
+  }
+  if (!lower) {
+    const int64_t st = t >> 6;
+    const int loc = (int)(t & 63);
+    bm = (int)(st / nsn) * UPD_SUPER + (loc >> 3);
+    bn = (int)(st % nsn) * UPD_SUPER + (loc & 7);
+    return bm < nbm && bn < nbn;
+  }
+  // super-tile row r < nsn holds r full super-tiles and the diagonal one:
+  // 64 r + 36 blocks, 32 r^2 + 4 r before it
+  const int64_t tri_total = 32 * (int64_t)nsn * nsn + 4 * (int64_t)nsn;
+  if (t < tri_total) {
+    int64_t r = (int64_t)((sqrt(16.0 + 128.0 * (double)t) - 4.0) * (1.0 / 64.0));
+    while (32 * r * r + 4 * r > t) --r;
+    while (32 * (r + 1) * (r + 1) + 4 * (r + 1) <= t) ++r;
+    const int64_t u = t - (32 * r * r + 4 * r);
+    if (u < 64 * r) {
+      const int loc = (int)(u & 63);
+      bm = (int)r * UPD_SUPER + (loc >> 3);
+      bn = (int)(u >> 6) * UPD_SUPER + (loc & 7);
     } else {
-      int64_t rest = st - tri;
-      sm = nsn + (int)(rest / nsn);
-      sn = (int)(rest % nsn);
+      const int v = (int)(u - 64 * r);               // 0 .. 35, row by row of the triangle
+      int i = (int)((sqrtf(8.0f * (float)v + 1.0f) - 1.0f) * 0.5f);
+      while (i * (i + 1) / 2 > v) --i;
+      while ((i + 1) * (i + 2) / 2 <= v) ++i;
+      bm = (int)r * UPD_SUPER + i;
+      bn = (int)r * UPD_SUPER + (v - i * (i + 1) / 2);
     }
   } else {
-    sm = (int)(st / nsn);
-    sn = (int)(st % nsn);
+    const int64_t u = t - tri_total;
+    const int64_t row = u / (64 * (int64_t)nsn), w = u % (64 * (int64_t)nsn);
+    const int loc = (int)(w & 63);
+    bm = (nsn + (int)row) * UPD_SUPER + (loc >> 3);
+    bn = (int)(w >> 6) * UPD_SUPER + (loc & 7);
   }
-  bm = sm * UPD_SUPER + (loc >> 3);
-  bn = sn * UPD_SUPER + (loc & 7);
-  return bm < nbm && bn < nbn && (!LOWER || bn <= bm);
+  return bm < nbm && bn < nbn && bn <= bm;
 }
+
+// Block of workgroup `id` in a launch that starts at the k0-th number of every
+// XCD's range of `per` numbers.
+__device__ __forceinline__ bool update_block_of(const bool lower, int64_t id, int64_t per, int64_t k0,
+                                                int nbm, int nbn, int nsn, int swl, int& bm, int& bn) {
+  const int xcd = (int)(id & 7);
+  const int64_t k = k0 + (id >> 3);
+  if (k >= per) return false;
+  return update_block_of_number(lower, (int64_t)xcd * per + k, nbm, nbn, nsn, swl, bm, bn);
+}
+
+// Optional tail of a lower-triangular launch: the factorisation of the leaf that starts at
+// C's top-left corner (w = 0: none), done by the workgroup that reduced that
+// block.  Pointers as for leaf_factor_kernel.
+template <typename T>
+struct FusedLeaf {
+  int w;
+  T* dvec;
+  T* dinv;
+  T* linv;
+  long long pivot0;
+  DevFlags* flags;
+};
 
 // TM = MFMA tiles per wavefront in each direction: 4 -> 128 x 128 block, 2 -> 64 x 64.
 // SLABS = number of 128-byte K slabs staged per pipeline step (1 or 2).  A longer
 // step lets each accumulator take more consecutive MFMAs: on gfx950 every switch
 // of the fp64 MFMA accumulator costs about one extra MFMA time, so 16 tiles x 8
 // chained products waste 1/9 of the matrix pipe where 16 x 4 waste 1/5.
-template <typename T, bool LOWER, int TM, int SLABS>
-__device__ __forceinline__ void schur_update_body(
+template <typename T, int TM, int SLABS>
+struct UpdShape {
+  using X = Mfma<T>;
+  static constexpr int BK = X::BK * SLABS;
+  static constexpr int S = (128 * SLABS + 16) / (int)sizeof(T);   // LDS row stride in elements (padded)
+  static constexpr int BM = 32 * TM, BN = 32 * TM;                // block of C per workgroup
+  static constexpr int LDS_ELEMS = 2 * BM * S + 2 * BN * S;       // both operands, double buffered
+  static_assert(LDS_ELEMS >= FACTOR_LDS_ELEMS, "the fused leaf needs the operand buffers");
+};
+
+// One block (bm, bn) of C, by all threads of the workgroup; `lds` = LDS_ELEMS
+// elements.  Every thread returns from it (there are barriers inside), so a
+// workgroup may call it for one block after another.
+template <typename T, int TM, int SLABS>
+__device__ __forceinline__ void schur_update_block(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K,
-    int nsn) {
+    const bool lower, const int bm, const int bn, const FusedLeaf<T>& fl, T* __restrict__ lds) {
   using X = Mfma<T>;
   using acc_t = typename X::acc_t;
   using vec_t = typename X::vec_t;
@@ -110,17 +179,14 @@ __device__ __forceinline__ void schur_update_body(
   constexpr int NV = BM / RPS;                        // steps (= vectors per thread per operand)
   constexpr int KS = BK / 4;                          // MFMA k-steps per slab
 
-  __shared__ __attribute__((aligned(16))) T As[2][BM * S];
-  __shared__ __attribute__((aligned(16))) T Bs[2][BN * S];
+  T (*As)[BM * S] = reinterpret_cast<T (*)[BM * S]>(lds);
+  T (*Bs)[BN * S] = reinterpret_cast<T (*)[BN * S]>(lds + 2 * BM * S);
 
-  int bm, bn;
-  if (!update_block_of<LOWER>(blockIdx.x, gridDim.x, (M + BM - 1) / BM, (N + BN - 1) / BN, nsn, bm, bn))
-    return;
   const int row0 = bm * BM, col0 = bn * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   // a wavefront whose 64 x 64 piece lies strictly above the diagonal has nothing to do
-  const bool active = !(LOWER && (row0 + wm * WT + WT - 1 < col0 + wn * WT));
+  const bool active = !(lower && (row0 + wm * WT + WT - 1 < col0 + wn * WT));
 
   // ---- global -> register staging ---------------------------------------
   // VPR consecutive lanes read one whole staged row (BK elements, 128 or 256
@@ -173,7 +239,7 @@ __device__ __forceinline__ void schur_update_body(
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
           const int gcol = col0 + wn * WT + j * 16 + r16;
-          if (gcol < N && (!LOWER || gcol <= grow)) acc[i][j][r] = crow[gcol];
+          if (gcol < N && (!lower || gcol <= grow)) acc[i][j][r] = crow[gcol];
         }
       }
     }
@@ -227,54 +293,84 @@ __device__ __forceinline__ void schur_update_body(
   }
 
   // ---- epilogue: store the reduced block ----------------------------------
-  if (!active) return;
+  if (active) {
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int grow = row0 + wm * WT + i * 16 + X::acc_row(lane, r);
-      if (grow >= M) continue;
-      T* crow = C + (int64_t)grow * ldc;
+      for (int r = 0; r < 4; ++r) {
+        const int grow = row0 + wm * WT + i * 16 + X::acc_row(lane, r);
+        if (grow >= M) continue;
+        T* crow = C + (int64_t)grow * ldc;
 #pragma unroll
-      for (int j = 0; j < TM; ++j) {
-        const int gcol = col0 + wn * WT + j * 16 + r16;
-        if (gcol < N && (!LOWER || gcol <= grow)) crow[gcol] = acc[i][j][r];
+        for (int j = 0; j < TM; ++j) {
+          const int gcol = col0 + wn * WT + j * 16 + r16;
+          if (gcol < N && (!lower || gcol <= grow)) crow[gcol] = acc[i][j][r];
+        }
       }
     }
   }
+  if (lower && fl.w > 0 && bm == 0 && bn == 0) {
+    __syncthreads();   // the block's stores are visible to the whole workgroup, LDS is free
+    leaf_factor_body<T>(C, ldc, fl.w, fl.dvec, fl.dinv, fl.linv, fl.pivot0, fl.flags, lds);
+  }
+}
+
+// One block per workgroup.
+template <typename T, int TM, int SLABS>
+__device__ __forceinline__ void schur_update_body(
+    T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
+    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K,
+    int nsn, int swl, const bool lower, int per, int k0, const FusedLeaf<T>& fl) {
+  using Sh = UpdShape<T, TM, SLABS>;
+  __shared__ __attribute__((aligned(16))) T lds[Sh::LDS_ELEMS];
+  int bm, bn;
+  if (!update_block_of(lower, blockIdx.x, per, k0, (M + Sh::BM - 1) / Sh::BM,
+                       (N + Sh::BN - 1) / Sh::BN, nsn, swl, bm, bn))
+    return;
+  schur_update_block<T, TM, SLABS>(C, ldc, A, lda, B, ldb, d, M, N, K, lower, bm, bn, fl, lds);
 }
 
 // Names for the same body: the update of the trailing matrix by a finished block
 // column (the bulk of all work), and the updates inside a block column's own
 // recursive factorisation (128- and 64-wide blocks; the small one spreads short
-// launches over more compute units).
-template <typename T, bool LOWER>
+// launches over more compute units).  The latter sit on the chain of dependent
+// launches and often share SIMDs with a workgroup of the former: they run at a
+// raised wave priority.
+template <typename T>
 __global__ __launch_bounds__(UPD_THREADS) void trailing_update_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
-    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nsn) {
-  schur_update_body<T, LOWER, 4, 1>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn);
+    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nsn,
+    int swl, int lower, int per, int k0, FusedLeaf<T> fl) {
+  schur_update_body<T, 4, 1>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn, swl, lower != 0, per, k0, fl);
 }
-template <typename T, bool LOWER>
+template <typename T>
 __global__ __launch_bounds__(UPD_THREADS) void panel_update_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
-    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nsn) {
-  schur_update_body<T, LOWER, 4, 1>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn);
+    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nsn,
+    int swl, int lower, int per, int k0, FusedLeaf<T> fl) {
+  __builtin_amdgcn_s_setprio(2);
+  schur_update_body<T, 4, 1>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn, swl, lower != 0, per, k0, fl);
 }
-template <typename T, bool LOWER>
+template <typename T>
 __global__ __launch_bounds__(UPD_THREADS) void panel_update64_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
-    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nsn) {
-  schur_update_body<T, LOWER, 2, 1>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn);
+    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nsn,
+    int swl, int lower, int per, int k0, FusedLeaf<T> fl) {
+  __builtin_amdgcn_s_setprio(2);
+  schur_update_body<T, 2, 1>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn, swl, lower != 0, per, k0, fl);
 }
 
 // K = 64 exactly (the update of the columns right of a leaf by that leaf): both
 // operands, the pivots and the C block are requested in one go and the whole
 // product runs from LDS, so the launch costs one memory round trip instead of one
 // per slab.  64 x 64 block of C per workgroup, 2 x 2 MFMA tiles per wavefront.
-template <typename T, bool LOWER>
+template <typename T>
 __global__ __launch_bounds__(UPD_THREADS) void leaf_update_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
-    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int nsn) {
+    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int nsn, int swl,
+    int lower_, int per, FusedLeaf<T> fl) {
+  __builtin_amdgcn_s_setprio(2);
+  const bool lower = lower_ != 0;
   using X = Mfma<T>;
   using acc_t = typename X::acc_t;
   using vec_t = typename X::vec_t;
@@ -283,16 +379,19 @@ __global__ __launch_bounds__(UPD_THREADS) void leaf_update_kernel(
   constexpr int S = (KT * (int)sizeof(T) + 16) / (int)sizeof(T);   // padded LDS row, elements
   constexpr int VPR = KT / VEC;                             // 16-byte vectors per row
   constexpr int NV = VPR / 4;                               // per thread (4 threads per row)
-  __shared__ __attribute__((aligned(16))) T As[64 * S];
-  __shared__ __attribute__((aligned(16))) T Bs[64 * S];
+  __shared__ __attribute__((aligned(16))) T lds[2 * 64 * S];
+  static_assert(2 * 64 * S >= FACTOR_LDS_ELEMS, "the fused leaf needs the operand buffers");
+  T* As = lds;
+  T* Bs = lds + 64 * S;
 
   int bm, bn;
-  if (!update_block_of<LOWER>(blockIdx.x, gridDim.x, (M + 63) / 64, (N + 63) / 64, nsn, bm, bn)) return;
+  if (!update_block_of(lower, blockIdx.x, per, 0, (M + 63) / 64, (N + 63) / 64, nsn, swl, bm, bn))
+    return;
   const int row0 = bm * 64, col0 = bn * 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int r16 = lane & 15, g = lane >> 4;
-  const bool active = !(LOWER && (row0 + wm * 32 + 31 < col0 + wn * 32));
+  const bool active = !(lower && (row0 + wm * 32 + 31 < col0 + wn * 32));
 
   const int srow = tid >> 2, sq = tid & 3;
   int ar = row0 + srow; if (ar > M - 1) ar = M - 1;
@@ -323,7 +422,7 @@ __global__ __launch_bounds__(UPD_THREADS) void leaf_update_kernel(
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
           const int gcol = col0 + wn * 32 + j * 16 + r16;
-          if (gcol < N && (!LOWER || gcol <= grow)) acc[i][j][r] = crow[gcol];
+          if (gcol < N && (!lower || gcol <= grow)) acc[i][j][r] = crow[gcol];
         }
       }
   }
@@ -337,40 +436,45 @@ __global__ __launch_bounds__(UPD_THREADS) void leaf_update_kernel(
     }
   }
   __syncthreads();
-  if (!active) return;
+  if (active) {
 #pragma unroll
-  for (int slab = 0; slab < KT / BK; ++slab) {
-    const T* as = &As[(wm * 32 + r16) * S + slab * BK + g * KS];
-    const T* bs = &Bs[(wn * 32 + r16) * S + slab * BK + g * KS];
+    for (int slab = 0; slab < KT / BK; ++slab) {
+      const T* as = &As[(wm * 32 + r16) * S + slab * BK + g * KS];
+      const T* bs = &Bs[(wn * 32 + r16) * S + slab * BK + g * KS];
 #pragma unroll
-    for (int h = 0; h < KS / VEC; ++h) {
-      vec_t fa[2], fb[2];
+      for (int h = 0; h < KS / VEC; ++h) {
+        vec_t fa[2], fb[2];
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        fa[t] = *reinterpret_cast<const vec_t*>(as + t * 16 * S + h * VEC);
-        fb[t] = *reinterpret_cast<const vec_t*>(bs + t * 16 * S + h * VEC);
+        for (int t = 0; t < 2; ++t) {
+          fa[t] = *reinterpret_cast<const vec_t*>(as + t * 16 * S + h * VEC);
+          fb[t] = *reinterpret_cast<const vec_t*>(bs + t * 16 * S + h * VEC);
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i][j] = X::mfma(fa[i][e], fb[j][e], acc[i][j]);
       }
-#pragma unroll
-      for (int e = 0; e < VEC; ++e)
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-          for (int j = 0; j < 2; ++j) acc[i][j] = X::mfma(fa[i][e], fb[j][e], acc[i][j]);
     }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int grow = row0 + wm * 32 + i * 16 + X::acc_row(lane, r);
+        if (grow >= M) continue;
+        T* crow = C + (int64_t)grow * ldc;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int gcol = col0 + wn * 32 + j * 16 + r16;
+          if (gcol < N && (!lower || gcol <= grow)) crow[gcol] = acc[i][j][r];
+        }
+      }
   }
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int grow = row0 + wm * 32 + i * 16 + X::acc_row(lane, r);
-      if (grow >= M) continue;
-      T* crow = C + (int64_t)grow * ldc;
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int gcol = col0 + wn * 32 + j * 16 + r16;
-        if (gcol < N && (!LOWER || gcol <= grow)) crow[gcol] = acc[i][j][r];
-      }
-    }
+  if (lower && fl.w > 0 && bm == 0 && bn == 0) {
+    __syncthreads();
+    leaf_factor_body<T>(C, ldc, fl.w, fl.dvec, fl.dinv, fl.linv, fl.pivot0, fl.flags, lds);
+  }
 }
 
 }  // namespace mdet

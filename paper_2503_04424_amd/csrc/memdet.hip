@@ -93,6 +93,7 @@ struct Launcher {
   T* dinv = nullptr;
   T* linv = nullptr;          // inverses of the current leaf's diagonal sub-blocks
   DevFlags* flags = nullptr;
+  int slots = 0;              // trailing-update workgroups the device holds at one time
   double fma = 0.0;
   uint64_t launches = 0;
   // optional timing of the trailing-update launches (MDET_FLAG_PROFILE)
@@ -106,8 +107,12 @@ struct Launcher {
   // trailing = true marks the Schur update of the trailing matrix by a whole block
   // column (as opposed to the updates inside a block column's own factorisation);
   // it runs the same code under its own kernel name so profiles tell them apart.
+  // fuse: the launch also factors the leaf at C's top-left corner (lower only).
+  // leave_free >= 0 (trailing only): several launches in a row, each that many
+  // workgroups short of what the device holds, so that other streams' kernels find room.
   int update(hipStream_t st, T* C, int64_t ldc, const T* A, int64_t lda, const T* B, int64_t ldb,
-             const T* d, int64_t M, int64_t N, int64_t K, bool lower, bool trailing = false) {
+             const T* d, int64_t M, int64_t N, int64_t K, bool lower, bool trailing = false,
+             const FusedLeaf<T>* fuse = nullptr, int leave_free = -1) {
     if (M <= 0 || N <= 0 || K <= 0) return MDET_OK;
     if (lower && N > M) N = M;     // columns right of the last row lie above the diagonal
     constexpr int vec = 16 / (int)sizeof(T);
@@ -118,42 +123,48 @@ struct Launcher {
     // block column a K = 64 update runs single-shot from LDS and short launches
     // use 64 x 64 blocks so that they reach more compute units
     const bool leaf_k = !trailing && K == 64;
-    const bool small = !trailing && !leaf_k && update_grid(M, N, lower, 128).nblocks < 1024;
+    const bool small = !trailing && !leaf_k && 8 * update_grid(M, N, lower, 128).per < 1024;
     const int tile = (leaf_k || small) ? 64 : 128;
     const UpdGrid ug = update_grid(M, N, lower, tile);
-    const int nbn = ug.nsn;          // super-tile columns (kernel argument)
-    const int64_t nblk = ug.nblocks;
-    if (nblk > INT32_MAX) return MDET_EINVAL;
-    dim3 grid((unsigned)nblk), block(UPD_THREADS);
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    const bool timed = profile && trailing;
-    if (timed) {
-      fail->check(hipEventCreate(&e0));
-      fail->check(hipEventCreate(&e1));
-      fail->check(hipEventRecord(e0, st));
+    if (8 * ug.per > INT32_MAX) return MDET_EINVAL;
+    FusedLeaf<T> fl{0, nullptr, nullptr, nullptr, 0, nullptr};
+    if (fuse) {
+      if (!lower || fuse->w > LEAF || fuse->w > N || fuse->w > M) return MDET_EINVAL;
+      fl = *fuse;
     }
+    // workgroups per launch and XCD: everything at once, or rounds that fill all but
+    // leave_free of the device's slots
+    int64_t per_launch = ug.per;
+    if (trailing && leave_free >= 0 && slots - leave_free >= 8 && 8 * ug.per > slots - leave_free)
+      per_launch = (slots - leave_free) / 8;
+    dim3 block(UPD_THREADS);
+    const bool timed = profile && trailing;
+    for (int64_t k0 = 0; k0 < ug.per; k0 += per_launch) {
+      const int64_t kn = ug.per - k0 < per_launch ? ug.per - k0 : per_launch;
+      dim3 grid((unsigned)(8 * kn));
+      hipEvent_t e0 = nullptr, e1 = nullptr;
+      if (timed) {
+        fail->check(hipEventCreate(&e0));
+        fail->check(hipEventCreate(&e1));
+        fail->check(hipEventRecord(e0, st));
+      }
 #define MDET_LAUNCH_UPD(KERNEL)                                                                   \
-  do {                                                                                            \
-    if (lower)                                                                                    \
-      hipLaunchKernelGGL((KERNEL<T, true>), grid, block, 0, st, C, ldc, A, lda, B, ldb, d, (int)M, \
-                         (int)N, (int)K, (int)nbn);                                               \
-    else                                                                                          \
-      hipLaunchKernelGGL((KERNEL<T, false>), grid, block, 0, st, C, ldc, A, lda, B, ldb, d,       \
-                         (int)M, (int)N, (int)K, (int)nbn);                                       \
-  } while (0)
-    if (trailing) MDET_LAUNCH_UPD(trailing_update_kernel);
-    else if (leaf_k) {
-      if (lower)
-        hipLaunchKernelGGL((leaf_update_kernel<T, true>), grid, block, 0, st, C, ldc, A, lda, B, ldb,
-                           d, (int)M, (int)N, (int)nbn);
-      else
-        hipLaunchKernelGGL((leaf_update_kernel<T, false>), grid, block, 0, st, C, ldc, A, lda, B,
-                           ldb, d, (int)M, (int)N, (int)nbn);
-    } else if (small) MDET_LAUNCH_UPD(panel_update64_kernel);
-    else MDET_LAUNCH_UPD(panel_update_kernel);
+  hipLaunchKernelGGL((KERNEL<T>), grid, block, 0, st, C, ldc, A, lda, B, ldb, d, (int)M, (int)N,  \
+                     (int)K, ug.nsn, ug.swl, (int)lower, (int)ug.per, (int)k0, fl)
+      if (trailing) MDET_LAUNCH_UPD(trailing_update_kernel);
+      else if (leaf_k)
+        hipLaunchKernelGGL((leaf_update_kernel<T>), grid, block, 0, st, C, ldc, A, lda, B, ldb, d,
+                           (int)M, (int)N, ug.nsn, ug.swl, (int)lower, (int)ug.per, fl);
+      else if (small) MDET_LAUNCH_UPD(panel_update64_kernel);
+      else MDET_LAUNCH_UPD(panel_update_kernel);
 #undef MDET_LAUNCH_UPD
+      ++launches;
+      if (timed) {
+        fail->check(hipEventRecord(e1, st));
+        prof_events.emplace_back(e0, e1);
+      }
+    }
     fail->check(hipGetLastError());
-    ++launches;
     double f;
     if (lower) {
       // entries (r, c), c <= r, of an M x N trapezoid whose (0,0) is on the diagonal
@@ -163,23 +174,39 @@ struct Launcher {
       f = (double)M * (double)N * (double)K;
     }
     fma += f;
-    if (timed) {
-      fail->check(hipEventRecord(e1, st));
-      prof_events.emplace_back(e0, e1);
-      prof_fma += f;
-    }
+    if (timed) prof_fma += f;
     return MDET_OK;
   }
 
+  // Workgroup slots the bulk update leaves to the factorisation of a block column
+  // of m rows that runs beside it; -1: none, the update is one launch.  Leaving
+  // room pays while that factorisation is a chain of short, latency-bound kernels
+  // (measured: a gain up to about 8192 rows, a small loss at 16384 and beyond, where
+  // its own updates are large enough to want the whole device in turn).
+  int leave_free_for(int64_t m) const {
+    if (slots <= 0 || m > 8192) return -1;
+    return slots / 8;
+  }
+
+  // What an update launch needs to factor the leaf of width w whose first pivot has
+  // index d0 (see FusedLeaf).
+  FusedLeaf<T> fused_leaf(int64_t w, int64_t d0) const {
+    return FusedLeaf<T>{(int)(w < LEAF ? w : LEAF), dvec + d0, dinv + d0, linv, (long long)d0, flags};
+  }
+
   // Factor block column: P at its diagonal entry, m rows, w columns (w <= m).
-  // d0: index of its first pivot in dvec/dinv.
-  int factor_cols(hipStream_t st, T* P, int64_t ld, int64_t m, int64_t w, int64_t d0) {
+  // d0: index of its first pivot in dvec/dinv.  first_done: the first leaf has
+  // been factored already, by the update launch that produced it.
+  int factor_cols(hipStream_t st, T* P, int64_t ld, int64_t m, int64_t w, int64_t d0,
+                  bool first_done = false) {
     if (w <= 0) return MDET_OK;
     if (w <= LEAF) {
-      hipLaunchKernelGGL((leaf_factor_kernel<T>), dim3(1), dim3(FACTOR_THREADS), 0, st, P, ld, (int)w,
-                         dvec + d0, dinv + d0, linv, (long long)d0, flags);
-      fail->check(hipGetLastError());
-      ++launches;
+      if (!first_done) {
+        hipLaunchKernelGGL((leaf_factor_kernel<T>), dim3(1), dim3(FACTOR_THREADS), 0, st, P, ld,
+                           (int)w, dvec + d0, dinv + d0, linv, (long long)d0, flags);
+        fail->check(hipGetLastError());
+        ++launches;
+      }
       fma += ((double)w * w * w - (double)w) / 6.0;
       int64_t below = m - w;
       if (below > 0) {
@@ -197,14 +224,16 @@ struct Launcher {
     // split at a multiple of the leaf width nearest the middle
     int64_t leaves = (w + LEAF - 1) / LEAF;
     int64_t w1 = (leaves / 2) * LEAF;
-    int rc = factor_cols(st, P, ld, m, w1, d0);
+    int rc = factor_cols(st, P, ld, m, w1, d0, first_done);
     if (rc != MDET_OK) return rc;
-    // columns [w1, w), rows [w1, m)  -=  L[rows, 0:w1] D L[cols, 0:w1]^T
+    // columns [w1, w), rows [w1, m)  -=  L[rows, 0:w1] D L[cols, 0:w1]^T, and the
+    // first leaf of those columns factored by the same launch
     T* C = P + w1 * ld + w1;
     const T* A = P + w1 * ld;
-    rc = update(st, C, ld, A, ld, A, ld, dvec + d0, m - w1, w - w1, w1, true);
+    const FusedLeaf<T> fl = fused_leaf(w - w1, d0 + w1);
+    rc = update(st, C, ld, A, ld, A, ld, dvec + d0, m - w1, w - w1, w1, true, false, &fl);
     if (rc != MDET_OK) return rc;
-    return factor_cols(st, C, ld, m - w1, w - w1, d0 + w1);
+    return factor_cols(st, C, ld, m - w1, w - w1, d0 + w1, true);
   }
 
   // After all streams are idle: sum of the timed launches' durations (seconds).
@@ -271,12 +300,20 @@ static int factor_resident(Launcher<T>& L, const Plan& pl, std::vector<ColRef<T>
     const int64_t wk = pl.col_width(k);
     const int64_t mk = n - k * bs;
     touch(s0, k);
-    int rc = L.factor_cols(s0, cols[k].base, cols[k].ld, mk, wk, k * bs);
+    // every column but the group's first had its first leaf factored by the update
+    // launch that finished it
+    int rc = L.factor_cols(s0, cols[k].base, cols[k].ld, mk, wk, k * bs, k > jb);
     if (rc != MDET_OK) return rc;
     if (hooks && hooks->column_final) hooks->column_final(k);
     if (k + 1 >= je) break;
+    // While the rest of the trailing matrix is updated on the side stream, the next
+    // block column is factored on the panel stream.  For a short block column that
+    // is a chain of small kernels with little work each: the bulk update then runs
+    // in rounds that leave them room, and starts once the next column's own update
+    // (which wants the whole device) is through.
+    const int leave_free = lookahead && k + 2 < je ? L.leave_free_for(mk - wk) : -1;
     hipEvent_t ev_panel = nullptr;
-    if (lookahead && k + 2 < je) {
+    if (lookahead && k + 2 < je && leave_free < 0) {
       ev_panel = events.get();
       L.fail->check(hipEventRecord(ev_panel, s0));
     }
@@ -286,9 +323,14 @@ static int factor_resident(Launcher<T>& L, const Plan& pl, std::vector<ColRef<T>
       const int64_t j = k + 1;
       touch(s0, j);
       const T* A = cols[k].base + (j - k) * bs * cols[k].ld;
+      const FusedLeaf<T> fl = L.fused_leaf(pl.col_width(j), j * bs);
       rc = L.update(s0, cols[j].base, cols[j].ld, A, cols[k].ld, A, cols[k].ld, L.dvec + k * bs,
-                    n - j * bs, pl.col_width(j), wk, true, true);
+                    n - j * bs, pl.col_width(j), wk, true, true, &fl);
       if (rc != MDET_OK) return rc;
+    }
+    if (lookahead && k + 2 < je && leave_free >= 0) {
+      ev_panel = events.get();
+      L.fail->check(hipEventRecord(ev_panel, s0));
     }
     if (k + 2 < je) {
       if (lookahead) L.fail->check(hipStreamWaitEvent(s1, ev_panel, 0));
@@ -298,14 +340,15 @@ static int factor_resident(Launcher<T>& L, const Plan& pl, std::vector<ColRef<T>
         // all remaining resident columns in one launch (they are contiguous in memory)
         int64_t ncols = (je < pl.T ? je * bs : n) - j * bs;
         rc = L.update(s1, cols[j].base, cols[j].ld, A, cols[k].ld, A, cols[k].ld, L.dvec + k * bs,
-                      n - j * bs, ncols, wk, true, true);
+                      n - j * bs, ncols, wk, true, true, nullptr, leave_free);
         if (rc != MDET_OK) return rc;
       } else {
         for (int64_t j = k + 2; j < je; ++j) {
           touch(s1, j);
           const T* A = cols[k].base + (j - k) * bs * cols[k].ld;
           rc = L.update(s1, cols[j].base, cols[j].ld, A, cols[k].ld, A, cols[k].ld,
-                        L.dvec + k * bs, n - j * bs, pl.col_width(j), wk, true, true);
+                        L.dvec + k * bs, n - j * bs, pl.col_width(j), wk, true, true, nullptr,
+                        leave_free);
           if (rc != MDET_OK) return rc;
         }
       }
@@ -391,6 +434,11 @@ static void bind_small(Launcher<T>& L, char* base, const SmallArea& sa) {
   L.dinv = (T*)(base + sa.dinv);
   L.linv = (T*)(base + sa.linv);
   L.flags = (DevFlags*)(base + sa.flags);
+  // two workgroups of the trailing update fit one compute unit (registers and LDS)
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
+    L.slots = 2 * cus;
 }
 
 template <typename T>

@@ -44,6 +44,7 @@ def dev(a):
     (128, 128, 64, False), (256, 128, 128, False), (300, 200, 64, False),
     (1000, 517, 192, False), (64, 64, 64, True), (384, 384, 128, True),
     (777, 333, 64, True), (1, 1, 64, False), (129, 1, 64, True), (2050, 1030, 256, True),
+    (2300, 2300, 64, True), (1100, 1500, 64, False),
 ])
 def test_schur_update_against_definition(M, dtype, M_, N_, K_, lower):
     rng = np.random.default_rng(M_ * 7 + N_)
@@ -196,6 +197,22 @@ def test_block_size_invariance_and_lookahead_bit_identity(M):
     r1, d1 = run_device(M, a, 256)
     r2, d2 = run_device(M, a, 256, flags=M.FLAG_NO_LOOKAHEAD)
     assert r1.logabsdet == r2.logabsdet and np.array_equal(d1, d2)
+
+
+def test_bulk_update_in_rounds_beside_the_panel_chain(M):
+    """Large enough that the bulk of the trailing update is issued as several launches
+    that leave part of the device to the next block column's factorisation: same bits
+    as the single-stream run, and the KMS closed form (Sec. 4.1-style check)."""
+    w = W.kms(4608, 0.7, block_size=256)
+    a = torch.from_numpy(w.dense()).cuda()
+    r1 = M.mdet_logdet_device(a.clone(), block_size=256, overwrite=True)
+    r2 = M.mdet_logdet_device(a.clone(), block_size=256, overwrite=True, flags=M.FLAG_NO_LOOKAHEAD)
+    r3 = M.mdet_logdet_device(a.clone(), block_size=512, overwrite=True)
+    assert r1.status == 0 and r1.sign == 1
+    assert r1.kernel_launches > r2.kernel_launches       # the rounds are extra launches
+    assert r1.logabsdet == r2.logabsdet
+    exact = w.closed_form_logdet()
+    assert rel(r1.logabsdet, exact) <= TOL["f64"] and rel(r3.logabsdet, exact) <= TOL["f64"]
 
 
 def test_flop_counter_is_tiling_independent(M):

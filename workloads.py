@@ -201,7 +201,7 @@ class _TorchNS:
 
 
 # --------------------------------------------------------------------------
-# The benchmark configurations (BASELINE.json "configs", in order)
+# The five benchmark configurations, in order
 # --------------------------------------------------------------------------
 GIB = 1 << 30
 
