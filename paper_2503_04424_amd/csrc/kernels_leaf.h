@@ -287,10 +287,16 @@ __global__ __launch_bounds__(256) void leaf_solve_kernel(
     const T* __restrict__ dinv, const T* __restrict__ linv) {
   using X = Mfma<T>;
   using acc_t = typename X::acc_t;
-  __shared__ T Ls[LEAF * LEAF_PAD];             // strictly lower part of the leaf's L
+  // Only the sub-blocks L[b, p], p < b, and the solved W_p, p < NSUB - 1, are ever
+  // multiplied: rows 16.. and columns ..47 of the leaf.  Keeping just those holds the
+  // workgroup's LDS (60 KB in fp64) below that of a trailing-update workgroup, so
+  // that it fits whichever half of a compute unit such a workgroup has just left.
+  constexpr int LW = LEAF - SUB;                // rows of L kept = columns of L and W kept
+  constexpr int LW_PAD = LW + 1;
+  __shared__ T Ls[LW * LW_PAD];                 // L[16.., ..47], strictly lower part
   __shared__ T Li[NSUB * SUB * SUB_PAD];        // inverses of its diagonal sub-blocks
   __shared__ T rinv[LEAF];
-  __shared__ T wsc[4][SUB * LEAF_PAD];          // per wavefront: solved W, row-major
+  __shared__ T wsc[4][SUB * LW_PAD];            // per wavefront: solved W, row-major
   __shared__ T tsc[4][SUB * SUB_PAD];           // per wavefront: layout change of T_b
   __builtin_amdgcn_s_setprio(2);                // on the chain of dependent launches
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -322,7 +328,7 @@ __global__ __launch_bounds__(256) void leaf_solve_kernel(
 #pragma unroll
     for (int q = 0; q < LEAF * LEAF / 256; ++q) {
       const int e = q * 256 + tid, r = e >> 6, c = e & 63;
-      Ls[r * LEAF_PAD + c] = v[q];
+      if (r >= SUB && c < LW) Ls[(r - SUB) * LW_PAD + c] = v[q];
     }
 #pragma unroll
     for (int q = 0; q < NSUB * SUB * SUB / 256; ++q) {
@@ -344,8 +350,8 @@ __global__ __launch_bounds__(256) void leaf_solve_kernel(
 #pragma unroll
       for (int s4 = 0; s4 < 4; ++s4) {
         const int k = p * SUB + 4 * s4 + g;
-        const T aop = -ws[l16 * LEAF_PAD + k];
-        const T bop = Ls[(b * SUB + l16) * LEAF_PAD + k];
+        const T aop = -ws[l16 * LW_PAD + k];
+        const T bop = Ls[((b - 1) * SUB + l16) * LW_PAD + k];
         acc = X::mfma(aop, bop, acc);
       }
     }
@@ -364,7 +370,7 @@ __global__ __launch_bounds__(256) void leaf_solve_kernel(
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int row16 = X::acc_row(lane, r);
-      ws[row16 * LEAF_PAD + b * SUB + l16] = wb[r];
+      if (b < NSUB - 1) ws[row16 * LW_PAD + b * SUB + l16] = wb[r];
       const int64_t row = r0 + row16;
       const int col = b * SUB + l16;
       if (row < m && col < w) Xg[row * ld + col] = wb[r] * rj;
