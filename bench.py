@@ -75,6 +75,78 @@ def measured_traffic(workload):
     return None
 
 
+def kernel_report(reps=5):
+    """Stand-alone rates of the path's kernels through the single-step entry points:
+    the Schur update against the matrix-core peak, the leaf solve and the log/sign
+    reduction against HBM bandwidth.  One JSON line."""
+    import torch
+    import paper_2503_04424_amd as M
+    M.load()
+    torch.cuda.set_device(0)
+    HBM = 8000.0   # GB/s, published
+
+    def timed(fn, prep=None):
+        best = None
+        for _ in range(reps):
+            if prep:
+                prep()
+            torch.cuda.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None else min(best, ms)
+        return best
+
+    out = []
+    for dt, name in ((torch.float64, "f64"), (torch.float32, "f32")):
+        for K in (1024, 4096):
+            Mr = 16384
+            g = torch.Generator(device="cuda").manual_seed(7)
+            a = torch.randn(Mr, K, dtype=dt, device="cuda", generator=g)
+            d = torch.rand(K, dtype=dt, device="cuda", generator=g) + 0.5
+            c = torch.zeros(Mr, Mr, dtype=dt, device="cuda")
+            ms = timed(lambda: M.mdet_step_schur_update(c, a, a, d, lower=True))
+            flop = 2.0 * K * (Mr * (Mr + 1) / 2)
+            tf = flop / ms / 1e9
+            out.append({"kernel": "trailing_update_kernel", "dtype": name,
+                        "shape": f"M=N={Mr} K={K} lower", "ms": ms, "achieved": tf, "unit": "TFLOP/s",
+                        "bound": "mfma", "peak": PEAK[name], "frac": tf / PEAK[name]})
+            del a, c, d
+    # one 64-column leaf: factorisation of the 64 x 64 diagonal block + solve of the rows below
+    for m in (32768, 131072):
+        w = 64
+        g = torch.Generator(device="cuda").manual_seed(11)
+        src = torch.randn(m, w, dtype=torch.float64, device="cuda", generator=g) * 0.01
+        src[:w] += torch.eye(w, dtype=torch.float64, device="cuda")
+        src[:w] = (src[:w] + src[:w].T) / 2
+        panel = torch.empty_like(src)
+        dv = torch.zeros(w, dtype=torch.float64, device="cuda")
+        di = torch.zeros_like(dv)
+        flags = torch.zeros(16 + 8192, dtype=torch.uint8, device="cuda")
+        flags[:16] = 255
+        ms = timed(lambda: M.mdet_step_panel_factor(panel, w, dv, di, flags), prep=lambda: panel.copy_(src))
+        gb = 2.0 * (m - w) * w * 8 / 1e9
+        out.append({"kernel": "leaf_factor_kernel + leaf_solve_kernel", "dtype": "f64",
+                    "shape": f"m={m} w={w}", "ms": ms, "bytes": gb * 1e9,
+                    "note": "both launches timed together; the solve's own duration and GB/s are in the "
+                            "rocprofv3 summary of this command", "bound": "hbm", "peak": HBM, "unit": "GB/s",
+                    "achieved": gb / (ms * 1e-3), "frac": gb / (ms * 1e-3) / HBM})
+    for n in (196608,):          # one workgroup per block column; here a single column
+        dvec = torch.rand(n, dtype=torch.float64, device="cuda") + 0.5
+        res = torch.zeros(8, dtype=torch.float64, device="cuda")
+        ms = timed(lambda: M.mdet_step_logdet_reduce(dvec, res))
+        gb = n * 8 / 1e9
+        out.append({"kernel": "logdet_partial_kernel + logdet_combine_kernel", "dtype": "f64",
+                    "shape": f"n={n}", "ms": ms, "bound": "hbm", "peak": HBM, "unit": "GB/s",
+                    "achieved": gb / (ms * 1e-3), "frac": gb / (ms * 1e-3) / HBM})
+    print(json.dumps({"metric": "stand-alone kernel rates (single-step entry points)", "n_gpus": 1,
+                      "data": "synthetic", "kernels": out}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -88,6 +160,8 @@ def main():
                     help="device budget in GiB; >0 puts the matrix in pinned host memory and streams it")
     ap.add_argument("--no-lookahead", action="store_true",
                     help="diagnostic: run every kernel on one stream, nothing overlapped")
+    ap.add_argument("--kernels", action="store_true",
+                    help="instead of the path: stand-alone rates of its kernels (one JSON line)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0, help="order of the oracle's sample block")
     args = ap.parse_args()
@@ -95,6 +169,9 @@ def main():
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.kernels:
+        kernel_report()
+        return
 
     import numpy as np
     import torch
