@@ -284,6 +284,10 @@ struct ColRef {
 struct ResidentHooks {
   std::function<void(hipStream_t, int64_t)> before_touch;   // (stream, column)
   std::function<void(int64_t)> column_final;                // column k factored (on s0)
+  // Called once the work of the step after column k's has been queued: the place for
+  // anything that may block the calling thread (a copy to pageable host memory does),
+  // since the device then has a whole step of kernels to run meanwhile.
+  std::function<void(int64_t)> column_flush;
 };
 
 template <typename T>
@@ -305,7 +309,13 @@ static int factor_resident(Launcher<T>& L, const Plan& pl, std::vector<ColRef<T>
     int rc = L.factor_cols(s0, cols[k].base, cols[k].ld, mk, wk, k * bs, k > jb);
     if (rc != MDET_OK) return rc;
     if (hooks && hooks->column_final) hooks->column_final(k);
-    if (k + 1 >= je) break;
+    if (k + 1 >= je) {
+      if (hooks && hooks->column_flush) {
+        if (k > jb) hooks->column_flush(k - 1);
+        hooks->column_flush(k);
+      }
+      break;
+    }
     // While the rest of the trailing matrix is updated on the side stream, the next
     // block column is factored on the panel stream.  For a short block column that
     // is a chain of small kernels with little work each: the bulk update then runs
@@ -357,6 +367,7 @@ static int factor_resident(Launcher<T>& L, const Plan& pl, std::vector<ColRef<T>
         L.fail->check(hipEventRecord(ev_bulk_prev, s1));
       }
     }
+    if (hooks && hooks->column_flush && k > jb) hooks->column_flush(k - 1);
   }
   // join the side stream back into the main one
   if (lookahead && ev_bulk_prev) L.fail->check(hipStreamWaitEvent(s0, ev_bulk_prev, 0));
@@ -586,17 +597,23 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
   if (!pl.out_of_core) {
     // ---- everything resident: upload column by column, factor as columns arrive
     uint64_t off = 0;
-    std::vector<hipEvent_t> ready((size_t)T_, nullptr);
     for (int64_t j = 0; j < T_; ++j) {
       cols[j] = {(T*)(arena + off), pl.col_ld(j)};
       off += align256(pl.dev_col_bytes(j));
-      copy_col_rows(fail, pl, j, j * bs, n, cols[j].base, host_col(hA, j), true, sh, &h2d_bytes);
-      ready[j] = events.get();
-      MDET_HIP(fail, hipEventRecord(ready[j], sh));
     }
+    // A column is uploaded when the first kernel that touches it is about to be
+    // queued: columns arrive in the order of need, and a copy that blocks the
+    // calling thread (pageable memory) does so while the device works on the
+    // columns before it.
+    std::vector<hipEvent_t> ready((size_t)T_, nullptr);
     std::vector<char> seen0((size_t)T_, 0), seen1((size_t)T_, 0);
     ResidentHooks hooks;
     hooks.before_touch = [&](hipStream_t st, int64_t j) {
+      if (!ready[j]) {
+        copy_col_rows(fail, pl, j, j * bs, n, cols[j].base, host_col(hA, j), true, sh, &h2d_bytes);
+        ready[j] = events.get();
+        fail.check(hipEventRecord(ready[j], sh));
+      }
       std::vector<char>& seen = (st == s0) ? seen0 : seen1;
       if (!seen[j]) { seen[j] = 1; fail.check(hipStreamWaitEvent(st, ready[j], 0)); }
     };
@@ -606,6 +623,20 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
     const uint64_t tile_al = align256(pl.tile_bytes);
     hipEvent_t ev_arena_free = nullptr;   // previous group: compute finished and columns saved
     std::vector<hipEvent_t> saved;        // write-back completion of the previous group
+    // A factored column is saved in two steps: an event right behind its last kernel,
+    // and, a step later, the copy that waits for it (see ResidentHooks::column_flush).
+    std::vector<hipEvent_t> final_ev((size_t)T_, nullptr);
+    auto mark_final = [&](int64_t k) {
+      final_ev[k] = events.get();
+      fail.check(hipEventRecord(final_ev[k], s0));
+    };
+    auto write_back = [&](int64_t k) {
+      fail.check(hipStreamWaitEvent(sd, final_ev[k], 0));
+      copy_col_rows(fail, pl, k, k * bs, n, cols[k].base, host_col(hOut, k), false, sd, &d2h_bytes);
+      hipEvent_t sv = events.get();
+      fail.check(hipEventRecord(sv, sd));
+      saved.push_back(sv);
+    };
     for (size_t g = 0; g < pl.panels.size() && rc == MDET_OK; ++g) {
       const int64_t j0 = pl.panels[g].j0, j1 = pl.panels[g].j1;
       const int64_t wc = j1 - j0;
@@ -630,27 +661,20 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
       if (j0 == 0) {
         // first group: nothing to stream; upload column by column and factor as they arrive
         std::vector<hipEvent_t> ready((size_t)T_, nullptr);
-        for (int64_t j = j0; j < j1; ++j) {
-          copy_col_rows(fail, pl, j, j * bs, n, cols[j].base, host_col(hA, j), true, sh, &h2d_bytes);
-          ready[j] = events.get();
-          MDET_HIP(fail, hipEventRecord(ready[j], sh));
-        }
         std::vector<char> seen0((size_t)T_, 0), seen1((size_t)T_, 0);
         ResidentHooks hooks;
         hooks.before_touch = [&](hipStream_t st, int64_t j) {
+          if (!ready[j]) {   // uploaded when first needed, as in the in-core case
+            copy_col_rows(fail, pl, j, j * bs, n, cols[j].base, host_col(hA, j), true, sh, &h2d_bytes);
+            ready[j] = events.get();
+            fail.check(hipEventRecord(ready[j], sh));
+          }
           std::vector<char>& seen = (st == s0) ? seen0 : seen1;
           if (!seen[j]) { seen[j] = 1; fail.check(hipStreamWaitEvent(st, ready[j], 0)); }
         };
-        hooks.column_final = [&](int64_t k) {
-          hipEvent_t fin = events.get();
-          fail.check(hipEventRecord(fin, s0));
-          fail.check(hipStreamWaitEvent(sd, fin, 0));
-          copy_col_rows(fail, pl, k, k * bs, n, cols[k].base, host_col(hOut, k), false, sd, &d2h_bytes);
-          hipEvent_t sv = events.get();
-          fail.check(hipEventRecord(sv, sd));
-          saved.push_back(sv);
-        };
-        if (j1 == T_) hooks.column_final = nullptr;   // single group: nothing streams it again
+        hooks.column_final = mark_final;
+        hooks.column_flush = write_back;
+        if (j1 == T_) hooks.column_final = hooks.column_flush = nullptr;   // single group: nothing streams it again
         rc = factor_resident(L, pl, cols, j0, j1, false, lookahead, s0, s1, events, &hooks);
       } else {
         // The group's original blocks are uploaded one block row at a time, each just
@@ -717,17 +741,10 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
         }
         if (rc == MDET_OK) {
           ResidentHooks hooks;
-          hooks.column_final = [&](int64_t k) {
-            hipEvent_t fin = events.get();
-            fail.check(hipEventRecord(fin, s0));
-            fail.check(hipStreamWaitEvent(sd, fin, 0));
-            copy_col_rows(fail, pl, k, k * bs, n, cols[k].base, host_col(hOut, k), false, sd, &d2h_bytes);
-            hipEvent_t sv = events.get();
-            fail.check(hipEventRecord(sv, sd));
-            saved.push_back(sv);
-          };
+          hooks.column_final = mark_final;
+          hooks.column_flush = write_back;
           // the last group need not be written back: nothing will stream it again
-          if (j1 == T_) hooks.column_final = nullptr;
+          if (j1 == T_) hooks.column_final = hooks.column_flush = nullptr;
           rc = factor_resident(L, pl, cols, j0, j1, false, lookahead, s0, s1, events, &hooks);
         }
       }
