@@ -52,7 +52,8 @@ typedef enum {
 /* Parameters of one log-determinant call.  Zero-initialise, then set fields. */
 typedef struct mdet_params {
   uint32_t struct_size;      /* = sizeof(mdet_params); guards ABI drift            */
-  int32_t dtype;             /* mdet_dtype: type of the matrix AND of the arithmetic */
+  int32_t dtype;             /* mdet_dtype: type of the matrix AND of the arithmetic
+                                (but see MDET_FLAG_COMPUTE_F64)                     */
   int64_t n;                 /* matrix order (the paper's m)                        */
   int64_t block_size;        /* b; 0 = let the library choose                       */
   uint64_t mem_budget_bytes; /* cap on device bytes this call may allocate or use as
@@ -84,6 +85,16 @@ typedef struct mdet_params {
                                      (results are bit-identical either way)        */
 #define MDET_FLAG_FORCE_OUT_OF_CORE 2u /* host entry points: stream blocks even if the
                                      whole triangle would fit in the budget         */
+#define MDET_FLAG_COMPUTE_F64 8u  /* dtype = MDET_F32, mdet_logdet_device only: the
+                                     matrix is STORED in fp32 and every arithmetic step
+                                     runs in fp64 on the exactly widened values (App. C,
+                                     data-precision pipeline, stage 3: whatever precision
+                                     the matrix was stored in, the log-determinant is
+                                     computed in 64 bit).  The library works on an fp64
+                                     copy in its workspace (n * ld_padded * 8 bytes,
+                                     counted against the budget; the input is never
+                                     modified) and diag receives n DOUBLES.  The host
+                                     and provider entry points return MDET_EINVAL.     */
 #define MDET_FLAG_PROFILE 4u      /* bracket every trailing-update launch with HIP
                                      events on its own stream and report the sums in
                                      result->t_trailing_update etc.                 */

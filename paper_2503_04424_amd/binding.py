@@ -18,6 +18,7 @@ MDET_F32, MDET_F64 = 0, 1
 FLAG_NO_LOOKAHEAD = 1
 FLAG_FORCE_OUT_OF_CORE = 2
 FLAG_PROFILE = 4
+FLAG_COMPUTE_F64 = 8
 
 
 class Status:
@@ -258,8 +259,10 @@ def mdet_logdet_device(a, block_size=0, mem_budget=0, overwrite=False, flags=0, 
     p = _params(n, a.dtype, block_size, mem_budget, overwrite, flags, _stream_handle(stream),
                 workspace.data_ptr() if workspace is not None else None,
                 workspace.numel() * workspace.element_size() if workspace is not None else 0)
-    if diag is not None and (diag.dtype != a.dtype or diag.numel() < n or not diag.is_cuda):
-        raise ValueError("diag must be a CUDA tensor of n elements of the matrix dtype")
+    import torch
+    diag_dtype = torch.float64 if (flags & FLAG_COMPUTE_F64) else a.dtype
+    if diag is not None and (diag.dtype != diag_dtype or diag.numel() < n or not diag.is_cuda):
+        raise ValueError("diag must be a CUDA tensor of n elements of the arithmetic's dtype")
     r = _Result()
     st = load().mdet_logdet_device(C.byref(p), C.c_void_p(a.data_ptr()), ld, C.byref(r),
                                    C.c_void_p(diag.data_ptr()) if diag is not None else None)

@@ -67,4 +67,15 @@ __global__ void logdet_combine_kernel(const double* __restrict__ partial, int64_
   out[2] = neg;
 }
 
+// fp32 -> fp64 copy of the part of a row-major matrix the factorisation reads: row i
+// up to the end of its 64-column leaf on the diagonal.  Widening is exact.
+__global__ __launch_bounds__(256) void widen_lower_kernel(const float* __restrict__ src, int64_t lds,
+                                                          double* __restrict__ dst, int64_t ldd,
+                                                          int64_t n) {
+  const int64_t i = blockIdx.x;
+  int64_t end = (i / 64 + 1) * 64;
+  if (end > n) end = n;
+  for (int64_t j = threadIdx.x; j < end; j += 256) dst[i * ldd + j] = (double)src[i * lds + j];
+}
+
 }  // namespace mdet

@@ -463,7 +463,7 @@ static void reset_flags(Launcher<T>& L, hipStream_t st) {
 // ---------------------------------------------------------------------------
 template <typename T>
 static int logdet_device_t(const mdet_params& p, const Plan& pl, T* dA, int64_t ld, mdet_result* res,
-                           T* diag) {
+                           T* diag, const float* widen_from = nullptr) {
   HipFail fail;
   int dev = 0;
   MDET_HIP(fail, hipGetDevice(&dev));
@@ -499,8 +499,14 @@ static int logdet_device_t(const mdet_params& p, const Plan& pl, T* dA, int64_t 
     constexpr int vec = 16 / (int)sizeof(T);
     ldw = round_up(pl.n, vec);
     W = (T*)(ws.base + sa.total);
-    MDET_HIP(fail, hipMemcpy2DAsync(W, ldw * sizeof(T), dA, ld * sizeof(T), pl.n * sizeof(T), pl.n,
-                                    hipMemcpyDeviceToDevice, s0));
+    if (widen_from) {
+      hipLaunchKernelGGL(widen_lower_kernel, dim3((unsigned)pl.n), dim3(256), 0, s0, widen_from, ld,
+                         (double*)W, ldw, pl.n);
+      MDET_HIP(fail, hipGetLastError());
+    } else {
+      MDET_HIP(fail, hipMemcpy2DAsync(W, ldw * sizeof(T), dA, ld * sizeof(T), pl.n * sizeof(T), pl.n,
+                                      hipMemcpyDeviceToDevice, s0));
+    }
   }
   reset_flags(L, s0);
 
@@ -908,6 +914,8 @@ int mdet_logdet_device(const mdet_params* p, void* dA, int64_t ld, mdet_result* 
   if (p->n > 0 && ((uintptr_t)dA & 15u)) return MDET_EINVAL;
   auto t0 = std::chrono::steady_clock::now();
   if (p->dtype == MDET_F64) rc = logdet_device_t<double>(*p, pl, (double*)dA, ld, res, (double*)diag);
+  else if (p->flags & MDET_FLAG_COMPUTE_F64)
+    rc = logdet_device_t<double>(*p, pl, nullptr, ld, res, (double*)diag, (const float*)dA);
   else rc = logdet_device_t<float>(*p, pl, (float*)dA, ld, res, (float*)diag);
   res->t_total = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
   return rc;

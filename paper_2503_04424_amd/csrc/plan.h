@@ -90,8 +90,11 @@ inline SmallArea small_area(int64_t n, int64_t T, int beta) {
 inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& pl) {
   if (p.n < 0 || p.block_size < 0) return MDET_EINVAL;
   if (p.dtype != MDET_F32 && p.dtype != MDET_F64) return MDET_EINVAL;
+  // fp32 storage with fp64 arithmetic: everything on the device is fp64
+  const bool widen = p.dtype == MDET_F32 && (p.flags & MDET_FLAG_COMPUTE_F64) != 0;
+  if (widen && !device_input) return MDET_EINVAL;
   pl.n = p.n;
-  pl.beta = p.dtype == MDET_F64 ? 8 : 4;
+  pl.beta = (p.dtype == MDET_F64 || widen) ? 8 : 4;
   pl.bs = round_up(p.block_size > 0 ? p.block_size : default_block_size(p.n), 64);
   pl.T = p.n > 0 ? (p.n + pl.bs - 1) / pl.bs : 0;
   pl.device_input = device_input;
@@ -106,7 +109,7 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
   if (device_input) {
     const int vec = 16 / pl.beta;
     const bool aligned = ld % vec == 0;
-    pl.need_copy = !p.overwrite || !aligned;
+    pl.need_copy = widen || !p.overwrite || !aligned;
     if (pl.need_copy) {
       int64_t ldp = round_up(p.n > 0 ? p.n : 1, vec);
       pl.copy_bytes = align256((uint64_t)p.n * ldp * pl.beta);

@@ -121,6 +121,18 @@ def test_plan_rounds_block_size_and_handles_edges(M):
     assert a.dev_bytes_needed < 1 << 20 and b.dev_bytes_needed >= 8192 * 8192 * 8
 
 
+def test_plan_fp32_storage_with_fp64_arithmetic(M):
+    n = 3000
+    plain = M.mdet_plan(n, "f32", 256, overwrite=True, for_device_input=True)
+    wide = M.mdet_plan(n, "f32", 256, overwrite=True, flags=M.FLAG_COMPUTE_F64, for_device_input=True)
+    assert plain.dev_bytes_needed < n * n                   # in place: small scratch only
+    assert wide.dev_bytes_needed >= n * n * 8               # an fp64 copy of the matrix
+    with pytest.raises(M.MemdetError):                      # budget counts the copy
+        M.mdet_plan(n, "f32", 256, mem_budget=n * n * 4, flags=M.FLAG_COMPUTE_F64, for_device_input=True)
+    with pytest.raises(M.MemdetError):                      # device entry point only
+        M.mdet_plan(n, "f32", 256, flags=M.FLAG_COMPUTE_F64, for_device_input=False)
+
+
 def test_kms_golden_values_are_the_closed_form():
     gold = read_golden("kms_closed_form.txt")
     for key, val in gold.items():

@@ -147,6 +147,40 @@ def test_logdet_device_fp32_matches_oracle_on_same_bits(M, name, wl):
     assert rel(res.logabsdet, o.logabsdet) <= TOL["f32"]
 
 
+@pytest.mark.parametrize("name,wl", [
+    ("cfg1", lambda: W.config(1)),
+    ("cfg3_1280", lambda: W.scaled_down(W.config(3), 1280, 192)),
+    ("cfg2_1000", lambda: W.scaled_down(W.config(2), 1000, 128)),
+])
+def test_fp32_storage_with_fp64_arithmetic(M, name, wl):
+    """App. C, data-precision pipeline, stage 3: the matrix may be stored in fp32, the
+    log-determinant is computed in 64 bit.  Against the oracle on the same fp32 bits the
+    fp64 bar applies, also on the ill-conditioned inputs pure fp32 arithmetic cannot do."""
+    w = wl()
+    w.dtype = "f32"
+    a = w.dense()
+    o = oracle.ldlt_logdet(a, want_diag=True)
+    ad = dev(a)
+    before = ad.clone()
+    diag = torch.empty(w.n, dtype=torch.float64, device="cuda")
+    res = M.mdet_logdet_device(ad, block_size=w.block_size, flags=M.FLAG_COMPUTE_F64, diag=diag,
+                               overwrite=True)
+    assert res.status == 0 and res.sign == o.sign and res.negative_pivots == o.negative_pivots
+    assert rel(res.logabsdet, o.logabsdet) <= TOL["f64"]
+    assert torch.equal(ad, before)                      # the fp32 input is never written
+    # same bits as the fp64 path on the widened matrix
+    r64, d64 = run_device(M, a.astype(np.float64), w.block_size)
+    assert r64.logabsdet == res.logabsdet and np.array_equal(d64, diag.cpu().numpy())
+    # workspace accounting: the fp64 copy is part of it
+    dev_bytes, _ = M.mdet_workspace_query(w.n, "f32", w.block_size, for_device_input=True,
+                                          flags=M.FLAG_COMPUTE_F64)
+    assert dev_bytes >= w.n * w.n * 8
+    # the host entry point does not take this mode
+    packed = M.pack_lower_block_columns(torch.from_numpy(a), w.block_size)
+    bad = M.mdet_logdet_host(packed, w.n, w.block_size, flags=M.FLAG_COMPUTE_F64, raise_on_error=False)
+    assert bad.status == M.Status.EINVAL
+
+
 @pytest.mark.parametrize("n", [0, 1, 2, 63, 64, 65, 127, 129, 257, 777, 1001])
 def test_ragged_and_tiny_orders(M, n):
     if n == 0:
