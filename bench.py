@@ -311,6 +311,9 @@ def main():
     if out_of_core:
         line["host_link"] = {"bytes_h2d": final.bytes_h2d, "bytes_d2h": final.bytes_d2h,
                              "GBps_avg_h2d": final.bytes_h2d / sec / 1e9,
+                             "seconds_busy_h2d": final.t_h2d, "seconds_busy_d2h": final.t_d2h,
+                             "GBps_while_copying_h2d": (final.bytes_h2d / final.t_h2d / 1e9) if final.t_h2d else None,
+                             "GBps_while_copying_d2h": (final.bytes_d2h / final.t_d2h / 1e9) if final.t_d2h else None,
                              "dev_bytes_high_water": final.dev_bytes_high_water,
                              "superpanels": final.num_superpanels}
     cf = w.closed_form_logdet()

@@ -120,6 +120,10 @@ typedef struct mdet_result {
   uint64_t trailing_update_launches;
   double t_trailing_update;      /* seconds, sum of the launches' event-timed durations */
   double trailing_update_flops;  /* 2 x multiply-adds those launches performed          */
+  /* filled by the host entry points when MDET_FLAG_PROFILE is set: time the host link
+     was busy in each direction (sum of the copies' event-timed durations, seconds) */
+  double t_h2d;
+  double t_d2h;
 } mdet_result;
 
 /*

@@ -46,6 +46,7 @@ class _Result(C.Structure):
         ("bytes_d2h", C.c_uint64), ("dev_bytes_high_water", C.c_uint64),
         ("kernel_launches", C.c_uint64), ("trailing_update_launches", C.c_uint64),
         ("t_trailing_update", C.c_double), ("trailing_update_flops", C.c_double),
+        ("t_h2d", C.c_double), ("t_d2h", C.c_double),
     ]
 
 
@@ -146,6 +147,8 @@ class LogdetResult:
     trailing_update_launches: int = 0
     t_trailing_update: float = 0.0
     trailing_update_flops: float = 0.0
+    t_h2d: float = 0.0
+    t_d2h: float = 0.0
 
 
 @dataclass
@@ -201,7 +204,7 @@ def _result(status: int, r: _Result) -> LogdetResult:
                         r.block_size_used, r.num_blocks, bool(r.out_of_core), r.num_superpanels,
                         r.flops, r.t_total, r.bytes_h2d, r.bytes_d2h, r.dev_bytes_high_water,
                         r.kernel_launches, r.hip_error, r.trailing_update_launches,
-                        r.t_trailing_update, r.trailing_update_flops)
+                        r.t_trailing_update, r.trailing_update_flops, r.t_h2d, r.t_d2h)
 
 
 _SOFT = (Status.OK, Status.ESINGULAR, Status.ENONFINITE)

@@ -541,10 +541,46 @@ static int logdet_device_t(const mdet_params& p, const Plan& pl, T* dA, int64_t 
 // ---------------------------------------------------------------------------
 // Copy of rows [r0, r1) of block column j between the host layout (leading
 // dimension w_j) and its device image (leading dimension col_ld(j)).
+// With MDET_FLAG_PROFILE: every host <-> device copy of the host path bracketed by
+// events on its stream; copies of one direction share a stream, so the sum of their
+// durations is the time the link was busy in that direction.
+struct CopyProfile {
+  bool on = false;
+  HipFail* fail = nullptr;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> ev[2];   // [0] host -> device, [1] device -> host
+  struct Scope {
+    CopyProfile* p; int dir; hipStream_t st; hipEvent_t e0 = nullptr, e1 = nullptr;
+    Scope(CopyProfile* p_, int dir_, hipStream_t st_) : p(p_), dir(dir_), st(st_) {
+      if (!p->on) return;
+      p->fail->check(hipEventCreate(&e0));
+      p->fail->check(hipEventCreate(&e1));
+      p->fail->check(hipEventRecord(e0, st));
+    }
+    ~Scope() {
+      if (!p->on) return;
+      p->fail->check(hipEventRecord(e1, st));
+      p->ev[dir].emplace_back(e0, e1);
+    }
+  };
+  double collect(int dir) {   // seconds; call when the streams are idle
+    double ms_total = 0.0;
+    for (auto& pr : ev[dir]) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) ms_total += ms;
+      (void)hipEventDestroy(pr.first);
+      (void)hipEventDestroy(pr.second);
+    }
+    ev[dir].clear();
+    return ms_total * 1e-3;
+  }
+};
+
 template <typename T>
 static void copy_col_rows(HipFail& fail, const Plan& pl, int64_t j, int64_t r0, int64_t r1, T* dev_col,
-                          T* host_col, bool to_device, hipStream_t st, uint64_t* bytes) {
+                          T* host_col, bool to_device, hipStream_t st, uint64_t* bytes,
+                          CopyProfile* prof) {
   if (r1 <= r0) return;
+  CopyProfile::Scope timed(prof, to_device ? 0 : 1, st);
   const int64_t w = pl.col_width(j), ldd = pl.col_ld(j);
   T* d = dev_col + (r0 - j * pl.bs) * ldd;
   T* h = host_col + (r0 - j * pl.bs) * w;
@@ -598,6 +634,9 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
   const int64_t bs = pl.bs, n = pl.n, T_ = pl.T;
   std::vector<ColRef<T>> cols((size_t)T_, ColRef<T>{nullptr, 0});
   uint64_t h2d_bytes = 0, d2h_bytes = 0;
+  CopyProfile cprof;
+  cprof.on = L.profile;
+  cprof.fail = &fail;
   auto host_col = [&](T* base, int64_t j) { return base + pl.col_offset(j); };
 
   if (!pl.out_of_core) {
@@ -616,7 +655,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
     ResidentHooks hooks;
     hooks.before_touch = [&](hipStream_t st, int64_t j) {
       if (!ready[j]) {
-        copy_col_rows(fail, pl, j, j * bs, n, cols[j].base, host_col(hA, j), true, sh, &h2d_bytes);
+        copy_col_rows(fail, pl, j, j * bs, n, cols[j].base, host_col(hA, j), true, sh, &h2d_bytes, &cprof);
         ready[j] = events.get();
         fail.check(hipEventRecord(ready[j], sh));
       }
@@ -638,7 +677,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
     };
     auto write_back = [&](int64_t k) {
       fail.check(hipStreamWaitEvent(sd, final_ev[k], 0));
-      copy_col_rows(fail, pl, k, k * bs, n, cols[k].base, host_col(hOut, k), false, sd, &d2h_bytes);
+      copy_col_rows(fail, pl, k, k * bs, n, cols[k].base, host_col(hOut, k), false, sd, &d2h_bytes, &cprof);
       hipEvent_t sv = events.get();
       fail.check(hipEventRecord(sv, sd));
       saved.push_back(sv);
@@ -671,7 +710,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
         ResidentHooks hooks;
         hooks.before_touch = [&](hipStream_t st, int64_t j) {
           if (!ready[j]) {   // uploaded when first needed, as in the in-core case
-            copy_col_rows(fail, pl, j, j * bs, n, cols[j].base, host_col(hA, j), true, sh, &h2d_bytes);
+            copy_col_rows(fail, pl, j, j * bs, n, cols[j].base, host_col(hA, j), true, sh, &h2d_bytes, &cprof);
             ready[j] = events.get();
             fail.check(hipEventRecord(ready[j], sh));
           }
@@ -690,7 +729,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
         auto upload_row = [&](int64_t i) {
           const int64_t r0 = i * bs, r1 = (i + 1) * bs < n ? (i + 1) * bs : n;
           for (int64_t j = j0; j < j1 && j <= i; ++j)
-            copy_col_rows(fail, pl, j, r0, r1, cols[j].base, host_col(hA, j), true, sh, &h2d_bytes);
+            copy_col_rows(fail, pl, j, r0, r1, cols[j].base, host_col(hA, j), true, sh, &h2d_bytes, &cprof);
           row_ready[i] = events.get();
           MDET_HIP(fail, hipEventRecord(row_ready[i], sh));
         };
@@ -707,6 +746,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
             for (int64_t i = j0; i < j1; ++i) upload_row(i);
           {
             const size_t nbytes = (size_t)(rows_end_J - j0 * bs) * bs * sizeof(T);
+            CopyProfile::Scope timed(&cprof, 0, sh);
             MDET_HIP(fail, hipMemcpyAsync(bpool[q], hk + (j0 - k) * bs * bs, nbytes, hipMemcpyHostToDevice, sh));
             h2d_bytes += nbytes;
           }
@@ -728,7 +768,10 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
             if (k == 0) upload_row(i);
             if (slot_free[sl]) MDET_HIP(fail, hipStreamWaitEvent(sh, slot_free[sl], 0));
             const size_t nbytes = (size_t)wi * bs * sizeof(T);
-            MDET_HIP(fail, hipMemcpyAsync(ring[sl], hk + (i - k) * bs * bs, nbytes, hipMemcpyHostToDevice, sh));
+            {
+              CopyProfile::Scope timed(&cprof, 0, sh);
+              MDET_HIP(fail, hipMemcpyAsync(ring[sl], hk + (i - k) * bs * bs, nbytes, hipMemcpyHostToDevice, sh));
+            }
             h2d_bytes += nbytes;
             if (!slot_ready[sl]) slot_ready[sl] = events.get();
             MDET_HIP(fail, hipEventRecord(slot_ready[sl], sh));
@@ -777,6 +820,8 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
   L.collect_profile(res);
   res->bytes_h2d = h2d_bytes;
   res->bytes_d2h = d2h_bytes;
+  res->t_h2d = cprof.collect(0);
+  res->t_d2h = cprof.collect(1);
   if (!fail.ok()) { res->hip_error = fail.code; return MDET_EHIP; }
   if (rc != MDET_OK) return rc;
   return finish_result(o, res);
