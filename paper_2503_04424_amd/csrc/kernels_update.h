@@ -196,24 +196,28 @@ __device__ __forceinline__ void schur_update_block(
   const T* Bc = B + scol;
   vec_t ra[NV], rb[NV], rd;
 
-  auto gload = [&](int kt) {
-    rd = *reinterpret_cast<const vec_t*>(d + scol + (int64_t)kt * BK);
-#pragma unroll
-    for (int v = 0; v < NV; ++v) {
-      int ar = row0 + v * RPS + srow; if (ar > M - 1) ar = M - 1;
-      int br = col0 + v * RPS + srow; if (br > N - 1) br = N - 1;
-      ra[v] = *reinterpret_cast<const vec_t*>(Ac + (int64_t)ar * lda + (int64_t)kt * BK);
-      rb[v] = *reinterpret_cast<const vec_t*>(Bc + (int64_t)br * ldb + (int64_t)kt * BK);
-    }
+  // One of NV pieces of a slab: piece v covers rows v*RPS + srow of both operands
+  // (piece 0 also brings the slab's pivots).
+  auto gload_piece = [&](int kt, int v) {
+    if (v == 0) rd = *reinterpret_cast<const vec_t*>(d + scol + (int64_t)kt * BK);
+    int ar = row0 + v * RPS + srow; if (ar > M - 1) ar = M - 1;
+    int br = col0 + v * RPS + srow; if (br > N - 1) br = N - 1;
+    ra[v] = *reinterpret_cast<const vec_t*>(Ac + (int64_t)ar * lda + (int64_t)kt * BK);
+    rb[v] = *reinterpret_cast<const vec_t*>(Bc + (int64_t)br * ldb + (int64_t)kt * BK);
   };
-  auto sstore = [&](int buf) {
+  auto sstore_piece = [&](int buf, int v) {
     T* as = &As[buf][srow * S + scol];
     T* bs = &Bs[buf][srow * S + scol];
+    *reinterpret_cast<vec_t*>(as + v * RPS * S) = -(ra[v] * rd);
+    *reinterpret_cast<vec_t*>(bs + v * RPS * S) = rb[v];
+  };
+  auto gload = [&](int kt) {
 #pragma unroll
-    for (int v = 0; v < NV; ++v) {
-      *reinterpret_cast<vec_t*>(as + v * RPS * S) = -(ra[v] * rd);
-      *reinterpret_cast<vec_t*>(bs + v * RPS * S) = rb[v];
-    }
+    for (int v = 0; v < NV; ++v) gload_piece(kt, v);
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int v = 0; v < NV; ++v) sstore_piece(buf, v);
   };
 
   const int r16 = lane & 15, g = lane >> 4;
@@ -251,9 +255,18 @@ __device__ __forceinline__ void schur_update_block(
   sstore(0);
   __syncthreads();
 
+  // The next slab's traffic rides inside the products of this one: with enough
+  // stages (TM = 4) its global loads go out one piece per stage at the front and its
+  // LDS stores one piece per stage at the back, so that neither forms a stretch in
+  // which the matrix pipe has nothing queued (measured: all loads up front and all
+  // stores behind the last product cost 4 and 8 % of the kernel's rate).  The
+  // stores go to the buffer nobody reads during this slab.
+  constexpr int NST = TM * TM;                        // stages = accumulators
+  constexpr bool SPREAD_LOADS = false;
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
-    if (kt + 1 < nk) gload(kt + 1);
+    const bool more = kt + 1 < nk;
+    if (more && !(SPREAD_LOADS && active)) gload(kt + 1);
     if (active) {
       // lane group g owns the KS consecutive k's [g*KS, (g+1)*KS) of the slab; MFMA
       // step s multiplies the s-th of them from every group (any assignment of the
@@ -279,16 +292,22 @@ __device__ __forceinline__ void schur_update_block(
       for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
+          const int stage = i * TM + j;
           if (i == 0 && j + 1 < TM) fetch(fb[j + 1], bs + (j + 1) * 16 * S);
           if (j == TM - 1 && i + 1 < TM) fetch(fa[(i + 1) & 1], as + (i + 1) * 16 * S);
-          __builtin_amdgcn_sched_barrier(0);   // fetches go out before this stage's products
+          if (more) {
+            if (SPREAD_LOADS && stage < NV) gload_piece(kt + 1, stage);
+            if (stage >= NST - NV) sstore_piece(buf ^ 1, stage - (NST - NV));
+          }
+          __builtin_amdgcn_sched_barrier(0);   // all of the above goes out before this stage's products
 #pragma unroll
           for (int e = 0; e < KS; ++e) acc[i][j] = X::mfma(fa[i & 1][e], fb[j][e], acc[i][j]);
           __builtin_amdgcn_sched_barrier(0);
         }
       }
+    } else if (more) {
+      sstore(buf ^ 1);
     }
-    if (kt + 1 < nk) sstore(buf ^ 1);
     __syncthreads();
   }
 
