@@ -192,18 +192,37 @@ __device__ __forceinline__ void schur_update_block(
   // VPR consecutive lanes read one whole staged row (BK elements, 128 or 256
   // contiguous bytes), so every load instruction consumes complete cache lines.
   const int scol = (tid % VPR) * VEC, srow = tid / VPR;
-  const T* Ac = A + scol;
-  const T* Bc = B + scol;
   vec_t ra[NV], rb[NV], rd;
+  // Addresses: a base common to the workgroup (scalar registers; moves along K) plus a
+  // 32-bit byte offset per thread and piece that is fixed for the whole block (row
+  // clamped at the ragged edge included).  The host checks that 128 rows of either
+  // operand span less than 4 GiB.
+  const char* Abase = reinterpret_cast<const char*>(A + (int64_t)row0 * lda);
+  const char* Bbase = reinterpret_cast<const char*>(B + (int64_t)col0 * ldb);
+  unsigned aoff[NV], boff[NV];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    int ar = v * RPS + srow; if (row0 + ar > M - 1) ar = M - 1 - row0;
+    int br = v * RPS + srow; if (col0 + br > N - 1) br = N - 1 - col0;
+    aoff[v] = (unsigned)(((int64_t)ar * lda + scol) * (int64_t)sizeof(T));
+    boff[v] = (unsigned)(((int64_t)br * ldb + scol) * (int64_t)sizeof(T));
+  }
+  const unsigned doff = (unsigned)(scol * sizeof(T));
 
   // One of NV pieces of a slab: piece v covers rows v*RPS + srow of both operands
   // (piece 0 also brings the slab's pivots).
+  // Two nudges keep these loads in the "scalar base + 32-bit vector offset" form
+  // inside the K loop, instead of one 64-bit induction pointer per thread and piece
+  // (16 VGPRs and as many 64-bit vector adds per slab): the slab's byte offset goes
+  // through readfirstlane (it is uniform anyway), and the per-thread offset through
+  // an empty asm, so that its widening is not hoisted out of the loop.
+  auto pinned = [](unsigned o) { asm volatile("" : "+v"(o)); return o; };
   auto gload_piece = [&](int kt, int v) {
-    if (v == 0) rd = *reinterpret_cast<const vec_t*>(d + scol + (int64_t)kt * BK);
-    int ar = row0 + v * RPS + srow; if (ar > M - 1) ar = M - 1;
-    int br = col0 + v * RPS + srow; if (br > N - 1) br = N - 1;
-    ra[v] = *reinterpret_cast<const vec_t*>(Ac + (int64_t)ar * lda + (int64_t)kt * BK);
-    rb[v] = *reinterpret_cast<const vec_t*>(Bc + (int64_t)br * ldb + (int64_t)kt * BK);
+    const unsigned kb = __builtin_amdgcn_readfirstlane((unsigned)kt * (unsigned)(BK * sizeof(T)));
+    if (v == 0)
+      rd = *reinterpret_cast<const vec_t*>(reinterpret_cast<const char*>(d) + kb + pinned(doff));
+    ra[v] = *reinterpret_cast<const vec_t*>(Abase + kb + pinned(aoff[v]));
+    rb[v] = *reinterpret_cast<const vec_t*>(Bbase + kb + pinned(boff[v]));
   };
   auto sstore_piece = [&](int buf, int v) {
     T* as = &As[buf][srow * S + scol];

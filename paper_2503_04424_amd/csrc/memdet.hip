@@ -119,6 +119,9 @@ struct Launcher {
     if (K % 64 != 0 || lda % vec != 0 || ldb % vec != 0 || !aligned16(A) || !aligned16(B) ||
         !aligned16(d) || M > INT32_MAX || N > INT32_MAX || K > INT32_MAX || ldc < N)
       return MDET_EINVAL;
+    // the kernels address an operand's 128-row strip with 32-bit byte offsets
+    if ((uint64_t)lda * sizeof(T) * 128 >= (1ull << 32) || (uint64_t)ldb * sizeof(T) * 128 >= (1ull << 32))
+      return MDET_EINVAL;
     // kernel choice: the trailing update always uses 128 x 128 blocks; inside a
     // block column a K = 64 update runs single-shot from LDS and short launches
     // use 64 x 64 blocks so that they reach more compute units
