@@ -21,6 +21,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "kernels_leaf.h"
 #include "mfma.h"
 
@@ -145,10 +147,7 @@ struct FusedLeaf {
 };
 
 // TM = MFMA tiles per wavefront in each direction: 4 -> 128 x 128 block, 2 -> 64 x 64.
-// SLABS = number of 128-byte K slabs staged per pipeline step (1 or 2).  A longer
-// step lets each accumulator take more consecutive MFMAs: on gfx950 every switch
-// of the fp64 MFMA accumulator costs about one extra MFMA time, so 16 tiles x 8
-// chained products waste 1/9 of the matrix pipe where 16 x 4 waste 1/5.
+// SLABS = number of 128-byte K slabs staged per pipeline step (1 or 2).
 template <typename T, int TM, int SLABS>
 struct UpdShape {
   using X = Mfma<T>;
@@ -274,18 +273,18 @@ __device__ __forceinline__ void schur_update_block(
   sstore(0);
   __syncthreads();
 
-  // The next slab's traffic rides inside the products of this one: with enough
-  // stages (TM = 4) its global loads go out one piece per stage at the front and its
-  // LDS stores one piece per stage at the back, so that neither forms a stretch in
-  // which the matrix pipe has nothing queued (measured: all loads up front and all
-  // stores behind the last product cost 4 and 8 % of the kernel's rate).  The
-  // stores go to the buffer nobody reads during this slab.
+  // The next slab's LDS stores ride between the last products of this one, one piece
+  // per stage, and go to the buffer nobody reads during this slab; issued in one go
+  // behind the last product they left the matrix pipe with nothing queued (measured:
+  // 8 % of the kernel's rate).  The global loads stay in one burst at the start of
+  // the slab: spread over the first stages they were slower.
   constexpr int NST = TM * TM;                        // stages = accumulators
-  constexpr bool SPREAD_LOADS = false;
-  for (int kt = 0; kt < nk; ++kt) {
+  // One slab; MORE: another one follows (decided at compile time, so that the
+  // stages of a slab form one straight run of instructions).
+  auto slab = [&](const int kt, auto more_tag) {
+    constexpr bool MORE = decltype(more_tag)::value;
     const int buf = kt & 1;
-    const bool more = kt + 1 < nk;
-    if (more && !(SPREAD_LOADS && active)) gload(kt + 1);
+    if (MORE) gload(kt + 1);
     if (active) {
       // lane group g owns the KS consecutive k's [g*KS, (g+1)*KS) of the slab; MFMA
       // step s multiplies the s-th of them from every group (any assignment of the
@@ -314,21 +313,20 @@ __device__ __forceinline__ void schur_update_block(
           const int stage = i * TM + j;
           if (i == 0 && j + 1 < TM) fetch(fb[j + 1], bs + (j + 1) * 16 * S);
           if (j == TM - 1 && i + 1 < TM) fetch(fa[(i + 1) & 1], as + (i + 1) * 16 * S);
-          if (more) {
-            if (SPREAD_LOADS && stage < NV) gload_piece(kt + 1, stage);
-            if (stage >= NST - NV) sstore_piece(buf ^ 1, stage - (NST - NV));
-          }
+          if (MORE && stage >= NST - NV) sstore_piece(buf ^ 1, stage - (NST - NV));
           __builtin_amdgcn_sched_barrier(0);   // all of the above goes out before this stage's products
 #pragma unroll
           for (int e = 0; e < KS; ++e) acc[i][j] = X::mfma(fa[i & 1][e], fb[j][e], acc[i][j]);
           __builtin_amdgcn_sched_barrier(0);
         }
       }
-    } else if (more) {
+    } else if (MORE) {
       sstore(buf ^ 1);
     }
     __syncthreads();
-  }
+  };
+  for (int kt = 0; kt + 1 < nk; ++kt) slab(kt, std::true_type{});
+  slab(nk - 1, std::false_type{});
 
   // ---- epilogue: store the reduced block ----------------------------------
   if (active) {
