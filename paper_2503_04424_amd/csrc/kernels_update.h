@@ -13,10 +13,10 @@
 // Tiling (gfx950): 256 threads = 4 wavefronts in a 2 x 2 arrangement, each
 // wavefront owns a 64 x 64 piece of a 128 x 128 block of C as 4 x 4 MFMA tiles of
 // 16 x 16 (v_mfma_f64_16x16x4_f64 / v_mfma_f32_16x16x4_f32).  K is walked in
-// slabs of 128 bytes per row (16 doubles / 32 floats) that are staged through
-// LDS, double buffered, with the next slab's global loads in flight while the
-// current one is multiplied.  The scaling by -d is applied to the A operand as it
-// is written to LDS; the accumulators are seeded with C.
+// slabs of 128 bytes per row (16 doubles / 32 floats) that go from global memory
+// straight into LDS, double buffered, the next slab's loads in flight while the
+// current one is multiplied.  The scaling by -d is applied to the A fragments as
+// they are read from LDS; the accumulators are seeded with C.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -147,21 +147,35 @@ struct FusedLeaf {
 };
 
 // TM = MFMA tiles per wavefront in each direction: 4 -> 128 x 128 block, 2 -> 64 x 64.
-// SLABS = number of 128-byte K slabs staged per pipeline step (1 or 2).
-template <typename T, int TM, int SLABS>
+template <typename T, int TM>
 struct UpdShape {
   using X = Mfma<T>;
-  static constexpr int BK = X::BK * SLABS;
-  static constexpr int S = (128 * SLABS + 16) / (int)sizeof(T);   // LDS row stride in elements (padded)
+  static constexpr int BK = X::BK;                                // K elements per slab: 128 bytes a row
   static constexpr int BM = 32 * TM, BN = 32 * TM;                // block of C per workgroup
-  static constexpr int LDS_ELEMS = 2 * BM * S + 2 * BN * S;       // both operands, double buffered
-  static_assert(LDS_ELEMS >= FACTOR_LDS_ELEMS, "the fused leaf needs the operand buffers");
+  static constexpr int SLAB_ELEMS = 2 * (BM + BN) * BK;           // both operands, double buffered
+  static constexpr int LDS_ELEMS = SLAB_ELEMS > FACTOR_LDS_ELEMS ? SLAB_ELEMS : FACTOR_LDS_ELEMS;
 };
+
+typedef __attribute__((address_space(1))) const void* upd_global_ptr;
+typedef __attribute__((address_space(3))) void* upd_lds_ptr;
 
 // One block (bm, bn) of C, by all threads of the workgroup; `lds` = LDS_ELEMS
 // elements.  Every thread returns from it (there are barriers inside), so a
 // workgroup may call it for one block after another.
-template <typename T, int TM, int SLABS>
+//
+// Staging.  A slab is 128 bytes of K per operand row.  It goes from global memory
+// straight into LDS (global_load_lds_dwordx4: every lane names its own 16 global
+// bytes, and lane l's land at the wavefront's LDS base + 16 l), so it needs no
+// staging registers, no LDS store instructions and no wait before the end of the
+// slab.  One such load fills 1 KB = 8 rows; a workgroup's four wavefronts issue
+// BM/32 of them per operand and slab.  Rows are 128 bytes apart in LDS without
+// padding; instead the eight 16-byte chunks of row r are stored in the order
+// chunk ^ ((r >> 1) & 7), which a lane arranges by choosing what it loads.  The
+// 16 lanes that fetch one MFMA operand (16 consecutive rows, same logical chunk)
+// then hit 16 different bank groups.  The scaling by -d is applied to the A
+// fragments as they come out of LDS (the same single rounding of a * (-d) as if
+// it were applied on the way in).
+template <typename T, int TM>
 __device__ __forceinline__ void schur_update_block(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K,
@@ -169,17 +183,16 @@ __device__ __forceinline__ void schur_update_block(
   using X = Mfma<T>;
   using acc_t = typename X::acc_t;
   using vec_t = typename X::vec_t;
-  constexpr int BK = X::BK * SLABS, VEC = X::VEC;
-  constexpr int S = (128 * SLABS + 16) / (int)sizeof(T);   // LDS row stride in elements (padded)
+  constexpr int BK = X::BK, VEC = X::VEC;
+  static_assert(BK * sizeof(T) == 128 && VEC * sizeof(T) == 16, "a slab row is eight 16-byte chunks");
   constexpr int WT = 16 * TM;                         // rows/cols of C per wavefront
   constexpr int BM = 2 * WT, BN = 2 * WT;             // block of C per workgroup
-  constexpr int VPR = BK / VEC;                       // 16-byte vectors per staged row
-  constexpr int RPS = UPD_THREADS / VPR;              // rows staged per step by the workgroup
-  constexpr int NV = BM / RPS;                        // steps (= vectors per thread per operand)
-  constexpr int KS = BK / 4;                          // MFMA k-steps per slab
+  constexpr int NV = BM / 32;                         // 1 KB loads per wavefront, operand and slab
+  constexpr int KS = BK / 4;                          // MFMA k-steps per slab (= 2 chunks a lane)
+  static_assert(KS == 2 * VEC, "a lane's share of a slab row is two chunks");
 
-  T (*As)[BM * S] = reinterpret_cast<T (*)[BM * S]>(lds);
-  T (*Bs)[BN * S] = reinterpret_cast<T (*)[BN * S]>(lds + 2 * BM * S);
+  T (*As)[BM * BK] = reinterpret_cast<T (*)[BM * BK]>(lds);
+  T (*Bs)[BN * BK] = reinterpret_cast<T (*)[BN * BK]>(lds + 2 * BM * BK);
 
   const int row0 = bm * BM, col0 = bn * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -187,13 +200,11 @@ __device__ __forceinline__ void schur_update_block(
   // a wavefront whose 64 x 64 piece lies strictly above the diagonal has nothing to do
   const bool active = !(lower && (row0 + wm * WT + WT - 1 < col0 + wn * WT));
 
-  // ---- global -> register staging ---------------------------------------
-  // VPR consecutive lanes read one whole staged row (BK elements, 128 or 256
-  // contiguous bytes), so every load instruction consumes complete cache lines.
-  const int scol = (tid % VPR) * VEC, srow = tid / VPR;
-  vec_t ra[NV], rb[NV], rd;
-  // Addresses: a base common to the workgroup (scalar registers; moves along K) plus a
-  // 32-bit byte offset per thread and piece that is fixed for the whole block (row
+  // ---- global -> LDS staging --------------------------------------------
+  // Load v of a wavefront covers rows 8 * (4 v + wave) .. + 7 of the block; lane l
+  // brings physical chunk l & 7 of row l >> 3, i.e. logical chunk (l & 7) ^ swizzle.
+  // Addresses: a base common to the workgroup (scalar registers; moves along K) plus
+  // a 32-bit byte offset per lane and load that is fixed for the whole block (row
   // clamped at the ragged edge included).  The host checks that 128 rows of either
   // operand span less than 4 GiB.
   const char* Abase = reinterpret_cast<const char*>(A + (int64_t)row0 * lda);
@@ -201,42 +212,32 @@ __device__ __forceinline__ void schur_update_block(
   unsigned aoff[NV], boff[NV];
 #pragma unroll
   for (int v = 0; v < NV; ++v) {
-    int ar = v * RPS + srow; if (row0 + ar > M - 1) ar = M - 1 - row0;
-    int br = v * RPS + srow; if (col0 + br > N - 1) br = N - 1 - col0;
-    aoff[v] = (unsigned)(((int64_t)ar * lda + scol) * (int64_t)sizeof(T));
-    boff[v] = (unsigned)(((int64_t)br * ldb + scol) * (int64_t)sizeof(T));
+    const int rt = 8 * (4 * v + wave) + (lane >> 3);          // row within the block
+    const int chunk = (lane & 7) ^ ((rt >> 1) & 7);           // logical 16-byte chunk this lane brings
+    int ar = rt; if (row0 + ar > M - 1) ar = M - 1 - row0;
+    int br = rt; if (col0 + br > N - 1) br = N - 1 - col0;
+    aoff[v] = (unsigned)(((int64_t)ar * lda + chunk * VEC) * (int64_t)sizeof(T));
+    boff[v] = (unsigned)(((int64_t)br * ldb + chunk * VEC) * (int64_t)sizeof(T));
   }
-  const unsigned doff = (unsigned)(scol * sizeof(T));
-
-  // One of NV pieces of a slab: piece v covers rows v*RPS + srow of both operands
-  // (piece 0 also brings the slab's pivots).
   // Two nudges keep these loads in the "scalar base + 32-bit vector offset" form
-  // inside the K loop, instead of one 64-bit induction pointer per thread and piece
-  // (16 VGPRs and as many 64-bit vector adds per slab): the slab's byte offset goes
-  // through readfirstlane (it is uniform anyway), and the per-thread offset through
-  // an empty asm, so that its widening is not hoisted out of the loop.
+  // inside the K loop, instead of one 64-bit induction pointer per lane and load:
+  // the slab's byte offset goes through readfirstlane (it is uniform anyway), and
+  // the per-lane offset through an empty asm, so that its widening is not hoisted
+  // out of the loop.
   auto pinned = [](unsigned o) { asm volatile("" : "+v"(o)); return o; };
-  auto gload_piece = [&](int kt, int v) {
+  auto gload = [&](int kt, int buf) {
     const unsigned kb = __builtin_amdgcn_readfirstlane((unsigned)kt * (unsigned)(BK * sizeof(T)));
-    if (v == 0)
-      rd = *reinterpret_cast<const vec_t*>(reinterpret_cast<const char*>(d) + kb + pinned(doff));
-    ra[v] = *reinterpret_cast<const vec_t*>(Abase + kb + pinned(aoff[v]));
-    rb[v] = *reinterpret_cast<const vec_t*>(Bbase + kb + pinned(boff[v]));
-  };
-  auto sstore_piece = [&](int buf, int v) {
-    T* as = &As[buf][srow * S + scol];
-    T* bs = &Bs[buf][srow * S + scol];
-    *reinterpret_cast<vec_t*>(as + v * RPS * S) = -(ra[v] * rd);
-    *reinterpret_cast<vec_t*>(bs + v * RPS * S) = rb[v];
-  };
-  auto gload = [&](int kt) {
 #pragma unroll
-    for (int v = 0; v < NV; ++v) gload_piece(kt, v);
+    for (int v = 0; v < NV; ++v) {
+      const int blk = __builtin_amdgcn_readfirstlane(4 * v + wave);
+      __builtin_amdgcn_global_load_lds((upd_global_ptr)(Abase + kb + pinned(aoff[v])),
+                                       (upd_lds_ptr)(&As[buf][blk * 8 * BK]), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((upd_global_ptr)(Bbase + kb + pinned(boff[v])),
+                                       (upd_lds_ptr)(&Bs[buf][blk * 8 * BK]), 16, 0, 0);
+    }
   };
-  auto sstore = [&](int buf) {
-#pragma unroll
-    for (int v = 0; v < NV; ++v) sstore_piece(buf, v);
-  };
+  // all of this wavefront's loads have landed (the barrier that follows publishes them)
+  auto landed = [] { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
   const int r16 = lane & 15, g = lane >> 4;
 
@@ -269,40 +270,53 @@ __device__ __forceinline__ void schur_update_block(
 
   const int nk = K / BK;
 
-  gload(0);
-  sstore(0);
+  // lane group g owns the KS consecutive k's [g*KS, (g+1)*KS) of a slab, i.e. its
+  // logical chunks 2g and 2g+1; MFMA step s multiplies the s-th of them from every
+  // group (any assignment of the slab's k's to steps is valid as long as A and B
+  // use the same one).  Where those chunks sit in a row depends only on the lane
+  // (rows 16 apart share the swizzle).
+  const int sw = (r16 >> 1) & 7;
+  const int c0 = ((2 * g) ^ sw) * VEC, c1 = ((2 * g + 1) ^ sw) * VEC;
+  const T* dlane = d + g * KS;
+  vec_t dcur[2], dnext[2];                            // d of this lane's k's: current slab, next slab
+  auto load_d = [&](vec_t (&dst)[2], int kt) {
+    dst[0] = *reinterpret_cast<const vec_t*>(dlane + (int64_t)kt * BK);
+    dst[1] = *reinterpret_cast<const vec_t*>(dlane + (int64_t)kt * BK + VEC);
+  };
+
+  gload(0, 0);
+  if (active) load_d(dcur, 0);
+  landed();
   __syncthreads();
 
-  // The next slab's LDS stores ride between the last products of this one, one piece
-  // per stage, and go to the buffer nobody reads during this slab; issued in one go
-  // behind the last product they left the matrix pipe with nothing queued (measured:
-  // 8 % of the kernel's rate).  The global loads stay in one burst at the start of
-  // the slab: spread over the first stages they were slower.
-  constexpr int NST = TM * TM;                        // stages = accumulators
   // One slab; MORE: another one follows (decided at compile time, so that the
-  // stages of a slab form one straight run of instructions).
+  // stages of a slab form one straight run of instructions).  The next slab's loads
+  // go out first, into the buffer nobody reads during this slab.
   auto slab = [&](const int kt, auto more_tag) {
     constexpr bool MORE = decltype(more_tag)::value;
     const int buf = kt & 1;
-    if (MORE) gload(kt + 1);
+    if (MORE) gload(kt + 1, buf ^ 1);
     if (active) {
-      // lane group g owns the KS consecutive k's [g*KS, (g+1)*KS) of the slab; MFMA
-      // step s multiplies the s-th of them from every group (any assignment of the
-      // slab's k's to steps is valid as long as A and B use the same one).
-      const T* as = &As[buf][(wm * WT + r16) * S + g * KS];
-      const T* bs = &Bs[buf][(wn * WT + r16) * S + g * KS];
+      if (MORE) load_d(dnext, kt + 1);
+      T nd[KS];                                         // -d, this lane's k's
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) { nd[e] = -dcur[0][e]; nd[VEC + e] = -dcur[1][e]; }
+      const T* as = &As[buf][(wm * WT + r16) * BK];
+      const T* bs = &Bs[buf][(wn * WT + r16) * BK];
       // Fragments are fetched one 16-row strip at a time, each fetch issued one
       // stage ahead of its first use, so that LDS latency hides behind the chain
       // of MFMAs of the stage before.  Stage (i, j): all KS products of
       // accumulator (i, j) back to back.
       T fa[2][KS], fb[TM][KS];
       auto fetch = [&](T (&f)[KS], const T* base) {
+        const vec_t v0 = *reinterpret_cast<const vec_t*>(base + c0);
+        const vec_t v1 = *reinterpret_cast<const vec_t*>(base + c1);
 #pragma unroll
-        for (int h = 0; h < KS / VEC; ++h) {
-          const vec_t v = *reinterpret_cast<const vec_t*>(base + h * VEC);
+        for (int e = 0; e < VEC; ++e) { f[e] = v0[e]; f[VEC + e] = v1[e]; }
+      };
+      auto scale = [&](T (&f)[KS]) {
 #pragma unroll
-          for (int e = 0; e < VEC; ++e) f[h * VEC + e] = v[e];
-        }
+        for (int e = 0; e < KS; ++e) f[e] *= nd[e];
       };
       fetch(fa[0], as);
       fetch(fb[0], bs);
@@ -310,18 +324,20 @@ __device__ __forceinline__ void schur_update_block(
       for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
-          const int stage = i * TM + j;
-          if (i == 0 && j + 1 < TM) fetch(fb[j + 1], bs + (j + 1) * 16 * S);
-          if (j == TM - 1 && i + 1 < TM) fetch(fa[(i + 1) & 1], as + (i + 1) * 16 * S);
-          if (MORE && stage >= NST - NV) sstore_piece(buf ^ 1, stage - (NST - NV));
+          if (i == 0 && j + 1 < TM) fetch(fb[j + 1], bs + (j + 1) * 16 * BK);
+          if (j == TM - 1 && i + 1 < TM) fetch(fa[(i + 1) & 1], as + (i + 1) * 16 * BK);
+          if (j == 0) scale(fa[i & 1]);
           __builtin_amdgcn_sched_barrier(0);   // all of the above goes out before this stage's products
 #pragma unroll
           for (int e = 0; e < KS; ++e) acc[i][j] = X::mfma(fa[i & 1][e], fb[j][e], acc[i][j]);
           __builtin_amdgcn_sched_barrier(0);
         }
       }
-    } else if (MORE) {
-      sstore(buf ^ 1);
+    }
+    if (MORE) {
+      landed();
+      dcur[0] = dnext[0];
+      dcur[1] = dnext[1];
     }
     __syncthreads();
   };
@@ -352,18 +368,18 @@ __device__ __forceinline__ void schur_update_block(
 }
 
 // One block per workgroup.
-template <typename T, int TM, int SLABS>
+template <typename T, int TM>
 __device__ __forceinline__ void schur_update_body(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K,
     int nsn, int swl, const bool lower, int per, int k0, const FusedLeaf<T>& fl) {
-  using Sh = UpdShape<T, TM, SLABS>;
+  using Sh = UpdShape<T, TM>;
   __shared__ __attribute__((aligned(16))) T lds[Sh::LDS_ELEMS];
   int bm, bn;
   if (!update_block_of(lower, blockIdx.x, per, k0, (M + Sh::BM - 1) / Sh::BM,
                        (N + Sh::BN - 1) / Sh::BN, nsn, swl, bm, bn))
     return;
-  schur_update_block<T, TM, SLABS>(C, ldc, A, lda, B, ldb, d, M, N, K, lower, bm, bn, fl, lds);
+  schur_update_block<T, TM>(C, ldc, A, lda, B, ldb, d, M, N, K, lower, bm, bn, fl, lds);
 }
 
 // Names for the same body: the update of the trailing matrix by a finished block
@@ -377,7 +393,7 @@ __global__ __launch_bounds__(UPD_THREADS) void trailing_update_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nsn,
     int swl, int lower, int per, int k0, FusedLeaf<T> fl) {
-  schur_update_body<T, 4, 1>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn, swl, lower != 0, per, k0, fl);
+  schur_update_body<T, 4>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn, swl, lower != 0, per, k0, fl);
 }
 template <typename T>
 __global__ __launch_bounds__(UPD_THREADS) void panel_update_kernel(
@@ -385,7 +401,7 @@ __global__ __launch_bounds__(UPD_THREADS) void panel_update_kernel(
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nsn,
     int swl, int lower, int per, int k0, FusedLeaf<T> fl) {
   __builtin_amdgcn_s_setprio(2);
-  schur_update_body<T, 4, 1>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn, swl, lower != 0, per, k0, fl);
+  schur_update_body<T, 4>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn, swl, lower != 0, per, k0, fl);
 }
 template <typename T>
 __global__ __launch_bounds__(UPD_THREADS) void panel_update64_kernel(
@@ -393,7 +409,7 @@ __global__ __launch_bounds__(UPD_THREADS) void panel_update64_kernel(
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nsn,
     int swl, int lower, int per, int k0, FusedLeaf<T> fl) {
   __builtin_amdgcn_s_setprio(2);
-  schur_update_body<T, 2, 1>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn, swl, lower != 0, per, k0, fl);
+  schur_update_body<T, 2>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn, swl, lower != 0, per, k0, fl);
 }
 
 // K = 64 exactly (the update of the columns right of a leaf by that leaf): both
