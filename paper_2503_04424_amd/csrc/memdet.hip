@@ -43,27 +43,58 @@ struct HipFail {
 // ---------------------------------------------------------------------------
 // per-device stream / event cache (streams are created once and reused)
 // ---------------------------------------------------------------------------
+// Streams of one device, created on first use and kept for the life of the process.
+// The runtime multiplexes streams onto a few hardware queues (four by default), and
+// a wait at the head of a hardware queue holds up every stream that shares it; so
+// the two compute streams are created first, and the two copy streams only when a
+// host entry point needs them.
 struct StreamSet {
   hipStream_t main = nullptr, side = nullptr, h2d = nullptr, d2h = nullptr;
-  bool ready = false;
+  bool ready = false, copy_ready = false;
 };
 static std::mutex g_mu;
 static StreamSet g_streams[64];
 
-static hipError_t get_streams(int dev, StreamSet** out) {
+static hipError_t get_streams(int dev, StreamSet** out, bool with_copy_streams) {
   std::lock_guard<std::mutex> lk(g_mu);
   if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
   StreamSet& s = g_streams[dev];
+  hipError_t e;
   if (!s.ready) {
-    hipError_t e;
     if ((e = hipStreamCreateWithFlags(&s.main, hipStreamNonBlocking)) != hipSuccess) return e;
     if ((e = hipStreamCreateWithFlags(&s.side, hipStreamNonBlocking)) != hipSuccess) return e;
+    s.ready = true;
+  }
+  if (with_copy_streams && !s.copy_ready) {
     if ((e = hipStreamCreateWithFlags(&s.h2d, hipStreamNonBlocking)) != hipSuccess) return e;
     if ((e = hipStreamCreateWithFlags(&s.d2h, hipStreamNonBlocking)) != hipSuccess) return e;
-    s.ready = true;
+    s.copy_ready = true;
   }
   *out = &s;
   return hipSuccess;
+}
+
+// Events with timing, for MDET_FLAG_PROFILE: taken from and returned to a free list
+// kept for the life of the process (creating one costs the calling thread about as
+// much as a kernel launch).
+static std::vector<hipEvent_t> g_timing_events;
+static hipEvent_t timing_event_get(HipFail* fail) {
+  {
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!g_timing_events.empty()) {
+      hipEvent_t e = g_timing_events.back();
+      g_timing_events.pop_back();
+      return e;
+    }
+  }
+  hipEvent_t e = nullptr;
+  fail->check(hipEventCreate(&e));
+  return e;
+}
+static void timing_event_put(hipEvent_t e) {
+  if (!e) return;
+  std::lock_guard<std::mutex> lk(g_mu);
+  g_timing_events.push_back(e);
 }
 
 // A small pool of reusable events (timing disabled).
@@ -147,8 +178,8 @@ struct Launcher {
       dim3 grid((unsigned)(8 * kn));
       hipEvent_t e0 = nullptr, e1 = nullptr;
       if (timed) {
-        fail->check(hipEventCreate(&e0));
-        fail->check(hipEventCreate(&e1));
+        e0 = timing_event_get(fail);
+        e1 = timing_event_get(fail);
         fail->check(hipEventRecord(e0, st));
       }
 #define MDET_LAUNCH_UPD(KERNEL)                                                                   \
@@ -245,8 +276,8 @@ struct Launcher {
     for (auto& pr : prof_events) {
       float ms = 0.f;
       if (hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) ms_total += ms;
-      (void)hipEventDestroy(pr.first);
-      (void)hipEventDestroy(pr.second);
+      timing_event_put(pr.first);
+      timing_event_put(pr.second);
     }
     res->trailing_update_launches = prof_events.size();
     res->t_trailing_update = ms_total * 1e-3;
@@ -471,7 +502,7 @@ static int logdet_device_t(const mdet_params& p, const Plan& pl, T* dA, int64_t 
   int dev = 0;
   MDET_HIP(fail, hipGetDevice(&dev));
   StreamSet* ss = nullptr;
-  MDET_HIP(fail, get_streams(dev, &ss));
+  MDET_HIP(fail, get_streams(dev, &ss, false));
   if (!fail.ok()) { res->hip_error = fail.code; return MDET_EHIP; }
 
   Workspace ws;
@@ -555,8 +586,8 @@ struct CopyProfile {
     CopyProfile* p; int dir; hipStream_t st; hipEvent_t e0 = nullptr, e1 = nullptr;
     Scope(CopyProfile* p_, int dir_, hipStream_t st_) : p(p_), dir(dir_), st(st_) {
       if (!p->on) return;
-      p->fail->check(hipEventCreate(&e0));
-      p->fail->check(hipEventCreate(&e1));
+      e0 = timing_event_get(p->fail);
+      e1 = timing_event_get(p->fail);
       p->fail->check(hipEventRecord(e0, st));
     }
     ~Scope() {
@@ -570,8 +601,8 @@ struct CopyProfile {
     for (auto& pr : ev[dir]) {
       float ms = 0.f;
       if (hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) ms_total += ms;
-      (void)hipEventDestroy(pr.first);
-      (void)hipEventDestroy(pr.second);
+      timing_event_put(pr.first);
+      timing_event_put(pr.second);
     }
     ev[dir].clear();
     return ms_total * 1e-3;
@@ -607,7 +638,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
   int dev = 0;
   MDET_HIP(fail, hipGetDevice(&dev));
   StreamSet* ss = nullptr;
-  MDET_HIP(fail, get_streams(dev, &ss));
+  MDET_HIP(fail, get_streams(dev, &ss, true));
   if (!fail.ok()) { res->hip_error = fail.code; return MDET_EHIP; }
 
   Workspace ws;
