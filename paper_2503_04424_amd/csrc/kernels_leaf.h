@@ -116,16 +116,16 @@ __device__ __forceinline__ void panel16_step(T (&a)[SUB], const int c0, const in
 }
 
 // Column `col` of the inverse of the unit-lower 16 x 16 block whose row i is held
-// by lane i in a[0..i): x_i = delta_ic - sum_{k<i} L[i][k] x_k.
-template <typename T, int I>
-__device__ __forceinline__ void inv16_step(const T (&a)[SUB], T (&x)[SUB], const int col) {
-  if constexpr (I < SUB) {
-    T s = col == I ? T(1) : T(0);
+// by lane i in a[0..i): x_i = delta_ic - sum_{k<i} L[i][k] x_k.  Step K takes the
+// finished x_K out of every later x_i; the terms reach each x_i in the order
+// k = 0, 1, ... as in the sum, but the multiply-adds of one step do not depend on
+// each other.
+template <typename T, int K>
+__device__ __forceinline__ void inv16_step(const T (&a)[SUB], T (&x)[SUB]) {
+  if constexpr (K < SUB - 1) {
 #pragma unroll
-    for (int k = 0; k < I; ++k) s -= lane_value(a[k], I) * x[k];
-    x[I] = s;
-    __builtin_amdgcn_sched_barrier(0);
-    inv16_step<T, I + 1>(a, x, col);
+    for (int i = K + 1; i < SUB; ++i) x[i] -= lane_value(a[K], i) * x[K];
+    inv16_step<T, K + 1>(a, x);
   }
 }
 
@@ -137,7 +137,9 @@ __device__ __forceinline__ void leaf_invert_sub(const T* tile, T* __restrict__ l
   T a[SUB], x[SUB];
 #pragma unroll
   for (int q = 0; q < SUB; ++q) a[q] = tile[(c0 + l16) * LEAF_PAD + c0 + q];   // row l16 of L_bb
-  inv16_step<T, 0>(a, x, l16);
+#pragma unroll
+  for (int i = 0; i < SUB; ++i) x[i] = i == l16 ? T(1) : T(0);
+  inv16_step<T, 0>(a, x);
   if (g == 0) {
 #pragma unroll
     for (int i = 0; i < SUB; ++i) linv[(b * SUB + i) * SUB + l16] = x[i];
@@ -205,6 +207,14 @@ __device__ __forceinline__ void leaf_factor_body(
     } else if (wave == 3 && b > 0) {
       // meanwhile: inverse of the previous panel's diagonal sub-block
       leaf_invert_sub<T>(tile, linv, b - 1, l16, g);
+    } else if (b == NSUB - 1) {
+      // wavefronts 1 and 2 have no part in the last panel: they write back the
+      // columns that are final already (all but the last panel's)
+      constexpr int DONE = (NSUB - 1) * SUB;
+      for (int e = tid - 64; e < LEAF * DONE; e += 128) {
+        const int r = e / DONE, c = e % DONE;
+        if (r < w && c <= r) A[(int64_t)r * ld + c] = tile[r * LEAF_PAD + c];
+      }
     }
     __syncthreads();
     // trailing sub-blocks (ti, tj), b < tj <= ti:  S -= L[ti, b] D_b L[tj, b]^T
@@ -253,11 +263,14 @@ __device__ __forceinline__ void leaf_factor_body(
       }
     }
   }
-  // write back the lower triangle (L below the diagonal, D on it)
-#pragma unroll
-  for (int q = 0; q < LEAF * LEAF / FACTOR_THREADS; ++q) {
-    const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
-    if (r < w && c <= r) A[(int64_t)r * ld + c] = tile[r * LEAF_PAD + c];
+  // write back the last panel's columns (L below the diagonal, D on it); wavefront 3
+  // is busy with the last inverse
+  if (wave < 3) {
+    constexpr int DONE = (NSUB - 1) * SUB;
+    for (int e = tid; e < LEAF * SUB; e += 192) {
+      const int r = e / SUB, c = DONE + e % SUB;
+      if (r < w && c <= r) A[(int64_t)r * ld + c] = tile[r * LEAF_PAD + c];
+    }
   }
   __builtin_amdgcn_s_setprio(0);
 }
