@@ -34,9 +34,7 @@ struct DevFlags {
   unsigned long long bad_kind;    // 1 = zero, 2 = non-finite
 };
 
-// Value of `v` in lane `src` (uniform lane index), delivered in scalar registers:
-// a scalar operand costs an instruction or two per value, whereas a same-address
-// LDS read returns 64 copies at the LDS return rate (16 bytes per clock).
+// Value of `v` in lane `src` (uniform lane index), delivered in scalar registers.
 __device__ __forceinline__ double lane_value(double v, int src) {
   int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
   int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
@@ -94,52 +92,66 @@ __device__ __forceinline__ float fast_rcp(float d) {
   return r;
 }
 
-// Elimination of one 16-column panel held one row per lane (a[q] = entry (lane, c0+q)).
-// Step J: lane c0+J owns the pivot; lanes below it get l = w / d and subtract
-// l * w_c from their remaining columns, w_c read from lane c0+c.  Rows above the
-// panel's diagonal block (lanes < c0) compute on unused entries.
-template <typename T, int J>
-__device__ __forceinline__ void panel16_step(T (&a)[SUB], const int c0, const int lane, T* dsave,
-                                             T* rsave) {
-  if constexpr (J < SUB) {
+// Elimination of one 16-column panel held one row per lane (a[q] = entry (lane, c0+q)),
+// column by column.  Column J first receives the updates of the columns before it,
+//   a_iJ -= l_ik w_Jk,  k = 0 .. J-1,   w_Jk = d_k l_Jk (entry (J, k) before its division),
+// then lane c0+J owns the pivot d_J and the lanes below it get l_iJ = a_iJ / d_J.
+// The w_Jk are the same for every lane.  A value broadcast from a lane's register
+// costs two v_readlane per double (about 10 clocks of the wavefront's own issue
+// time); a same-address LDS read costs about 5 clocks of the LDS pipeline, beside
+// the vector ALU.  So every finished column goes to the tile in LDS before its
+// division, and row J+1 of those columns is fetched one step ahead, except for the
+// newest column, whose entry comes by v_readlane (an LDS round trip would sit on the
+// chain of dependent steps).  The products and their order are those of the
+// right-looking elimination.  Rows above the panel's diagonal block (lanes < c0)
+// compute on unused entries.
+template <typename T>
+__device__ __forceinline__ void panel16_eliminate(T (&a)[SUB], T* tile, const int c0,
+                                                  const int lane) {
+  T* mine = tile + lane * LEAF_PAD + c0;
+  T row[SUB];        // w_Jk, k < J-1, for the current step
+  T newest = T(0);   // w_J,J-1
+#pragma unroll
+  for (int J = 0; J < SUB; ++J) {
+    T ahead[SUB];
+    if (J + 1 < SUB) {
+      const T* next_row = tile + (c0 + J + 1) * LEAF_PAD + c0;
+#pragma unroll
+      for (int k = 0; k < J; ++k) ahead[k] = next_row[k];
+    }
+    // keep the reads up here and their uses in the next step: moved next to each
+    // other, every step would wait out the LDS latency
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int k = 0; k + 1 < J; ++k) a[J] -= a[k] * row[k];
+    if (J > 0) a[J] -= a[J - 1] * newest;
     const T wj = a[J];
+    mine[J] = wj;
     const T dj = lane_value(wj, c0 + J);
-    const T rj = fast_rcp(dj);
-    const T lj = wj * rj;
-    dsave[c0 + J] = dj;                        // same value from every lane
-    rsave[c0 + J] = rj;
+    if (J + 1 < SUB) newest = lane_value(wj, c0 + J + 1);
+    const T lj = wj * fast_rcp(dj);
+    a[J] = lane > c0 + J ? lj : wj;
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int c = J + 1; c < SUB; ++c) a[c] -= lj * lane_value(wj, c0 + c);   // a_ic -= l_iJ d_J l_cJ
-    a[J] = lane > c0 + J ? lj : a[J];
-    panel16_step<T, J + 1>(a, c0, lane, dsave, rsave);
-  }
-}
-
-// Column `col` of the inverse of the unit-lower 16 x 16 block whose row i is held
-// by lane i in a[0..i): x_i = delta_ic - sum_{k<i} L[i][k] x_k.  Step K takes the
-// finished x_K out of every later x_i; the terms reach each x_i in the order
-// k = 0, 1, ... as in the sum, but the multiply-adds of one step do not depend on
-// each other.
-template <typename T, int K>
-__device__ __forceinline__ void inv16_step(const T (&a)[SUB], T (&x)[SUB]) {
-  if constexpr (K < SUB - 1) {
-#pragma unroll
-    for (int i = K + 1; i < SUB; ++i) x[i] -= lane_value(a[K], i) * x[K];
-    inv16_step<T, K + 1>(a, x);
+    for (int k = 0; k < J; ++k) row[k] = ahead[k];
   }
 }
 
 // Inverse of the unit-lower diagonal sub-block b of the leaf in `tile` -> linv.
+// Lane (l16, g) computes column l16: x_i = delta_{i,l16} - sum_{k<i} L[i][k] x_k, the
+// terms in the order k = 0, 1, ...; the entries of L are same-address LDS reads.
 template <typename T>
 __device__ __forceinline__ void leaf_invert_sub(const T* tile, T* __restrict__ linv, const int b,
                                                 const int l16, const int g) {
-  const int c0 = b * SUB;
-  T a[SUB], x[SUB];
+  const T* Lb = tile + (b * SUB) * LEAF_PAD + b * SUB;
+  T x[SUB];
 #pragma unroll
-  for (int q = 0; q < SUB; ++q) a[q] = tile[(c0 + l16) * LEAF_PAD + c0 + q];   // row l16 of L_bb
+  for (int i = 0; i < SUB; ++i) {
+    T v = i == l16 ? T(1) : T(0);
 #pragma unroll
-  for (int i = 0; i < SUB; ++i) x[i] = i == l16 ? T(1) : T(0);
-  inv16_step<T, 0>(a, x);
+    for (int k = 0; k < i; ++k) v -= Lb[i * LEAF_PAD + k] * x[k];
+    x[i] = v;
+  }
   if (g == 0) {
 #pragma unroll
     for (int i = 0; i < SUB; ++i) linv[(b * SUB + i) * SUB + l16] = x[i];
@@ -155,8 +167,8 @@ __device__ __forceinline__ void leaf_invert_sub(const T* tile, T* __restrict__ l
 //                unit-lower diagonal sub-block into `linv` (used by the solve kernel).
 constexpr int FACTOR_THREADS = 256;
 
-// LDS the factorisation needs, in elements: the leaf, its pivots, their reciprocals.
-constexpr int FACTOR_LDS_ELEMS = LEAF * LEAF_PAD + 2 * LEAF;
+// LDS the factorisation needs, in elements: the leaf.
+constexpr int FACTOR_LDS_ELEMS = LEAF * LEAF_PAD;
 
 // The work of all FACTOR_THREADS threads of one workgroup; `lds` points at
 // FACTOR_LDS_ELEMS elements of shared memory nobody else uses.  The update
@@ -170,8 +182,6 @@ __device__ __forceinline__ void leaf_factor_body(
   using X = Mfma<T>;
   using acc_t = typename X::acc_t;
   T* tile = lds;
-  T* dsave = lds + LEAF * LEAF_PAD;
-  T* rsave = dsave + LEAF;
   // The elimination is one long chain of dependent instructions; beside a
   // workgroup of the trailing update on the same SIMDs it would otherwise get an
   // issue slot only now and then.
@@ -201,7 +211,7 @@ __device__ __forceinline__ void leaf_factor_body(
       T a[SUB];
 #pragma unroll
       for (int q = 0; q < SUB; ++q) a[q] = tile[lane * LEAF_PAD + c0 + q];
-      panel16_step<T, 0>(a, c0, lane, dsave, rsave);
+      panel16_eliminate<T>(a, tile, c0, lane);
 #pragma unroll
       for (int q = 0; q < SUB; ++q) tile[lane * LEAF_PAD + c0 + q] = a[q];
     } else if (wave == 3 && b > 0) {
@@ -234,7 +244,7 @@ __device__ __forceinline__ void leaf_factor_body(
 #pragma unroll
         for (int s4 = 0; s4 < 4; ++s4) {
           const int k = c0 + 4 * s4 + g;
-          aop[s4] = -(tile[(R + l16) * LEAF_PAD + k] * dsave[k]);
+          aop[s4] = -(tile[(R + l16) * LEAF_PAD + k] * tile[k * LEAF_PAD + k]);   // -(l d)
           bop[s4] = tile[(Cc + l16) * LEAF_PAD + k];
         }
 #pragma unroll
@@ -249,10 +259,10 @@ __device__ __forceinline__ void leaf_factor_body(
 
   // pivots out; first zero / non-finite pivot reported through the flags
   if (wave == 0) {
-    const T myd = dsave[lane];
+    const T myd = tile[lane * LEAF_PAD + lane];
     const bool zero = myd == T(0);
     const bool bad = lane < w && (zero || !(fabs((double)myd) <= 1.7976931348623157e308));
-    if (lane < w) { dvec[lane] = myd; dinv[lane] = rsave[lane]; }
+    if (lane < w) { dvec[lane] = myd; dinv[lane] = fast_rcp(myd); }
     const unsigned long long mask = __ballot(bad);
     if (mask != 0ull) {
       const int first = __ffsll((long long)mask) - 1;

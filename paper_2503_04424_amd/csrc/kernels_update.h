@@ -389,14 +389,14 @@ __device__ __forceinline__ void schur_update_body(
 // launches and often share SIMDs with a workgroup of the former: they run at a
 // raised wave priority.
 template <typename T>
-__global__ __launch_bounds__(UPD_THREADS) void trailing_update_kernel(
+__global__ __launch_bounds__(UPD_THREADS, 2) void trailing_update_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nsn,
     int swl, int lower, int per, int k0, FusedLeaf<T> fl) {
   schur_update_body<T, 4>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn, swl, lower != 0, per, k0, fl);
 }
 template <typename T>
-__global__ __launch_bounds__(UPD_THREADS) void panel_update_kernel(
+__global__ __launch_bounds__(UPD_THREADS, 2) void panel_update_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nsn,
     int swl, int lower, int per, int k0, FusedLeaf<T> fl) {
