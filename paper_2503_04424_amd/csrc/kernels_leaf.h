@@ -94,39 +94,45 @@ __device__ __forceinline__ float fast_rcp(float d) {
 
 // Elimination of one 16-column panel held one row per lane (a[q] = entry (lane, c0+q)),
 // column by column.  Column J first receives the updates of the columns before it,
-//   a_iJ -= l_ik w_Jk,  k = 0 .. J-1,   w_Jk = d_k l_Jk (entry (J, k) before its division),
+//   a_iJ -= w_ik l_Jk,  k = 0 .. J-1,   w_ik = d_k l_ik (entry (i, k) before its division),
 // then lane c0+J owns the pivot d_J and the lanes below it get l_iJ = a_iJ / d_J.
-// The w_Jk are the same for every lane.  A value broadcast from a lane's register
-// costs two v_readlane per double (about 10 clocks of the wavefront's own issue
-// time); a same-address LDS read costs about 5 clocks of the LDS pipeline, beside
-// the vector ALU.  So every finished column goes to the tile in LDS before its
-// division, and row J+1 of those columns is fetched one step ahead, except for the
-// newest column, whose entry comes by v_readlane (an LDS round trip would sit on the
-// chain of dependent steps).  The products and their order are those of the
-// right-looking elimination.  Rows above the panel's diagonal block (lanes < c0)
-// compute on unused entries.
+// The l_Jk are the same for every lane.  A value broadcast from a lane's register
+// costs two v_readlane per double (10 to 15 clocks of the wavefront's own issue time);
+// a same-address LDS read costs a third of that and the LDS works beside the vector
+// ALU.  So every finished column goes to the tile in LDS in its final form (l below
+// the diagonal, d on it) and row J+1 of the finished columns is fetched one step
+// ahead.  Only the newest column's entry comes by v_readlane, before its division
+// (an LDS round trip would sit on the chain of dependent steps); that one term is
+// formed as l_i,J-1 w_J,J-1.  Column J-1 is written at the top of step J, after the
+// reads of the older columns of row J+1 have been issued: LDS operations finish in
+// order, and this way nothing that step J waits for is younger than a whole step.
+// Rows above the panel's diagonal block (lanes < c0) compute on unused entries.
+// On return the tile holds the panel's final columns.
 template <typename T>
 __device__ __forceinline__ void panel16_eliminate(T (&a)[SUB], T* tile, const int c0,
                                                   const int lane) {
   T* mine = tile + lane * LEAF_PAD + c0;
-  T row[SUB];        // w_Jk, k < J-1, for the current step
+  T w[SUB];          // this row's entries before their division
+  T row[SUB];        // l_Jk, k < J-1, for the current step
   T newest = T(0);   // w_J,J-1
 #pragma unroll
   for (int J = 0; J < SUB; ++J) {
     T ahead[SUB];
+    const T* next_row = tile + (c0 + J + 1) * LEAF_PAD + c0;
     if (J + 1 < SUB) {
-      const T* next_row = tile + (c0 + J + 1) * LEAF_PAD + c0;
 #pragma unroll
-      for (int k = 0; k < J; ++k) ahead[k] = next_row[k];
+      for (int k = 0; k + 1 < J; ++k) ahead[k] = next_row[k];
     }
-    // keep the reads up here and their uses in the next step: moved next to each
+    if (J > 0) mine[J - 1] = a[J - 1];
+    if (J > 0 && J + 1 < SUB) ahead[J - 1] = next_row[J - 1];
+    // keep the LDS traffic up here and its uses in the next step: moved next to each
     // other, every step would wait out the LDS latency
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int k = 0; k + 1 < J; ++k) a[J] -= a[k] * row[k];
+    for (int k = 0; k + 1 < J; ++k) a[J] -= w[k] * row[k];
     if (J > 0) a[J] -= a[J - 1] * newest;
     const T wj = a[J];
-    mine[J] = wj;
+    w[J] = wj;
     const T dj = lane_value(wj, c0 + J);
     if (J + 1 < SUB) newest = lane_value(wj, c0 + J + 1);
     const T lj = wj * fast_rcp(dj);
@@ -135,27 +141,66 @@ __device__ __forceinline__ void panel16_eliminate(T (&a)[SUB], T* tile, const in
 #pragma unroll
     for (int k = 0; k < J; ++k) row[k] = ahead[k];
   }
+  mine[SUB - 1] = a[SUB - 1];
 }
 
 // Inverse of the unit-lower diagonal sub-block b of the leaf in `tile` -> linv.
 // Lane (l16, g) computes column l16: x_i = delta_{i,l16} - sum_{k<i} L[i][k] x_k, the
-// terms in the order k = 0, 1, ...; the entries of L are same-address LDS reads.
-template <typename T>
-__device__ __forceinline__ void leaf_invert_sub(const T* tile, T* __restrict__ linv, const int b,
-                                                const int l16, const int g) {
-  const T* Lb = tile + (b * SUB) * LEAF_PAD + b * SUB;
-  T x[SUB];
+// terms in the order k = 0, 1, ...; the entries of L are same-address LDS reads,
+// requested a group of rows ahead of the group being computed.  Left to itself the
+// compiler either puts each read next to its use, so that the latency of every one
+// shows, or issues all 120 at once and needs 300 registers: each group therefore
+// reads through an index the compiler cannot see through (a zero that has passed an
+// empty asm statement), which ties the reads to the place where they are written.
+__device__ __forceinline__ int opaque_zero() {
+  int z = 0;
+  asm volatile("" : "+v"(z));
+  return z;
+}
+template <typename T, int I0, int I1>
+__device__ __forceinline__ void invert_fetch(const T* Lb, T (&l)[SUB * (SUB - 1) / 2]) {
+  const T* p = Lb + opaque_zero();
 #pragma unroll
-  for (int i = 0; i < SUB; ++i) {
+  for (int i = I0; i < I1; ++i)
+#pragma unroll
+    for (int k = 0; k < i; ++k) l[i * (i - 1) / 2 + k] = p[i * LEAF_PAD + k];
+}
+template <typename T, int I0, int I1>
+__device__ __forceinline__ void invert_rows(const T (&l)[SUB * (SUB - 1) / 2], T (&x)[SUB],
+                                            const int l16) {
+#pragma unroll
+  for (int i = I0; i < I1; ++i) {
     T v = i == l16 ? T(1) : T(0);
 #pragma unroll
-    for (int k = 0; k < i; ++k) v -= Lb[i * LEAF_PAD + k] * x[k];
+    for (int k = 0; k < i; ++k) v -= l[i * (i - 1) / 2 + k] * x[k];
     x[i] = v;
   }
-  if (g == 0) {
+}
+template <typename T>
+__device__ __forceinline__ void leaf_invert_sub(const T* tile, T* __restrict__ linv, const int b,
+                                                const int l16) {
+  const T* Lb = tile + (b * SUB) * LEAF_PAD + b * SUB;
+  T l[SUB * (SUB - 1) / 2], x[SUB];
+  invert_fetch<T, 1, 7>(Lb, l);
+  invert_fetch<T, 7, 10>(Lb, l);
+  __builtin_amdgcn_sched_barrier(0);
+  invert_rows<T, 0, 7>(l, x, l16);
+  invert_fetch<T, 10, 12>(Lb, l);
+  __builtin_amdgcn_sched_barrier(0);
+  invert_rows<T, 7, 10>(l, x, l16);
+  invert_fetch<T, 12, 14>(Lb, l);
+  __builtin_amdgcn_sched_barrier(0);
+  invert_rows<T, 10, 12>(l, x, l16);
+  invert_fetch<T, 14, 16>(Lb, l);
+  __builtin_amdgcn_sched_barrier(0);
+  invert_rows<T, 12, 14>(l, x, l16);
+  __builtin_amdgcn_sched_barrier(0);
+  invert_rows<T, 14, 16>(l, x, l16);
+  // all four groups of 16 lanes hold the same columns and store the same values (a
+  // store by one group only would let the compiler move the arithmetic into that
+  // branch, behind all the reads)
 #pragma unroll
-    for (int i = 0; i < SUB; ++i) linv[(b * SUB + i) * SUB + l16] = x[i];
-  }
+  for (int i = 0; i < SUB; ++i) linv[(b * SUB + i) * SUB + l16] = x[i];
 }
 
 // Four wavefronts factor one leaf held in LDS, 16 columns at a time:
@@ -175,7 +220,18 @@ constexpr int FACTOR_LDS_ELEMS = LEAF * LEAF_PAD;
 // kernels call it too: the workgroup that has just reduced the top-left 64 x 64
 // block of its launch factors that block straight away, which takes one kernel
 // (and its launch-to-launch latency) off the chain of dependent launches.
+//
+// With IN_LDS the caller has put the leaf into `lds` already, entry by entry with
+// leaf_tile_put and a barrier after the last one (an update kernel hands over its
+// accumulators: writing the block to memory and reading it back would cost a memory
+// round trip on the chain of dependent launches); A is then only written.
 template <typename T>
+__device__ __forceinline__ void leaf_tile_put(T* __restrict__ lds, int row, int col, int w, T v) {
+  if (row < LEAF && col < LEAF)
+    lds[row * LEAF_PAD + col] = (row < w && col < w) ? v : (row == col ? T(1) : T(0));
+}
+
+template <typename T, bool IN_LDS = false>
 __device__ __forceinline__ void leaf_factor_body(
     T* __restrict__ A, int64_t ld, int w, T* __restrict__ dvec, T* __restrict__ dinv,
     T* __restrict__ linv, long long pivot0, DevFlags* flags, T* __restrict__ lds) {
@@ -186,9 +242,10 @@ __device__ __forceinline__ void leaf_factor_body(
   // workgroup of the trailing update on the same SIMDs it would otherwise get an
   // issue slot only now and then.
   __builtin_amdgcn_s_setprio(3);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // the same in all lanes: scalar branches
   const int l16 = lane & 15, g = lane >> 4;
-  {
+  if constexpr (!IN_LDS) {
     // 64 x 64 tile, 16 entries per thread, all requests in flight together
     T v[LEAF * LEAF / FACTOR_THREADS];
 #pragma unroll
@@ -201,8 +258,8 @@ __device__ __forceinline__ void leaf_factor_body(
       const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
       tile[r * LEAF_PAD + c] = v[q];
     }
+    __syncthreads();
   }
-  __syncthreads();
 
 #pragma unroll 1
   for (int b = 0; b < NSUB; ++b) {
@@ -212,11 +269,9 @@ __device__ __forceinline__ void leaf_factor_body(
 #pragma unroll
       for (int q = 0; q < SUB; ++q) a[q] = tile[lane * LEAF_PAD + c0 + q];
       panel16_eliminate<T>(a, tile, c0, lane);
-#pragma unroll
-      for (int q = 0; q < SUB; ++q) tile[lane * LEAF_PAD + c0 + q] = a[q];
     } else if (wave == 3 && b > 0) {
       // meanwhile: inverse of the previous panel's diagonal sub-block
-      leaf_invert_sub<T>(tile, linv, b - 1, l16, g);
+      leaf_invert_sub<T>(tile, linv, b - 1, l16);
     } else if (b == NSUB - 1) {
       // wavefronts 1 and 2 have no part in the last panel: they write back the
       // columns that are final already (all but the last panel's)
@@ -255,7 +310,7 @@ __device__ __forceinline__ void leaf_factor_body(
     }
     __syncthreads();
   }
-  if (wave == 3) leaf_invert_sub<T>(tile, linv, NSUB - 1, l16, g);
+  if (wave == 3) leaf_invert_sub<T>(tile, linv, NSUB - 1, l16);
 
   // pivots out; first zero / non-finite pivot reported through the flags
   if (wave == 0) {

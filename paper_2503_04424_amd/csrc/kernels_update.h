@@ -345,6 +345,21 @@ __device__ __forceinline__ void schur_update_block(
   slab(nk - 1, std::false_type{});
 
   // ---- epilogue: store the reduced block ----------------------------------
+  // The workgroup that goes on to factor the leaf at the block's top left hands that
+  // part over in LDS (the operand buffers are free after the last slab's barrier)
+  // and leaves its write-back to the factorisation.
+  const bool fuse = lower && fl.w > 0 && bm == 0 && bn == 0;
+  const int wleaf = fuse ? fl.w : 0;
+  if (fuse) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+          leaf_tile_put<T>(lds, wm * WT + i * 16 + X::acc_row(lane, r), wn * WT + j * 16 + r16,
+                           wleaf, acc[i][j][r]);
+  }
   if (active) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -356,14 +371,15 @@ __device__ __forceinline__ void schur_update_block(
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
           const int gcol = col0 + wn * WT + j * 16 + r16;
-          if (gcol < N && (!lower || gcol <= grow)) crow[gcol] = acc[i][j][r];
+          if (gcol < N && (!lower || gcol <= grow) && !(grow < wleaf && gcol < wleaf))
+            crow[gcol] = acc[i][j][r];
         }
       }
     }
   }
-  if (lower && fl.w > 0 && bm == 0 && bn == 0) {
-    __syncthreads();   // the block's stores are visible to the whole workgroup, LDS is free
-    leaf_factor_body<T>(C, ldc, fl.w, fl.dvec, fl.dinv, fl.linv, fl.pivot0, fl.flags, lds);
+  if (fuse) {
+    __syncthreads();
+    leaf_factor_body<T, true>(C, ldc, fl.w, fl.dvec, fl.dinv, fl.linv, fl.pivot0, fl.flags, lds);
   }
 }
 
@@ -509,6 +525,22 @@ __global__ __launch_bounds__(UPD_THREADS) void leaf_update_kernel(
             for (int j = 0; j < 2; ++j) acc[i][j] = X::mfma(fa[i][e], fb[j][e], acc[i][j]);
       }
     }
+  }
+  // the workgroup that factors the leaf at C's top left hands it over in LDS
+  const bool fuse = lower && fl.w > 0 && bm == 0 && bn == 0;
+  const int wleaf = fuse ? fl.w : 0;
+  if (fuse) {
+    __syncthreads();   // everybody is done with the operands
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          leaf_tile_put<T>(lds, wm * 32 + i * 16 + X::acc_row(lane, r), wn * 32 + j * 16 + r16,
+                           wleaf, acc[i][j][r]);
+  }
+  if (active) {
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -519,13 +551,14 @@ __global__ __launch_bounds__(UPD_THREADS) void leaf_update_kernel(
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
           const int gcol = col0 + wn * 32 + j * 16 + r16;
-          if (gcol < N && (!lower || gcol <= grow)) crow[gcol] = acc[i][j][r];
+          if (gcol < N && (!lower || gcol <= grow) && !(grow < wleaf && gcol < wleaf))
+            crow[gcol] = acc[i][j][r];
         }
       }
   }
-  if (lower && fl.w > 0 && bm == 0 && bn == 0) {
+  if (fuse) {
     __syncthreads();
-    leaf_factor_body<T>(C, ldc, fl.w, fl.dvec, fl.dinv, fl.linv, fl.pivot0, fl.flags, lds);
+    leaf_factor_body<T, true>(C, ldc, fl.w, fl.dvec, fl.dinv, fl.linv, fl.pivot0, fl.flags, lds);
   }
 }
 
