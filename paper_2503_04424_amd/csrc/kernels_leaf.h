@@ -181,21 +181,28 @@ __device__ __forceinline__ void leaf_invert_sub(const T* tile, T* __restrict__ l
                                                 const int l16) {
   const T* Lb = tile + (b * SUB) * LEAF_PAD + b * SUB;
   T l[SUB * (SUB - 1) / 2], x[SUB];
-  invert_fetch<T, 1, 7>(Lb, l);
-  invert_fetch<T, 7, 10>(Lb, l);
+  // groups of rows with about 20 entries each; two groups are in flight at a time
+  invert_fetch<T, 1, 6>(Lb, l);
+  invert_fetch<T, 6, 9>(Lb, l);
   __builtin_amdgcn_sched_barrier(0);
-  invert_rows<T, 0, 7>(l, x, l16);
-  invert_fetch<T, 10, 12>(Lb, l);
+  invert_rows<T, 0, 6>(l, x, l16);
+  invert_fetch<T, 9, 11>(Lb, l);
   __builtin_amdgcn_sched_barrier(0);
-  invert_rows<T, 7, 10>(l, x, l16);
-  invert_fetch<T, 12, 14>(Lb, l);
+  invert_rows<T, 6, 9>(l, x, l16);
+  invert_fetch<T, 11, 13>(Lb, l);
   __builtin_amdgcn_sched_barrier(0);
-  invert_rows<T, 10, 12>(l, x, l16);
-  invert_fetch<T, 14, 16>(Lb, l);
+  invert_rows<T, 9, 11>(l, x, l16);
+  invert_fetch<T, 13, 14>(Lb, l);
   __builtin_amdgcn_sched_barrier(0);
-  invert_rows<T, 12, 14>(l, x, l16);
+  invert_rows<T, 11, 13>(l, x, l16);
+  invert_fetch<T, 14, 15>(Lb, l);
   __builtin_amdgcn_sched_barrier(0);
-  invert_rows<T, 14, 16>(l, x, l16);
+  invert_rows<T, 13, 14>(l, x, l16);
+  invert_fetch<T, 15, 16>(Lb, l);
+  __builtin_amdgcn_sched_barrier(0);
+  invert_rows<T, 14, 15>(l, x, l16);
+  __builtin_amdgcn_sched_barrier(0);
+  invert_rows<T, 15, 16>(l, x, l16);
   // all four groups of 16 lanes hold the same columns and store the same values (a
   // store by one group only would let the compiler move the arithmetic into that
   // branch, behind all the reads)
