@@ -443,7 +443,8 @@ __global__ __launch_bounds__(256) void leaf_solve_kernel(
     // accumulator layout -> operand layout through LDS
 #pragma unroll
     for (int r = 0; r < 4; ++r) ts[X::acc_row(lane, r) * SUB_PAD + l16] = acc[r];
-    __syncthreads();
+    // (ts and ws belong to this wavefront alone, and a wavefront's LDS operations
+    // complete in the order they were issued: no barrier between these steps)
     // W_b = T_b L_bb^-T
     acc_t wb = acc_t{0, 0, 0, 0};
 #pragma unroll
@@ -460,7 +461,6 @@ __global__ __launch_bounds__(256) void leaf_solve_kernel(
       const int col = b * SUB + l16;
       if (row < m && col < w) Xg[row * ld + col] = wb[r] * rj;
     }
-    __syncthreads();
   }
 }
 
