@@ -249,6 +249,45 @@ int mdet_step_panel_factor(int32_t dtype, void* P, int64_t ld, int64_t m, int64_
 int mdet_step_logdet_reduce(int32_t dtype, const void* d, int64_t n, double* out,
                             void* stream);
 
+/* ------------------------------------------------------------------------
+ * Principal-minor sequence and FLODANCE (Sec. 3.2, Alg. 2)
+ *
+ * The pivots D_ii that the log-determinant calls return in `diag` give the
+ * log-determinants of all leading principal blocks, ell_k = sum_{i<=k} log|D_ii|
+ * (Sec. 2.1); Alg. 2 fits the curve of Eq. (7) to every d-th of them and
+ * extrapolates it.  All pointers below are DEVICE pointers unless said otherwise;
+ * the caller owns every buffer; each call only queues kernels on `stream` (the
+ * results are there once the stream has run them), allocates nothing and returns
+ * MDET_EINVAL for inconsistent arguments, MDET_ENOMEM_DEVICE for a workspace that is
+ * too small and MDET_EHIP if a launch failed.  All arithmetic is fp64.
+ * ---------------------------------------------------------------------- */
+
+/* Device bytes that the two calls below need as workspace, for a pivot vector of
+ * length n and a fit over `rows` = n_s - n_0 samples with q correction terms (pure
+ * host code; pass 0 for the part that is not used). */
+int mdet_sequence_workspace_query(int64_t n, int64_t rows, int32_t q, uint64_t* bytes);
+
+/* ell[k] = sum_{i<=k} log|d[i]|, k = 0 .. n-1 (Alg. 2, first step): log|det| of the
+ * (k+1) x (k+1) leading principal block.  d: n pivots of type dtype; ell: n doubles. */
+int mdet_principal_logdets(int32_t dtype, const void* d, int64_t n, double* ell,
+                           void* workspace, uint64_t workspace_bytes, void* stream);
+
+/* The regression of Alg. 2 on ell[0 .. len): with L_j = ell[j d - 1] / j it uses
+ * n_j = n0 + 1 .. ns (needs 1 <= n0 < ns, ns d <= len, 0 <= q <= 10 and at least
+ * q + 2 samples), responses y_j = n_j (n_j-1)^-1/2 (L_{n_j} - L_{n0}) and covariates
+ * (n_j-1)^1/2 and -(n_j-1)^-1/2 n_j^(1-i) logGamma(n_j+1), i = 1 .. q+1, and solves
+ * the least-squares problem by Householder QR.  coef receives q + 4 doubles:
+ * c_0, nu_0 .. nu_q, then L_{n0}, then the residual norm |X beta - y|_2. */
+int mdet_flodance_fit(const double* ell, int64_t len, int64_t d, int64_t n0, int64_t ns,
+                      int32_t q, double* coef, void* workspace, uint64_t workspace_bytes,
+                      void* stream);
+
+/* out[i] = Lhat_n at n = n_values[i] (Alg. 2, last step):
+ * L_{n0} + c_0 (1 - 1/n) - sum_{i=1}^{q+1} nu_{i-1} n^-i logGamma(n+1), from the q + 4
+ * doubles that mdet_flodance_fit wrote.  n_values, out: `count` doubles each. */
+int mdet_flodance_eval(const double* coef, int32_t q, const double* n_values, int64_t count,
+                       double* out, void* stream);
+
 const char* mdet_strerror(int status);
 const char* mdet_version(void);
 

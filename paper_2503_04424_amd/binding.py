@@ -69,6 +69,8 @@ EXPORTS = [
     "mdet_logdet_provider", "mdet_host_layout_offset", "mdet_paper_block_rule",
     "mdet_paper_fma_count", "mdet_step_schur_update", "mdet_step_panel_factor",
     "mdet_step_logdet_reduce", "mdet_strerror", "mdet_version",
+    "mdet_sequence_workspace_query", "mdet_principal_logdets", "mdet_flodance_fit",
+    "mdet_flodance_eval",
 ]
 
 _lib = None
@@ -101,6 +103,10 @@ def load():
     L.mdet_step_schur_update.argtypes = [i32, vp, i64, vp, i64, vp, i64, vp, i64, i64, i64, i32, vp]
     L.mdet_step_panel_factor.argtypes = [i32, vp, i64, i64, i64, vp, vp, i64, vp, vp]
     L.mdet_step_logdet_reduce.argtypes = [i32, vp, i64, vp, vp]
+    L.mdet_sequence_workspace_query.argtypes = [i64, i64, i32, C.POINTER(u64)]
+    L.mdet_principal_logdets.argtypes = [i32, vp, i64, vp, vp, u64, vp]
+    L.mdet_flodance_fit.argtypes = [vp, i64, i64, i64, i64, i32, vp, vp, u64, vp]
+    L.mdet_flodance_eval.argtypes = [vp, i32, vp, i64, vp, vp]
     L.mdet_strerror.argtypes = [C.c_int]
     L.mdet_strerror.restype = C.c_char_p
     L.mdet_version.restype = C.c_char_p
@@ -359,6 +365,65 @@ def mdet_step_logdet_reduce(d, out, stream=None) -> None:
                                         _stream_handle(stream))
     if st != Status.OK:
         raise MemdetError(st)
+
+
+def mdet_sequence_workspace_query(n=0, rows=0, q=0) -> int:
+    """Device bytes of workspace for mdet_principal_logdets (n pivots) and
+    mdet_flodance_fit (rows = n_s - n_0 samples, q correction terms)."""
+    b = C.c_uint64(0)
+    st = load().mdet_sequence_workspace_query(int(n), int(rows), int(q), C.byref(b))
+    if st != Status.OK:
+        raise MemdetError(st)
+    return b.value
+
+
+def _sequence_workspace(n, rows, q, like):
+    import torch
+    return torch.empty(max(256, mdet_sequence_workspace_query(n, rows, q)), dtype=torch.uint8,
+                       device=like.device)
+
+
+def mdet_principal_logdets(diag, ell=None, workspace=None, stream=None):
+    """ell[k] = sum_{i<=k} log|diag[i]| on the GPU (asynchronous); returns ell (float64)."""
+    import torch
+    n = diag.numel()
+    if ell is None:
+        ell = torch.empty(n, dtype=torch.float64, device=diag.device)
+    ws = workspace if workspace is not None else _sequence_workspace(n, 0, 0, diag)
+    st = load().mdet_principal_logdets(_dtype_code(diag.dtype), diag.data_ptr(), n, ell.data_ptr(),
+                                       ws.data_ptr(), ws.numel() * ws.element_size(),
+                                       _stream_handle(stream))
+    if st != Status.OK:
+        raise MemdetError(st)
+    return ell
+
+
+def mdet_flodance_fit(ell, d, n0, ns, q, coef=None, workspace=None, stream=None):
+    """The regression of Alg. 2 on the GPU (asynchronous); returns the q + 4 float64
+    (c_0, nu_0 .. nu_q, L_{n0}, residual norm) as a device tensor."""
+    import torch
+    if coef is None:
+        coef = torch.empty(max(int(q), 0) + 4, dtype=torch.float64, device=ell.device)
+    ws = workspace if workspace is not None else _sequence_workspace(0, max(int(ns) - int(n0), 0),
+                                                                     min(max(int(q), 0), 10), ell)
+    st = load().mdet_flodance_fit(ell.data_ptr(), ell.numel(), int(d), int(n0), int(ns), int(q),
+                                  coef.data_ptr(), ws.data_ptr(), ws.numel() * ws.element_size(),
+                                  _stream_handle(stream))
+    if st != Status.OK:
+        raise MemdetError(st)
+    return coef
+
+
+def mdet_flodance_eval(coef, q, n_values, out=None, stream=None):
+    """Lhat_n at every entry of n_values (float64 device tensor), on the GPU (asynchronous)."""
+    import torch
+    if out is None:
+        out = torch.empty_like(n_values)
+    st = load().mdet_flodance_eval(coef.data_ptr(), int(q), n_values.data_ptr(), n_values.numel(),
+                                   out.data_ptr(), _stream_handle(stream))
+    if st != Status.OK:
+        raise MemdetError(st)
+    return out
 
 
 def pack_lower_block_columns(a, block_size: int, out=None, pin: bool = False):
