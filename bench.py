@@ -143,6 +143,26 @@ def kernel_report(reps=5):
         out.append({"kernel": "logdet_partial_kernel + logdet_combine_kernel", "dtype": "f64",
                     "shape": f"n={n}", "ms": ms, "bound": "hbm", "peak": HBM, "unit": "GB/s",
                     "achieved": gb / (ms * 1e-3), "frac": gb / (ms * 1e-3) / HBM})
+    # principal-minor sequence and the FLODANCE regression (Sec. 3.2, Alg. 2) at the size of the
+    # paper's experiments: 50 000 data points with d = 10 outputs, q = 10 correction terms
+    n_s, dd, n0, q = 50000, 10, 100, 10
+    piv = torch.rand(n_s * dd, dtype=torch.float64, device="cuda") + 0.5
+    ell = torch.empty_like(piv)
+    ws = torch.empty(M.mdet_sequence_workspace_query(n_s * dd, n_s - n0, q), dtype=torch.uint8, device="cuda")
+    ms = timed(lambda: M.mdet_principal_logdets(piv, ell=ell, workspace=ws))
+    gb = 3.0 * n_s * dd * 8 / 1e9          # pivots read twice, sequence written once
+    out.append({"kernel": "seq_chunk_sums + seq_chunk_offsets + seq_running_sum", "dtype": "f64",
+                "shape": f"n={n_s * dd}", "ms": ms, "bytes": gb * 1e9, "bound": "hbm", "peak": HBM,
+                "unit": "GB/s", "achieved": gb / (ms * 1e-3), "frac": gb / (ms * 1e-3) / HBM})
+    coef = torch.empty(q + 4, dtype=torch.float64, device="cuda")
+    ms = timed(lambda: M.mdet_flodance_fit(ell, dd, n0, n_s, q, coef=coef, workspace=ws))
+    out.append({"kernel": "flo_qr_kernel (3 levels)", "dtype": "f64",
+                "shape": f"rows={n_s - n0} cols={q + 3}", "ms": ms,
+                "note": "latency-bound: 13 dependent reflections per level, one block reduction each"})
+    nv = torch.logspace(2, 6, 100000, dtype=torch.float64, device="cuda")
+    ov = torch.empty_like(nv)
+    ms = timed(lambda: M.mdet_flodance_eval(coef, q, nv, out=ov))
+    out.append({"kernel": "flo_eval_kernel", "dtype": "f64", "shape": "count=100000", "ms": ms})
     print(json.dumps({"metric": "stand-alone kernel rates (single-step entry points)", "n_gpus": 1,
                       "data": "synthetic", "kernels": out}))
 

@@ -58,14 +58,29 @@ __global__ __launch_bounds__(SEQ_THREADS) void seq_chunk_sums_kernel(const T* __
   if (threadIdx.x == 0) sums[blockIdx.x] = s;
 }
 
-// pass 2: exclusive running sum of the chunk sums, in order (a few hundred at most)
-__global__ void seq_chunk_offsets_kernel(double* __restrict__ sums, int64_t nchunks) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
-  double run = 0.0;
-  for (int64_t c = 0; c < nchunks; ++c) {
-    const double s = sums[c];
-    sums[c] = run;
-    run += s;
+// pass 2: exclusive running sum of the chunk sums, in order (a few hundred at most):
+// one workgroup stages them through LDS, one thread adds them up
+__global__ __launch_bounds__(SEQ_THREADS) void seq_chunk_offsets_kernel(double* __restrict__ sums,
+                                                                       int64_t nchunks) {
+  __shared__ double tile[4 * SEQ_THREADS];
+  __shared__ double carry;
+  if (threadIdx.x == 0) carry = 0.0;
+  for (int64_t base = 0; base < nchunks; base += 4 * SEQ_THREADS) {
+    const int64_t m = nchunks - base < 4 * SEQ_THREADS ? nchunks - base : 4 * SEQ_THREADS;
+    for (int i = threadIdx.x; i < m; i += SEQ_THREADS) tile[i] = sums[base + i];
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      double run = carry;
+      for (int i = 0; i < m; ++i) {
+        const double v = tile[i];
+        tile[i] = run;
+        run += v;
+      }
+      carry = run;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < m; i += SEQ_THREADS) sums[base + i] = tile[i];
+    __syncthreads();
   }
 }
 

@@ -58,13 +58,13 @@ int mdet_principal_logdets(int32_t dtype, const void* d, int64_t n, double* ell,
   if (dtype == MDET_F64) {
     hipLaunchKernelGGL((seq_chunk_sums_kernel<double>), dim3((unsigned)chunks), dim3(SEQ_THREADS), 0, st,
                        (const double*)d, n, sums);
-    hipLaunchKernelGGL(seq_chunk_offsets_kernel, dim3(1), dim3(64), 0, st, sums, chunks);
+    hipLaunchKernelGGL(seq_chunk_offsets_kernel, dim3(1), dim3(SEQ_THREADS), 0, st, sums, chunks);
     hipLaunchKernelGGL((seq_running_sum_kernel<double>), dim3((unsigned)chunks), dim3(SEQ_THREADS), 0, st,
                        (const double*)d, n, (const double*)sums, ell);
   } else {
     hipLaunchKernelGGL((seq_chunk_sums_kernel<float>), dim3((unsigned)chunks), dim3(SEQ_THREADS), 0, st,
                        (const float*)d, n, sums);
-    hipLaunchKernelGGL(seq_chunk_offsets_kernel, dim3(1), dim3(64), 0, st, sums, chunks);
+    hipLaunchKernelGGL(seq_chunk_offsets_kernel, dim3(1), dim3(SEQ_THREADS), 0, st, sums, chunks);
     hipLaunchKernelGGL((seq_running_sum_kernel<float>), dim3((unsigned)chunks), dim3(SEQ_THREADS), 0, st,
                        (const float*)d, n, (const double*)sums, ell);
   }
