@@ -133,6 +133,40 @@ def test_pageable_host_memory_and_caller_workspace(M):
     assert ei.value.status == M.Status.ENOMEM_DEVICE
 
 
+def test_matrix_in_a_file_through_a_memory_map(M, tmp_path):
+    # the third tier of the paper (Sec. 2.2: the matrix lives on disk, a scratch file takes
+    # the updated blocks): the host entry point takes any host pointer, so a shared memory
+    # map of a file serves as the store; with overwrite=0 a second map is the scratchpad
+    n, bs = 2304, 256
+    w = W.scaled_down(W.config(4), n, bs)
+    a = w.dense()
+    o = oracle.ldlt_logdet(a)
+    src = packed(M, a, bs, pin=False)
+    path, scratch_path = str(tmp_path / "matrix.bin"), str(tmp_path / "scratch.bin")
+    src.numpy().tofile(path)
+    lo = min_budget(M, n, "f64", bs)
+    ref = M.mdet_logdet_host(src.clone(), n, bs, mem_budget=lo, flags=M.FLAG_FORCE_OUT_OF_CORE)
+    # (a) scratch file, input file untouched
+    mapped = torch.from_file(path, shared=True, size=src.numel(), dtype=torch.float64)
+    open(scratch_path, "wb").truncate(src.numel() * 8)
+    scratch = torch.from_file(scratch_path, shared=True, size=src.numel(), dtype=torch.float64)
+    res = M.mdet_logdet_host(mapped, n, bs, mem_budget=lo, overwrite=False, host_scratch=scratch,
+                             flags=M.FLAG_FORCE_OUT_OF_CORE)
+    assert res.out_of_core and res.dev_bytes_high_water <= lo
+    assert res.logabsdet == ref.logabsdet and rel(res.logabsdet, o.logabsdet) <= TOL["f64"]
+    del mapped
+    assert np.array_equal(np.fromfile(path, dtype=np.float64), src.numpy())
+    # (b) in place: the file ends up holding the factors (unit-lower L and D)
+    mapped = torch.from_file(path, shared=True, size=src.numel(), dtype=torch.float64)
+    res = M.mdet_logdet_host(mapped, n, bs, mem_budget=lo, flags=M.FLAG_FORCE_OUT_OF_CORE)
+    assert res.logabsdet == ref.logabsdet
+    del mapped
+    on_disk = np.fromfile(path, dtype=np.float64)
+    first_diag = on_disk[np.arange(bs) * bs + np.arange(bs)]          # diagonal of block column 0
+    assert np.max(np.abs(first_diag - oracle.ldlt_logdet(a, want_diag=True).diag[:bs])
+                  / np.abs(first_diag)) <= 1e-9
+
+
 def test_budget_below_minimum_working_set(M):
     n, bs = 1024, 128
     lo = min_budget(M, n, "f64", bs)
