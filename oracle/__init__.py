@@ -30,6 +30,11 @@ def _load():
             fn.argtypes = [ptr_t, i64, i64, pd, ctypes.POINTER(ctypes.c_int),
                            ctypes.POINTER(i64), ctypes.POINTER(i64),
                            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        for name in ("oracle_cholesky_f64", "oracle_cholesky_f32"):
+            fn = getattr(lib, name)
+            fn.restype = ctypes.c_int
+            fn.argtypes = [ctypes.c_void_p, i64, i64, pd, ctypes.POINTER(i64),
+                           ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         lib.oracle_leibniz_f64.restype = ctypes.c_int
         lib.oracle_leibniz_f64.argtypes = [ctypes.c_void_p, ctypes.c_int, pd,
                                            ctypes.POINTER(ctypes.c_int), pd]
@@ -81,6 +86,43 @@ def ldlt_logdet(a: np.ndarray, want_diag: bool = False, want_L: bool = False) ->
         raise MemoryError("oracle allocation failed")
     return OracleResult(lad.value, sg.value, st, bad.value, neg.value, d, cum,
                         L if st == 0 else None)
+
+
+@dataclass
+class CholeskyResult:
+    logdet: float             # 2 sum log L_jj  (NaN when not positive definite)
+    status: int               # 0 ok, 3 a pivot was not positive
+    bad_pivot_index: int      # index of that pivot, else -1
+    diag: Optional[np.ndarray] = None        # L_jj
+    cum_logdet: Optional[np.ndarray] = None  # logdet of leading principal blocks
+    L: Optional[np.ndarray] = None           # lower-triangular factor
+
+
+def cholesky_logdet(a: np.ndarray, want_diag: bool = False, want_L: bool = False) -> CholeskyResult:
+    """logdet of the symmetric positive-definite matrix whose LOWER triangle is in ``a``,
+    by unblocked Cholesky in long double on the exact input bits (float64 or float32)."""
+    lib = _load()
+    if a.ndim != 2 or a.shape[0] != a.shape[1]:
+        raise ValueError("square matrix expected")
+    if a.dtype not in (np.float64, np.float32):
+        raise ValueError("float64 or float32 expected")
+    a = np.ascontiguousarray(a)
+    n = a.shape[0]
+    lda = a.strides[0] // a.itemsize if n > 0 else 1
+    fn = lib.oracle_cholesky_f64 if a.dtype == np.float64 else lib.oracle_cholesky_f32
+    ld = ctypes.c_double(0.0)
+    bad = ctypes.c_int64(-1)
+    d = np.empty(n, dtype=np.float64) if want_diag else None
+    cum = np.empty(n, dtype=np.float64) if want_diag else None
+    L = np.empty((n, n), dtype=np.float64) if want_L else None
+    st = fn(a.ctypes.data, n, max(lda, 1), ctypes.byref(ld), ctypes.byref(bad),
+            d.ctypes.data if d is not None else None,
+            cum.ctypes.data if cum is not None else None,
+            L.ctypes.data if L is not None else None)
+    if st == 2:
+        raise MemoryError("oracle allocation failed")
+    return CholeskyResult(ld.value, st, bad.value, d if st == 0 else None, cum if st == 0 else None,
+                          L if st == 0 else None)
 
 
 def leibniz_logdet(a: np.ndarray):

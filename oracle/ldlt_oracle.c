@@ -29,7 +29,14 @@
  * pivot column j; the summation order inside every dot product is k = 0..j-1.
  *
  * Also here: a brute-force Leibniz determinant (sum over all permutations),
- * used to pin the factorisation on tiny matrices.
+ * used to pin the factorisation on tiny matrices; and the same plain reference
+ * for the positive-definite form of the method (the paper's algorithm for
+ * symmetric positive-definite matrices; App. D: M = L L^T with lower-triangular
+ * L gives logdet(M[:k,:k]) = 2 sum_{i<=k} log L_ii), unblocked Cholesky in
+ * long double:
+ *
+ *      l_jj = sqrt(a_jj - sum_{k<j} l_jk^2)
+ *      l_ij = (a_ij - sum_{k<j} l_ik l_jk) / l_jj           (i > j)
  */
 #include <math.h>
 #include <stdint.h>
@@ -148,6 +155,64 @@ int oracle_ldlt_f32(const float *a, int64_t n, int64_t lda, double *logabsdet,
                     double *cum_out, double *l_out) {
   return ldlt_core(a, (size_t)n, (size_t)lda, get_f32, logabsdet, sign, bad,
                    negative, d_out, cum_out, l_out);
+}
+
+/*
+ * Cholesky recurrence.  Outputs (any may be NULL): diag_out[n] = l_jj,
+ * cum_out[n] = 2 sum_{j<=k} log l_jj, l_out[n*n] = row-major L (upper part zero).
+ * Returns 0 on success, 3 if a pivot a_jj - sum l_jk^2 is not positive (then
+ * *bad = its index and *logdet = NaN), 2 on allocation failure.
+ */
+static int chol_core(const void *a, size_t n, size_t lda, getter get, double *logdet,
+                     int64_t *bad, double *diag_out, double *cum_out, double *l_out) {
+  *logdet = 0.0;
+  if (bad) *bad = -1;
+  if (n == 0) return 0;
+  xreal *l = (xreal *)malloc(n * (n + 1) / 2 * sizeof(xreal)); /* row i: i + 1 entries */
+  if (!l) return 2;
+  int status = 0;
+  xreal acc_log = 0.0L;
+  for (size_t j = 0; j < n; ++j) {
+    xreal *lj = l + j * (j + 1) / 2;
+    xreal s = get(a, j, j, lda);
+    for (size_t k = 0; k < j; ++k) s -= lj[k] * lj[k];
+    if (!(s > 0.0L)) {
+      status = 3;
+      if (bad) *bad = (int64_t)j;
+      break;
+    }
+    const xreal ljj = sqrtl(s);
+    lj[j] = ljj;
+    acc_log += 2.0L * logl(ljj);
+    if (cum_out) cum_out[j] = (double)acc_log;
+    if (diag_out) diag_out[j] = (double)ljj;
+    long i;
+#pragma omp parallel for schedule(static)
+    for (i = (long)j + 1; i < (long)n; ++i) {
+      xreal *li = l + (size_t)i * ((size_t)i + 1) / 2;
+      xreal t = get(a, (size_t)i, j, lda);
+      for (size_t k = 0; k < j; ++k) t -= li[k] * lj[k];
+      li[j] = t / ljj;
+    }
+  }
+  *logdet = status == 0 ? (double)acc_log : NAN;
+  if (l_out && status == 0) {
+    memset(l_out, 0, n * n * sizeof(double));
+    for (size_t i = 0; i < n; ++i)
+      for (size_t k = 0; k <= i; ++k) l_out[i * n + k] = (double)l[i * (i + 1) / 2 + k];
+  }
+  free(l);
+  return status;
+}
+
+int oracle_cholesky_f64(const double *a, int64_t n, int64_t lda, double *logdet, int64_t *bad,
+                        double *diag_out, double *cum_out, double *l_out) {
+  return chol_core(a, (size_t)n, (size_t)lda, get_f64, logdet, bad, diag_out, cum_out, l_out);
+}
+
+int oracle_cholesky_f32(const float *a, int64_t n, int64_t lda, double *logdet, int64_t *bad,
+                        double *diag_out, double *cum_out, double *l_out) {
+  return chol_core(a, (size_t)n, (size_t)lda, get_f32, logdet, bad, diag_out, cum_out, l_out);
 }
 
 /*
