@@ -46,7 +46,8 @@ typedef enum {
   MDET_EHIP = 5,          /* a HIP call failed; raw code in result->hip_error      */
   MDET_ESINGULAR = 6,     /* exact zero pivot: sign = 0, logabsdet = -inf          */
   MDET_ENONFINITE = 7,    /* NaN/Inf pivot met (input not finite or overflow)      */
-  MDET_EPROVIDER = 8      /* the block provider returned non-zero                  */
+  MDET_EPROVIDER = 8,     /* the block provider returned non-zero                  */
+  MDET_ENOTPOSDEF = 9     /* MDET_FLAG_ASSUME_SPD and a negative pivot was met      */
 } mdet_status;
 
 /* Parameters of one log-determinant call.  Zero-initialise, then set fields. */
@@ -98,6 +99,14 @@ typedef struct mdet_params {
 #define MDET_FLAG_PROFILE 4u      /* bracket every trailing-update launch with HIP
                                      events on its own stream and report the sums in
                                      result->t_trailing_update etc.                 */
+#define MDET_FLAG_ASSUME_SPD 16u  /* the matrix is symmetric positive definite: use the
+                                     Cholesky form of the method (the paper's algorithm
+                                     for positive-definite matrices, App. D; block
+                                     columns hold rows of L D^(1/2), the Schur updates
+                                     are plain A B^T products without the diagonal
+                                     scaling).  A negative pivot ends the call with
+                                     MDET_ENOTPOSDEF and its index in bad_pivot_index;
+                                     `diag` still receives the pivots d_j = L_jj^2.    */
 
 typedef struct mdet_result {
   double logabsdet;            /* log|det A|; -inf when sign == 0                    */
@@ -227,7 +236,8 @@ double mdet_paper_fma_count(int64_t m);
 /* Trailing Schur-complement update (Sec. 2.2, S <- S - C B with the diagonal
  * scaling of the LDL^T case):  C[M x N] -= A[M x K] diag(d[K]) B[N x K]^T.
  * lower != 0: C's (0,0) lies on the matrix diagonal and only entries with
- * column <= row are computed and stored (Gramian / lower-triangle case). */
+ * column <= row are computed and stored (Gramian / lower-triangle case).
+ * d == NULL: no scaling, C -= A B^T (the positive-definite form). */
 int mdet_step_schur_update(int32_t dtype, void* C, int64_t ldc, const void* A,
                            int64_t lda, const void* B, int64_t ldb, const void* d,
                            int64_t M, int64_t N, int64_t K, int32_t lower, void* stream);

@@ -19,10 +19,11 @@ FLAG_NO_LOOKAHEAD = 1
 FLAG_FORCE_OUT_OF_CORE = 2
 FLAG_PROFILE = 4
 FLAG_COMPUTE_F64 = 8
+FLAG_ASSUME_SPD = 16
 
 
 class Status:
-    OK, EINVAL, EBUDGET, ENOMEM_DEVICE, ENOMEM_HOST, EHIP, ESINGULAR, ENONFINITE, EPROVIDER = range(9)
+    OK, EINVAL, EBUDGET, ENOMEM_DEVICE, ENOMEM_HOST, EHIP, ESINGULAR, ENONFINITE, EPROVIDER, ENOTPOSDEF = range(10)
 
 
 class _Params(C.Structure):
@@ -213,7 +214,7 @@ def _result(status: int, r: _Result) -> LogdetResult:
                         r.t_trailing_update, r.trailing_update_flops, r.t_h2d, r.t_d2h)
 
 
-_SOFT = (Status.OK, Status.ESINGULAR, Status.ENONFINITE)
+_SOFT = (Status.OK, Status.ESINGULAR, Status.ENONFINITE, Status.ENOTPOSDEF)
 
 
 def mdet_strerror(status: int) -> str:
@@ -339,11 +340,12 @@ def mdet_paper_fma_count(m) -> float:
 
 
 def mdet_step_schur_update(c, a, b, d, lower=False, stream=None) -> None:
-    """c[M,N] -= a[M,K] diag(d) b[N,K]^T on the GPU (asynchronous)."""
+    """c[M,N] -= a[M,K] diag(d) b[N,K]^T on the GPU (asynchronous); d=None: c -= a b^T."""
     M, K = a.shape
     N = b.shape[0]
     st = load().mdet_step_schur_update(_dtype_code(c.dtype), c.data_ptr(), c.stride(0), a.data_ptr(),
-                                       a.stride(0), b.data_ptr(), b.stride(0), d.data_ptr(), M, N, K,
+                                       a.stride(0), b.data_ptr(), b.stride(0),
+                                       d.data_ptr() if d is not None else None, M, N, K,
                                        1 if lower else 0, _stream_handle(stream))
     if st != Status.OK:
         raise MemdetError(st)

@@ -238,10 +238,16 @@ __device__ __forceinline__ void leaf_tile_put(T* __restrict__ lds, int row, int 
     lds[row * LEAF_PAD + col] = (row < w && col < w) ? v : (row == col ? T(1) : T(0));
 }
 
+//
+// spd != 0: the positive-definite form.  The leaf is still factored as L D L^T, but
+// every pivot must be positive (the first that is not is reported with kind 4) and
+// dinv receives d^(-1/2) instead of 1/d: the rows below the leaf, solved with that
+// scaling, are then rows of the Cholesky factor L D^(1/2), and the updates that use
+// them need no pivots.
 template <typename T, bool IN_LDS = false>
 __device__ __forceinline__ void leaf_factor_body(
     T* __restrict__ A, int64_t ld, int w, T* __restrict__ dvec, T* __restrict__ dinv,
-    T* __restrict__ linv, long long pivot0, DevFlags* flags, T* __restrict__ lds) {
+    T* __restrict__ linv, long long pivot0, DevFlags* flags, T* __restrict__ lds, int spd = 0) {
   using X = Mfma<T>;
   using acc_t = typename X::acc_t;
   T* tile = lds;
@@ -323,15 +329,19 @@ __device__ __forceinline__ void leaf_factor_body(
   if (wave == 0) {
     const T myd = tile[lane * LEAF_PAD + lane];
     const bool zero = myd == T(0);
-    const bool bad = lane < w && (zero || !(fabs((double)myd) <= 1.7976931348623157e308));
-    if (lane < w) { dvec[lane] = myd; dinv[lane] = fast_rcp(myd); }
+    const bool finite = fabs((double)myd) <= 1.7976931348623157e308;
+    const bool bad = lane < w && (zero || !finite || (spd != 0 && myd < T(0)));
+    if (lane < w) {
+      dvec[lane] = myd;
+      dinv[lane] = spd != 0 ? T(1) / sqrt(myd) : fast_rcp(myd);
+    }
     const unsigned long long mask = __ballot(bad);
     if (mask != 0ull) {
       const int first = __ffsll((long long)mask) - 1;
       if (lane == first) {
         unsigned long long idx = (unsigned long long)(pivot0 + first);
         unsigned long long old = atomicMin(&flags->first_bad, idx);
-        if (idx <= old) atomicExch(&flags->bad_kind, zero ? 1ull : 2ull);
+        if (idx <= old) atomicExch(&flags->bad_kind, zero ? 1ull : (!finite ? 2ull : 4ull));
       }
     }
   }
@@ -350,9 +360,9 @@ __device__ __forceinline__ void leaf_factor_body(
 template <typename T>
 __global__ __launch_bounds__(FACTOR_THREADS) void leaf_factor_kernel(
     T* __restrict__ A, int64_t ld, int w, T* __restrict__ dvec, T* __restrict__ dinv,
-    T* __restrict__ linv, long long pivot0, DevFlags* flags) {
+    T* __restrict__ linv, long long pivot0, DevFlags* flags, int spd) {
   __shared__ T lds[FACTOR_LDS_ELEMS];
-  leaf_factor_body<T>(A, ld, w, dvec, dinv, linv, pivot0, flags, lds);
+  leaf_factor_body<T>(A, ld, w, dvec, dinv, linv, pivot0, flags, lds, spd);
 }
 
 // ---------------------------------------------------------------------------

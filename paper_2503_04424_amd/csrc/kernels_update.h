@@ -144,6 +144,7 @@ struct FusedLeaf {
   T* linv;
   long long pivot0;
   DevFlags* flags;
+  int spd;   // positive-definite form (see leaf_factor_body)
 };
 
 // TM = MFMA tiles per wavefront in each direction: 4 -> 128 x 128 block, 2 -> 64 x 64.
@@ -175,7 +176,12 @@ typedef __attribute__((address_space(3))) void* upd_lds_ptr;
 // then hit 16 different bank groups.  The scaling by -d is applied to the A
 // fragments as they come out of LDS (the same single rounding of a * (-d) as if
 // it were applied on the way in).
-template <typename T, int TM>
+//
+// SCALED: the positive-definite form, C -= A B^T with operands that carry D^(1/2)
+// already (rows of the Cholesky factor): no pivots are read and no fragment is
+// scaled.  The accumulators then start from -C, collect +A B^T and are negated on
+// the way out, which rounds exactly like C - A B^T term by term.
+template <typename T, int TM, bool SCALED = false>
 __device__ __forceinline__ void schur_update_block(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K,
@@ -285,9 +291,19 @@ __device__ __forceinline__ void schur_update_block(
   };
 
   gload(0, 0);
-  if (active) load_d(dcur, 0);
+  if (!SCALED && active) load_d(dcur, 0);
   landed();
   __syncthreads();
+  if constexpr (SCALED) {
+    // -C, in one go now that the loads have landed (negating each entry as it is
+    // loaded would make every load wait for itself)
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TM; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[i][j][r] = -acc[i][j][r];
+  }
 
   // One slab; MORE: another one follows (decided at compile time, so that the
   // stages of a slab form one straight run of instructions).  The next slab's loads
@@ -297,10 +313,12 @@ __device__ __forceinline__ void schur_update_block(
     const int buf = kt & 1;
     if (MORE) gload(kt + 1, buf ^ 1);
     if (active) {
-      if (MORE) load_d(dnext, kt + 1);
+      if (!SCALED && MORE) load_d(dnext, kt + 1);
       T nd[KS];                                         // -d, this lane's k's
+      if constexpr (!SCALED) {
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) { nd[e] = -dcur[0][e]; nd[VEC + e] = -dcur[1][e]; }
+        for (int e = 0; e < VEC; ++e) { nd[e] = -dcur[0][e]; nd[VEC + e] = -dcur[1][e]; }
+      }
       const T* as = &As[buf][(wm * WT + r16) * BK];
       const T* bs = &Bs[buf][(wn * WT + r16) * BK];
       // Fragments are fetched one 16-row strip at a time, each fetch issued one
@@ -315,8 +333,10 @@ __device__ __forceinline__ void schur_update_block(
         for (int e = 0; e < VEC; ++e) { f[e] = v0[e]; f[VEC + e] = v1[e]; }
       };
       auto scale = [&](T (&f)[KS]) {
+        if constexpr (!SCALED) {
 #pragma unroll
-        for (int e = 0; e < KS; ++e) f[e] *= nd[e];
+          for (int e = 0; e < KS; ++e) f[e] *= nd[e];
+        }
       };
       fetch(fa[0], as);
       fetch(fb[0], bs);
@@ -336,8 +356,10 @@ __device__ __forceinline__ void schur_update_block(
     }
     if (MORE) {
       landed();
-      dcur[0] = dnext[0];
-      dcur[1] = dnext[1];
+      if constexpr (!SCALED) {
+        dcur[0] = dnext[0];
+        dcur[1] = dnext[1];
+      }
     }
     __syncthreads();
   };
@@ -358,7 +380,7 @@ __device__ __forceinline__ void schur_update_block(
 #pragma unroll
         for (int j = 0; j < TM; ++j)
           leaf_tile_put<T>(lds, wm * WT + i * 16 + X::acc_row(lane, r), wn * WT + j * 16 + r16,
-                           wleaf, acc[i][j][r]);
+                           wleaf, SCALED ? -acc[i][j][r] : acc[i][j][r]);
   }
   if (active) {
 #pragma unroll
@@ -372,19 +394,20 @@ __device__ __forceinline__ void schur_update_block(
         for (int j = 0; j < TM; ++j) {
           const int gcol = col0 + wn * WT + j * 16 + r16;
           if (gcol < N && (!lower || gcol <= grow) && !(grow < wleaf && gcol < wleaf))
-            crow[gcol] = acc[i][j][r];
+            crow[gcol] = SCALED ? -acc[i][j][r] : acc[i][j][r];
         }
       }
     }
   }
   if (fuse) {
     __syncthreads();
-    leaf_factor_body<T, true>(C, ldc, fl.w, fl.dvec, fl.dinv, fl.linv, fl.pivot0, fl.flags, lds);
+    leaf_factor_body<T, true>(C, ldc, fl.w, fl.dvec, fl.dinv, fl.linv, fl.pivot0, fl.flags, lds,
+                              fl.spd);
   }
 }
 
 // One block per workgroup.
-template <typename T, int TM>
+template <typename T, int TM, bool SCALED = false>
 __device__ __forceinline__ void schur_update_body(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K,
@@ -395,7 +418,7 @@ __device__ __forceinline__ void schur_update_body(
   if (!update_block_of(lower, blockIdx.x, per, k0, (M + Sh::BM - 1) / Sh::BM,
                        (N + Sh::BN - 1) / Sh::BN, nsn, swl, bm, bn))
     return;
-  schur_update_block<T, TM>(C, ldc, A, lda, B, ldb, d, M, N, K, lower, bm, bn, fl, lds);
+  schur_update_block<T, TM, SCALED>(C, ldc, A, lda, B, ldb, d, M, N, K, lower, bm, bn, fl, lds);
 }
 
 // Names for the same body: the update of the trailing matrix by a finished block
@@ -404,35 +427,35 @@ __device__ __forceinline__ void schur_update_body(
 // launches over more compute units).  The latter sit on the chain of dependent
 // launches and often share SIMDs with a workgroup of the former: they run at a
 // raised wave priority.
-template <typename T>
+template <typename T, bool SCALED = false>
 __global__ __launch_bounds__(UPD_THREADS, 2) void trailing_update_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nsn,
     int swl, int lower, int per, int k0, FusedLeaf<T> fl) {
-  schur_update_body<T, 4>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn, swl, lower != 0, per, k0, fl);
+  schur_update_body<T, 4, SCALED>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn, swl, lower != 0, per, k0, fl);
 }
-template <typename T>
+template <typename T, bool SCALED = false>
 __global__ __launch_bounds__(UPD_THREADS, 2) void panel_update_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nsn,
     int swl, int lower, int per, int k0, FusedLeaf<T> fl) {
   __builtin_amdgcn_s_setprio(2);
-  schur_update_body<T, 4>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn, swl, lower != 0, per, k0, fl);
+  schur_update_body<T, 4, SCALED>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn, swl, lower != 0, per, k0, fl);
 }
-template <typename T>
+template <typename T, bool SCALED = false>
 __global__ __launch_bounds__(UPD_THREADS) void panel_update64_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nsn,
     int swl, int lower, int per, int k0, FusedLeaf<T> fl) {
   __builtin_amdgcn_s_setprio(2);
-  schur_update_body<T, 2>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn, swl, lower != 0, per, k0, fl);
+  schur_update_body<T, 2, SCALED>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn, swl, lower != 0, per, k0, fl);
 }
 
 // K = 64 exactly (the update of the columns right of a leaf by that leaf): both
 // operands, the pivots and the C block are requested in one go and the whole
 // product runs from LDS, so the launch costs one memory round trip instead of one
 // per slab.  64 x 64 block of C per workgroup, 2 x 2 MFMA tiles per wavefront.
-template <typename T>
+template <typename T, bool SCALED = false>
 __global__ __launch_bounds__(UPD_THREADS) void leaf_update_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int nsn, int swl,
@@ -472,7 +495,7 @@ __global__ __launch_bounds__(UPD_THREADS) void leaf_update_kernel(
   for (int v = 0; v < NV; ++v) {
     ra[v] = *reinterpret_cast<const vec_t*>(Ap + v * VEC);
     rb[v] = *reinterpret_cast<const vec_t*>(Bp + v * VEC);
-    rd[v] = *reinterpret_cast<const vec_t*>(dp + v * VEC);
+    if constexpr (!SCALED) rd[v] = *reinterpret_cast<const vec_t*>(dp + v * VEC);
   }
   acc_t acc[2][2];
 #pragma unroll
@@ -499,7 +522,8 @@ __global__ __launch_bounds__(UPD_THREADS) void leaf_update_kernel(
     T* bs = &Bs[srow * S + sq * NV * VEC];
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
-      *reinterpret_cast<vec_t*>(as + v * VEC) = -(ra[v] * rd[v]);
+      if constexpr (SCALED) *reinterpret_cast<vec_t*>(as + v * VEC) = -ra[v];
+      else *reinterpret_cast<vec_t*>(as + v * VEC) = -(ra[v] * rd[v]);
       *reinterpret_cast<vec_t*>(bs + v * VEC) = rb[v];
     }
   }
@@ -558,7 +582,8 @@ __global__ __launch_bounds__(UPD_THREADS) void leaf_update_kernel(
   }
   if (fuse) {
     __syncthreads();
-    leaf_factor_body<T, true>(C, ldc, fl.w, fl.dvec, fl.dinv, fl.linv, fl.pivot0, fl.flags, lds);
+    leaf_factor_body<T, true>(C, ldc, fl.w, fl.dvec, fl.dinv, fl.linv, fl.pivot0, fl.flags, lds,
+                              fl.spd);
   }
 }
 

@@ -124,6 +124,7 @@ struct Launcher {
   T* dinv = nullptr;
   T* linv = nullptr;          // inverses of the current leaf's diagonal sub-blocks
   DevFlags* flags = nullptr;
+  bool spd = false;           // positive-definite form (MDET_FLAG_ASSUME_SPD)
   int slots = 0;              // trailing-update workgroups the device holds at one time
   double fma = 0.0;
   uint64_t launches = 0;
@@ -161,7 +162,7 @@ struct Launcher {
     const int tile = (leaf_k || small) ? 64 : 128;
     const UpdGrid ug = update_grid(M, N, lower, tile);
     if (8 * ug.per > INT32_MAX) return MDET_EINVAL;
-    FusedLeaf<T> fl{0, nullptr, nullptr, nullptr, 0, nullptr};
+    FusedLeaf<T> fl{0, nullptr, nullptr, nullptr, 0, nullptr, 0};
     if (fuse) {
       if (!lower || fuse->w > LEAF || fuse->w > N || fuse->w > M) return MDET_EINVAL;
       fl = *fuse;
@@ -182,16 +183,26 @@ struct Launcher {
         e1 = timing_event_get(fail);
         fail->check(hipEventRecord(e0, st));
       }
+#define MDET_LAUNCH_UPD_AS(KERNEL, SCALED)                                                         \
+  hipLaunchKernelGGL((KERNEL<T, SCALED>), grid, block, 0, st, C, ldc, A, lda, B, ldb, d, (int)M,  \
+                     (int)N, (int)K, ug.nsn, ug.swl, (int)lower, (int)ug.per, (int)k0, fl)
 #define MDET_LAUNCH_UPD(KERNEL)                                                                   \
-  hipLaunchKernelGGL((KERNEL<T>), grid, block, 0, st, C, ldc, A, lda, B, ldb, d, (int)M, (int)N,  \
-                     (int)K, ug.nsn, ug.swl, (int)lower, (int)ug.per, (int)k0, fl)
+  do {                                                                                            \
+    if (spd) MDET_LAUNCH_UPD_AS(KERNEL, true);                                                    \
+    else MDET_LAUNCH_UPD_AS(KERNEL, false);                                                       \
+  } while (0)
       if (trailing) MDET_LAUNCH_UPD(trailing_update_kernel);
-      else if (leaf_k)
-        hipLaunchKernelGGL((leaf_update_kernel<T>), grid, block, 0, st, C, ldc, A, lda, B, ldb, d,
-                           (int)M, (int)N, ug.nsn, ug.swl, (int)lower, (int)ug.per, fl);
-      else if (small) MDET_LAUNCH_UPD(panel_update64_kernel);
+      else if (leaf_k) {
+        if (spd)
+          hipLaunchKernelGGL((leaf_update_kernel<T, true>), grid, block, 0, st, C, ldc, A, lda, B, ldb,
+                             d, (int)M, (int)N, ug.nsn, ug.swl, (int)lower, (int)ug.per, fl);
+        else
+          hipLaunchKernelGGL((leaf_update_kernel<T, false>), grid, block, 0, st, C, ldc, A, lda, B, ldb,
+                             d, (int)M, (int)N, ug.nsn, ug.swl, (int)lower, (int)ug.per, fl);
+      } else if (small) MDET_LAUNCH_UPD(panel_update64_kernel);
       else MDET_LAUNCH_UPD(panel_update_kernel);
 #undef MDET_LAUNCH_UPD
+#undef MDET_LAUNCH_UPD_AS
       ++launches;
       if (timed) {
         fail->check(hipEventRecord(e1, st));
@@ -225,7 +236,8 @@ struct Launcher {
   // What an update launch needs to factor the leaf of width w whose first pivot has
   // index d0 (see FusedLeaf).
   FusedLeaf<T> fused_leaf(int64_t w, int64_t d0) const {
-    return FusedLeaf<T>{(int)(w < LEAF ? w : LEAF), dvec + d0, dinv + d0, linv, (long long)d0, flags};
+    return FusedLeaf<T>{(int)(w < LEAF ? w : LEAF), dvec + d0, dinv + d0, linv, (long long)d0, flags,
+                        spd ? 1 : 0};
   }
 
   // Factor block column: P at its diagonal entry, m rows, w columns (w <= m).
@@ -237,7 +249,7 @@ struct Launcher {
     if (w <= LEAF) {
       if (!first_done) {
         hipLaunchKernelGGL((leaf_factor_kernel<T>), dim3(1), dim3(FACTOR_THREADS), 0, st, P, ld,
-                           (int)w, dvec + d0, dinv + d0, linv, (long long)d0, flags);
+                           (int)w, dvec + d0, dinv + d0, linv, (long long)d0, flags, spd ? 1 : 0);
         fail->check(hipGetLastError());
         ++launches;
       }
@@ -425,6 +437,11 @@ static int finish_result(const DeviceOut& o, mdet_result* r) {
       r->logabsdet = -HUGE_VAL;
       return MDET_ESINGULAR;
     }
+    if (o.flags.bad_kind == 4) {
+      r->sign = 0;
+      r->logabsdet = std::nan("");
+      return MDET_ENOTPOSDEF;
+    }
     r->sign = 0;
     r->logabsdet = std::nan("");
     return MDET_ENONFINITE;
@@ -514,6 +531,7 @@ static int logdet_device_t(const mdet_params& p, const Plan& pl, T* dA, int64_t 
   Launcher<T> L;
   L.fail = &fail;
   L.profile = (p.flags & MDET_FLAG_PROFILE) != 0;
+  L.spd = (p.flags & MDET_FLAG_ASSUME_SPD) != 0;
   bind_small(L, ws.base, sa);
   double* partial = (double*)(ws.base + sa.partial);
   double* out = (double*)(ws.base + sa.out);
@@ -650,6 +668,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
   Launcher<T> L;
   L.fail = &fail;
   L.profile = (p.flags & MDET_FLAG_PROFILE) != 0;
+  L.spd = (p.flags & MDET_FLAG_ASSUME_SPD) != 0;
   bind_small(L, ws.base, sa);
   double* partial = (double*)(ws.base + sa.partial);
   double* out = (double*)(ws.base + sa.out);
@@ -921,6 +940,7 @@ const char* mdet_strerror(int s) {
     case MDET_ESINGULAR: return "matrix is singular: exact zero pivot";
     case MDET_ENONFINITE: return "non-finite pivot";
     case MDET_EPROVIDER: return "block provider failed";
+    case MDET_ENOTPOSDEF: return "matrix is not positive definite: a pivot is negative";
     default: return "unknown status";
   }
 }
@@ -1003,17 +1023,19 @@ int mdet_logdet_device(const mdet_params* p, void* dA, int64_t ld, mdet_result* 
 int mdet_step_schur_update(int32_t dtype, void* C, int64_t ldc, const void* A, int64_t lda,
                            const void* B, int64_t ldb, const void* d, int64_t M, int64_t N,
                            int64_t K, int32_t lower, void* stream) {
-  if (!C || !A || !B || !d || M < 0 || N < 0 || K < 0) return MDET_EINVAL;
+  if (!C || !A || !B || M < 0 || N < 0 || K < 0) return MDET_EINVAL;
   HipFail fail;
   int rc;
+  // d == NULL: the positive-definite form, C -= A B^T (the operand pointer stands in for the
+  // pivots the launcher's alignment check looks at; the kernel never reads them)
   if (dtype == MDET_F64) {
-    Launcher<double> L; L.fail = &fail;
+    Launcher<double> L; L.fail = &fail; L.spd = d == nullptr;
     rc = L.update((hipStream_t)stream, (double*)C, ldc, (const double*)A, lda, (const double*)B, ldb,
-                  (const double*)d, M, N, K, lower != 0, true);
+                  (const double*)(d ? d : A), M, N, K, lower != 0, true);
   } else if (dtype == MDET_F32) {
-    Launcher<float> L; L.fail = &fail;
+    Launcher<float> L; L.fail = &fail; L.spd = d == nullptr;
     rc = L.update((hipStream_t)stream, (float*)C, ldc, (const float*)A, lda, (const float*)B, ldb,
-                  (const float*)d, M, N, K, lower != 0, true);
+                  (const float*)(d ? d : A), M, N, K, lower != 0, true);
   } else return MDET_EINVAL;
   if (!fail.ok()) return MDET_EHIP;
   return rc;
