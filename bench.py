@@ -187,6 +187,8 @@ def main():
                     help="diagnostic: run every kernel on one stream, nothing overlapped")
     ap.add_argument("--compute-f64", action="store_true",
                     help="with --dtype f32 (in-core): fp32 storage, fp64 arithmetic")
+    ap.add_argument("--scaled-copy", action="store_true",
+                    help="in-core: MDET_FLAG_SCALED_COPY (2 n block_size elements more workspace)")
     ap.add_argument("--assume-spd", action="store_true",
                     help="the positive-definite (Cholesky) form of the method instead of LDL^T")
     ap.add_argument("--kernels", action="store_true",
@@ -229,6 +231,8 @@ def main():
         xflags |= M.FLAG_COMPUTE_F64
     if args.assume_spd:
         xflags |= M.FLAG_ASSUME_SPD
+    if args.scaled_copy:
+        xflags |= M.FLAG_SCALED_COPY
     results = []
     if not out_of_core:
         a = form_matrix_device(w, torch)
@@ -324,7 +328,8 @@ def main():
                    if out_of_core else "HBM, in-core",
                    "mem_budget_bytes": w.mem_budget, "seed": w.seed,
                    **({"storage": "f32, widened exactly; arithmetic f64"} if widen else {}),
-                   **({"form": "positive definite (Cholesky), MDET_FLAG_ASSUME_SPD"} if args.assume_spd else {})},
+                   **({"form": "positive definite (Cholesky), MDET_FLAG_ASSUME_SPD"} if args.assume_spd else {}),
+                   **({"workspace": "MDET_FLAG_SCALED_COPY"} if args.scaled_copy else {})},
         "time_to_logdet_s": sec, "frac_of_matrix_peak": value / peak,
         "logabsdet": final.logabsdet, "sign": final.sign, "negative_pivots": final.negative_pivots,
         "kernel_launches_per_step": final.kernel_launches,

@@ -99,6 +99,14 @@ typedef struct mdet_params {
 #define MDET_FLAG_PROFILE 4u      /* bracket every trailing-update launch with HIP
                                      events on its own stream and report the sums in
                                      result->t_trailing_update etc.                 */
+#define MDET_FLAG_SCALED_COPY 32u /* speed for memory: 2 n block_size further elements of
+                                     device workspace hold, for the block column being
+                                     factored, its rows scaled by the pivots (W = L D),
+                                     so that the Schur updates read their left operand
+                                     ready-made instead of scaling it on the fly.  Same
+                                     bits in the result.  Used where the whole matrix is
+                                     resident and the budget allows; ignored otherwise
+                                     and with MDET_FLAG_ASSUME_SPD (nothing to scale).  */
 #define MDET_FLAG_ASSUME_SPD 16u  /* the matrix is symmetric positive definite: use the
                                      Cholesky form of the method (the paper's algorithm
                                      for positive-definite matrices, App. D; block

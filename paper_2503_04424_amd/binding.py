@@ -20,6 +20,7 @@ FLAG_FORCE_OUT_OF_CORE = 2
 FLAG_PROFILE = 4
 FLAG_COMPUTE_F64 = 8
 FLAG_ASSUME_SPD = 16
+FLAG_SCALED_COPY = 32
 
 
 class Status:

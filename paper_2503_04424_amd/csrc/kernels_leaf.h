@@ -6,7 +6,10 @@
 // leaf_solve_kernel  : rows below the leaf, X = A_rows L^-T D^-1
 //                      (Sec. 2.2: in-place triangular solve of the off-diagonal
 //                      blocks; App. E.1 "solve lower triangular system"; the
-//                      D^-1 is the LDL^T "diagonal scaling").
+//                      D^-1 is the LDL^T "diagonal scaling").  On request also
+//                      W = X D into a second array, for the rows from `wfrom` on:
+//                      the operand of the Schur updates with the scaling applied,
+//                      rounded as the update kernels round l * d.
 //
 // Both work on 16-column sub-blocks: the sequential part (elimination inside a
 // 16 x 16 diagonal sub-block) runs on the vector ALUs with one matrix row per lane,
@@ -379,7 +382,8 @@ constexpr int SOLVE_ROWS = 64;   // rows per workgroup
 template <typename T>
 __global__ __launch_bounds__(256) void leaf_solve_kernel(
     T* __restrict__ Xg, int64_t ld, int m, int w, const T* __restrict__ Lleaf, int64_t ldl,
-    const T* __restrict__ dinv, const T* __restrict__ linv) {
+    const T* __restrict__ dinv, const T* __restrict__ linv, T* __restrict__ Wg, int64_t ldw,
+    const T* __restrict__ dvec, int wfrom) {
   using X = Mfma<T>;
   using acc_t = typename X::acc_t;
   // Only the sub-blocks L[b, p], p < b, and the solved W_p, p < NSUB - 1, are ever
@@ -391,6 +395,7 @@ __global__ __launch_bounds__(256) void leaf_solve_kernel(
   __shared__ T Ls[LW * LW_PAD];                 // L[16.., ..47], strictly lower part
   __shared__ T Li[NSUB * SUB * SUB_PAD];        // inverses of its diagonal sub-blocks
   __shared__ T rinv[LEAF];
+  __shared__ T dsc[LEAF];                       // pivots (only read when Wg is given)
   __shared__ T wsc[4][SUB * LW_PAD];            // per wavefront: solved W, row-major
   __shared__ T tsc[4][SUB * SUB_PAD];           // per wavefront: layout change of T_b
   __builtin_amdgcn_s_setprio(2);                // on the chain of dependent launches
@@ -420,6 +425,7 @@ __global__ __launch_bounds__(256) void leaf_solve_kernel(
 #pragma unroll
     for (int q = 0; q < NSUB * SUB * SUB / 256; ++q) u[q] = linv[q * 256 + tid];
     const T myr = (tid < LEAF && tid < w) ? dinv[tid < LEAF ? tid : 0] : T(0);
+    const T myd = (Wg != nullptr && tid < LEAF && tid < w) ? dvec[tid < LEAF ? tid : 0] : T(0);
 #pragma unroll
     for (int q = 0; q < LEAF * LEAF / 256; ++q) {
       const int e = q * 256 + tid, r = e >> 6, c = e & 63;
@@ -430,7 +436,7 @@ __global__ __launch_bounds__(256) void leaf_solve_kernel(
       const int e = q * 256 + tid, blk = e >> 8, i = (e >> 4) & 15, k = e & 15;
       Li[(blk * SUB + i) * SUB_PAD + k] = u[q];
     }
-    if (tid < LEAF) rinv[tid] = myr;
+    if (tid < LEAF) { rinv[tid] = myr; dsc[tid] = myd; }
   }
   __syncthreads();
 
@@ -463,13 +469,18 @@ __global__ __launch_bounds__(256) void leaf_solve_kernel(
       wb = X::mfma(ts[l16 * SUB_PAD + k], Li[(b * SUB + l16) * SUB_PAD + k], wb);
     }
     const T rj = rinv[b * SUB + l16];
+    const T dj = dsc[b * SUB + l16];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int row16 = X::acc_row(lane, r);
       if (b < NSUB - 1) ws[row16 * LW_PAD + b * SUB + l16] = wb[r];
       const int64_t row = r0 + row16;
       const int col = b * SUB + l16;
-      if (row < m && col < w) Xg[row * ld + col] = wb[r] * rj;
+      if (row < m && col < w) {
+        const T lv = wb[r] * rj;
+        Xg[row * ld + col] = lv;
+        if (Wg != nullptr && row >= wfrom) Wg[row * ldw + col] = lv * dj;
+      }
     }
   }
 }

@@ -32,6 +32,7 @@ struct Plan {
   uint64_t small_bytes = 0;        // pivots, reciprocals, flags, reduction scratch
   uint64_t layout_bytes = 0;       // packed lower block-column layout
   uint64_t copy_bytes = 0;
+  uint64_t wcopy_bytes = 0;        // two pivot-scaled copies of a block column (MDET_FLAG_SCALED_COPY)
   uint64_t ring_tiles = 3;         // streamed row blocks in flight (out-of-core)
   uint64_t tile_bytes = 0;
   uint64_t dev_bytes = 0;          // total device bytes the call uses
@@ -105,6 +106,11 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
   pl.h2d = pl.d2h = 0;
   pl.host_bytes = 0;
   const uint64_t budget = p.mem_budget_bytes;
+  // optional: room for W = L D of the block column being factored and of the one whose
+  // bulk update is still running; taken only where everything is resident and it fits
+  pl.wcopy_bytes = 0;
+  const uint64_t wcopy = ((p.flags & MDET_FLAG_SCALED_COPY) && !(p.flags & MDET_FLAG_ASSUME_SPD) && pl.T >= 2)
+                             ? 2 * align256((uint64_t)pl.n * pl.bs * pl.beta) : 0;
 
   if (device_input) {
     const int vec = 16 / pl.beta;
@@ -117,6 +123,10 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
     pl.dev_bytes = pl.small_bytes + pl.copy_bytes;
     pl.out_of_core = false;
     if (budget && pl.dev_bytes > budget) return MDET_EBUDGET;
+    if (wcopy && (!budget || pl.dev_bytes + wcopy <= budget)) {
+      pl.wcopy_bytes = wcopy;
+      pl.dev_bytes += wcopy;
+    }
     return MDET_OK;
   }
 
@@ -127,6 +137,10 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
   if (!force_ooc && (budget == 0 || incore <= budget)) {
     pl.out_of_core = false;
     pl.dev_bytes = incore;
+    if (wcopy && (!budget || incore + wcopy <= budget)) {
+      pl.wcopy_bytes = wcopy;
+      pl.dev_bytes += wcopy;
+    }
     pl.h2d = pl.layout_bytes;
     pl.panels.push_back({0, pl.T, pl.layout_bytes});
     return MDET_OK;

@@ -306,3 +306,31 @@ def test_budget_is_enforced_for_device_copy(M):
     assert ei.value.status == M.Status.EBUDGET
     res = M.mdet_logdet_device(a, block_size=128, overwrite=True, mem_budget=1 << 20)
     assert res.status == 0 and res.dev_bytes_high_water <= (1 << 20)
+
+
+@pytest.mark.parametrize("cfg,n,bs,dtype", [(1, 512, 128, "f64"), (2, 1536, 256, "f64"), (3, 2304, 512, "f64"),
+                                            (5, 1100, 192, "f64"), (1, 1000, 64, "f32"), (3, 4608, 1024, "f64")])
+def test_scaled_copy_gives_the_same_bits(M, cfg, n, bs, dtype):
+    # MDET_FLAG_SCALED_COPY: the updates read W = L D from a second array instead of scaling
+    # L on the fly; every product and every sum is the same
+    w = W.scaled_down(W.config(cfg, dtype), n, bs)
+    a = w.dense().astype(np.float64 if dtype == "f64" else np.float32)
+    ref = M.mdet_logdet_device(dev(a), block_size=bs)
+    diag = torch.empty(n, dtype=torch.float64 if dtype == "f64" else torch.float32, device="cuda")
+    res = M.mdet_logdet_device(dev(a), block_size=bs, flags=M.FLAG_SCALED_COPY, diag=diag)
+    assert res.status == 0 and res.logabsdet == ref.logabsdet and res.sign == ref.sign
+    plain = M.mdet_plan(n, dtype, bs, overwrite=False, for_device_input=True)
+    extra = M.mdet_plan(n, dtype, bs, overwrite=False, for_device_input=True, flags=M.FLAG_SCALED_COPY)
+    beta = 8 if dtype == "f64" else 4
+    rounded_bs = (bs + 63) // 64 * 64
+    assert extra.dev_bytes_needed - plain.dev_bytes_needed == 2 * ((n * rounded_bs * beta + 255) // 256 * 256)
+    assert res.dev_bytes_high_water == extra.dev_bytes_needed
+    # host entry point, everything resident
+    h = M.pack_lower_block_columns(torch.from_numpy(a), bs, pin=True)
+    hres = M.mdet_logdet_host(h, n, bs, flags=M.FLAG_SCALED_COPY)
+    assert hres.logabsdet == ref.logabsdet
+    # a budget that has no room for the copies: the flag is ignored, not an error
+    tight = M.mdet_logdet_device(dev(a), block_size=bs, flags=M.FLAG_SCALED_COPY,
+                                 mem_budget=plain.dev_bytes_needed + 4096)
+    assert tight.logabsdet == ref.logabsdet and tight.dev_bytes_high_water == plain.dev_bytes_needed
+
