@@ -177,10 +177,12 @@ typedef __attribute__((address_space(3))) void* upd_lds_ptr;
 // fragments as they come out of LDS (the same single rounding of a * (-d) as if
 // it were applied on the way in).
 //
-// SCALED: the positive-definite form, C -= A B^T with operands that carry D^(1/2)
-// already (rows of the Cholesky factor): no pivots are read and no fragment is
-// scaled.  The accumulators then start from -C, collect +A B^T and are negated on
-// the way out, which rounds exactly like C - A B^T term by term.
+// SCALED: C -= A B^T with operands that carry the diagonal scaling already (rows of
+// the Cholesky factor, or a left operand L D): no pivots are read and no fragment is
+// scaled.
+// In both forms the accumulators start from -C, collect +A D B^T and are negated on
+// the way out, which rounds exactly like C - A D B^T term by term and needs neither a
+// negated operand nor a negated pivot.
 template <typename T, int TM, bool SCALED = false>
 __device__ __forceinline__ void schur_update_block(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
@@ -247,7 +249,7 @@ __device__ __forceinline__ void schur_update_block(
 
   const int r16 = lane & 15, g = lane >> 4;
 
-  // The accumulators start from C and the (negated) products are added to them in
+  // The accumulators start from (minus) C and the products are added to them in
   // K order, so every entry is reduced term by term exactly as in the unblocked
   // recurrence a_ij - sum_k l_ik d_k l_jk; when the Schur complement is much
   // smaller than a_ij (low-rank Gram matrix plus a small shift) the late roundings
@@ -294,7 +296,7 @@ __device__ __forceinline__ void schur_update_block(
   if (!SCALED && active) load_d(dcur, 0);
   landed();
   __syncthreads();
-  if constexpr (SCALED) {
+  {
     // -C, in one go now that the loads have landed (negating each entry as it is
     // loaded would make every load wait for itself)
 #pragma unroll
@@ -314,10 +316,10 @@ __device__ __forceinline__ void schur_update_block(
     if (MORE) gload(kt + 1, buf ^ 1);
     if (active) {
       if (!SCALED && MORE) load_d(dnext, kt + 1);
-      T nd[KS];                                         // -d, this lane's k's
+      T nd[KS];                                         // d, this lane's k's
       if constexpr (!SCALED) {
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) { nd[e] = -dcur[0][e]; nd[VEC + e] = -dcur[1][e]; }
+        for (int e = 0; e < VEC; ++e) { nd[e] = dcur[0][e]; nd[VEC + e] = dcur[1][e]; }
       }
       const T* as = &As[buf][(wm * WT + r16) * BK];
       const T* bs = &Bs[buf][(wn * WT + r16) * BK];
@@ -380,7 +382,7 @@ __device__ __forceinline__ void schur_update_block(
 #pragma unroll
         for (int j = 0; j < TM; ++j)
           leaf_tile_put<T>(lds, wm * WT + i * 16 + X::acc_row(lane, r), wn * WT + j * 16 + r16,
-                           wleaf, SCALED ? -acc[i][j][r] : acc[i][j][r]);
+                           wleaf, -acc[i][j][r]);
   }
   if (active) {
 #pragma unroll
@@ -394,7 +396,7 @@ __device__ __forceinline__ void schur_update_block(
         for (int j = 0; j < TM; ++j) {
           const int gcol = col0 + wn * WT + j * 16 + r16;
           if (gcol < N && (!lower || gcol <= grow) && !(grow < wleaf && gcol < wleaf))
-            crow[gcol] = SCALED ? -acc[i][j][r] : acc[i][j][r];
+            crow[gcol] = -acc[i][j][r];
         }
       }
     }
