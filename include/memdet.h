@@ -35,7 +35,9 @@
 extern "C" {
 #endif
 
-typedef enum { MDET_F32 = 0, MDET_F64 = 1 } mdet_dtype;
+/* MDET_F16 (IEEE binary16) and MDET_BF16 are storage formats only: accepted by
+ * mdet_logdet_device together with MDET_FLAG_COMPUTE_F64, nowhere else. */
+typedef enum { MDET_F32 = 0, MDET_F64 = 1, MDET_F16 = 2, MDET_BF16 = 3 } mdet_dtype;
 
 typedef enum {
   MDET_OK = 0,
@@ -86,8 +88,9 @@ typedef struct mdet_params {
                                      (results are bit-identical either way)        */
 #define MDET_FLAG_FORCE_OUT_OF_CORE 2u /* host entry points: stream blocks even if the
                                      whole triangle would fit in the budget         */
-#define MDET_FLAG_COMPUTE_F64 8u  /* dtype = MDET_F32, mdet_logdet_device only: the
-                                     matrix is STORED in fp32 and every arithmetic step
+#define MDET_FLAG_COMPUTE_F64 8u  /* dtype = MDET_F32, MDET_F16 or MDET_BF16,
+                                     mdet_logdet_device only: the matrix is STORED in
+                                     that format and every arithmetic step
                                      runs in fp64 on the exactly widened values (App. C,
                                      data-precision pipeline, stage 3: whatever precision
                                      the matrix was stored in, the log-determinant is

@@ -14,7 +14,7 @@ from typing import Callable, Optional
 
 from . import build as _build
 
-MDET_F32, MDET_F64 = 0, 1
+MDET_F32, MDET_F64, MDET_F16, MDET_BF16 = 0, 1, 2, 3
 FLAG_NO_LOOKAHEAD = 1
 FLAG_FORCE_OUT_OF_CORE = 2
 FLAG_PROFILE = 4
@@ -178,7 +178,7 @@ class PlanInfo:
 
 def _dtype_code(dtype) -> int:
     if isinstance(dtype, int):
-        if dtype in (MDET_F32, MDET_F64):
+        if dtype in (MDET_F32, MDET_F64, MDET_F16, MDET_BF16):
             return dtype
         raise ValueError(f"unsupported dtype {dtype!r}")
     s = str(dtype)
@@ -186,6 +186,10 @@ def _dtype_code(dtype) -> int:
         return MDET_F64
     if s in ("f32", "float32", "torch.float32"):
         return MDET_F32
+    if s in ("f16", "float16", "torch.float16"):
+        return MDET_F16
+    if s in ("bf16", "bfloat16", "torch.bfloat16"):
+        return MDET_BF16
     raise ValueError(f"unsupported dtype {dtype!r}")
 
 

@@ -67,15 +67,29 @@ __global__ void logdet_combine_kernel(const double* __restrict__ partial, int64_
   out[2] = neg;
 }
 
-// fp32 -> fp64 copy of the part of a row-major matrix the factorisation reads: row i
-// up to the end of its 64-column leaf on the diagonal.  Widening is exact.
-__global__ __launch_bounds__(256) void widen_lower_kernel(const float* __restrict__ src, int64_t lds,
+// Storage formats that are only ever widened: IEEE binary16 and bfloat16, as raw bits.
+struct StoredF16 { uint16_t bits; };
+struct StoredBF16 { uint16_t bits; };
+__device__ __forceinline__ double widen_exact(float v) { return (double)v; }
+__device__ __forceinline__ double widen_exact(StoredF16 v) {
+  _Float16 h;
+  __builtin_memcpy(&h, &v.bits, 2);
+  return (double)h;
+}
+__device__ __forceinline__ double widen_exact(StoredBF16 v) {
+  return (double)__uint_as_float((uint32_t)v.bits << 16);     // bfloat16 = the upper half of a float
+}
+
+// fp32 / fp16 / bf16 -> fp64 copy of the part of a row-major matrix the factorisation
+// reads: row i up to the end of its 64-column leaf on the diagonal.  Widening is exact.
+template <typename S>
+__global__ __launch_bounds__(256) void widen_lower_kernel(const S* __restrict__ src, int64_t lds,
                                                           double* __restrict__ dst, int64_t ldd,
                                                           int64_t n) {
   const int64_t i = blockIdx.x;
   int64_t end = (i / 64 + 1) * 64;
   if (end > n) end = n;
-  for (int64_t j = threadIdx.x; j < end; j += 256) dst[i * ldd + j] = (double)src[i * lds + j];
+  for (int64_t j = threadIdx.x; j < end; j += 256) dst[i * ldd + j] = widen_exact(src[i * lds + j]);
 }
 
 }  // namespace mdet

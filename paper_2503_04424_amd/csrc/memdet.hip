@@ -536,7 +536,7 @@ static void reset_flags(Launcher<T>& L, hipStream_t st) {
 // ---------------------------------------------------------------------------
 template <typename T>
 static int logdet_device_t(const mdet_params& p, const Plan& pl, T* dA, int64_t ld, mdet_result* res,
-                           T* diag, const float* widen_from = nullptr) {
+                           T* diag, const void* widen_from = nullptr) {
   HipFail fail;
   int dev = 0;
   MDET_HIP(fail, hipGetDevice(&dev));
@@ -574,8 +574,16 @@ static int logdet_device_t(const mdet_params& p, const Plan& pl, T* dA, int64_t 
     ldw = round_up(pl.n, vec);
     W = (T*)(ws.base + sa.total);
     if (widen_from) {
-      hipLaunchKernelGGL(widen_lower_kernel, dim3((unsigned)pl.n), dim3(256), 0, s0, widen_from, ld,
-                         (double*)W, ldw, pl.n);
+      const dim3 grid((unsigned)pl.n), block(256);
+      if (p.dtype == MDET_F16)
+        hipLaunchKernelGGL((widen_lower_kernel<StoredF16>), grid, block, 0, s0,
+                           (const StoredF16*)widen_from, ld, (double*)W, ldw, pl.n);
+      else if (p.dtype == MDET_BF16)
+        hipLaunchKernelGGL((widen_lower_kernel<StoredBF16>), grid, block, 0, s0,
+                           (const StoredBF16*)widen_from, ld, (double*)W, ldw, pl.n);
+      else
+        hipLaunchKernelGGL((widen_lower_kernel<float>), grid, block, 0, s0, (const float*)widen_from,
+                           ld, (double*)W, ldw, pl.n);
       MDET_HIP(fail, hipGetLastError());
     } else {
       MDET_HIP(fail, hipMemcpy2DAsync(W, ldw * sizeof(T), dA, ld * sizeof(T), pl.n * sizeof(T), pl.n,
@@ -957,7 +965,7 @@ using namespace mdet;
 
 static bool params_ok(const mdet_params* p) {
   return p && p->struct_size == sizeof(mdet_params) && p->n >= 0 && p->block_size >= 0 &&
-         (p->dtype == MDET_F32 || p->dtype == MDET_F64);
+         (p->dtype == MDET_F32 || p->dtype == MDET_F64 || p->dtype == MDET_F16 || p->dtype == MDET_BF16);
 }
 
 extern "C" {
@@ -1047,7 +1055,7 @@ int mdet_logdet_device(const mdet_params* p, void* dA, int64_t ld, mdet_result* 
   auto t0 = std::chrono::steady_clock::now();
   if (p->dtype == MDET_F64) rc = logdet_device_t<double>(*p, pl, (double*)dA, ld, res, (double*)diag);
   else if (p->flags & MDET_FLAG_COMPUTE_F64)
-    rc = logdet_device_t<double>(*p, pl, nullptr, ld, res, (double*)diag, (const float*)dA);
+    rc = logdet_device_t<double>(*p, pl, nullptr, ld, res, (double*)diag, (const void*)dA);
   else rc = logdet_device_t<float>(*p, pl, (float*)dA, ld, res, (float*)diag);
   res->t_total = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
   return rc;

@@ -90,9 +90,11 @@ inline SmallArea small_area(int64_t n, int64_t T, int beta) {
 // Returns an mdet_status.
 inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& pl) {
   if (p.n < 0 || p.block_size < 0) return MDET_EINVAL;
-  if (p.dtype != MDET_F32 && p.dtype != MDET_F64) return MDET_EINVAL;
-  // fp32 storage with fp64 arithmetic: everything on the device is fp64
-  const bool widen = p.dtype == MDET_F32 && (p.flags & MDET_FLAG_COMPUTE_F64) != 0;
+  const bool narrow16 = p.dtype == MDET_F16 || p.dtype == MDET_BF16;
+  if (p.dtype != MDET_F32 && p.dtype != MDET_F64 && !narrow16) return MDET_EINVAL;
+  // fp32 or 16-bit storage with fp64 arithmetic: everything on the device is fp64
+  const bool widen = p.dtype != MDET_F64 && (p.flags & MDET_FLAG_COMPUTE_F64) != 0;
+  if (narrow16 && !widen) return MDET_EINVAL;      // 16-bit types are storage formats only
   if (widen && !device_input) return MDET_EINVAL;
   pl.n = p.n;
   pl.beta = (p.dtype == MDET_F64 || widen) ? 8 : 4;

@@ -114,7 +114,14 @@ def test_plan_rounds_block_size_and_handles_edges(M):
     with pytest.raises(M.MemdetError):
         M.mdet_plan(-1, "f64", 64)
     with pytest.raises(ValueError):
+        M.mdet_plan(10, "int8", 64)
+    # the 16-bit types are storage formats: only with fp64 arithmetic, device input only
+    with pytest.raises(M.MemdetError):
         M.mdet_plan(10, "f16", 64)
+    with pytest.raises(M.MemdetError):
+        M.mdet_plan(10, "bf16", 64, flags=M.FLAG_COMPUTE_F64)
+    assert M.mdet_plan(4096, "f16", 256, flags=M.FLAG_COMPUTE_F64,
+                       for_device_input=True).dev_bytes_needed >= 4096 * 4096 * 8
     # device input: only a small scratch unless a copy is needed
     a = M.mdet_plan(8192, "f64", 1024, 0, overwrite=True, for_device_input=True)
     b = M.mdet_plan(8192, "f64", 1024, 0, overwrite=False, for_device_input=True)

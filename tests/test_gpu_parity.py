@@ -334,3 +334,28 @@ def test_scaled_copy_gives_the_same_bits(M, cfg, n, bs, dtype):
                                  mem_budget=plain.dev_bytes_needed + 4096)
     assert tight.logabsdet == ref.logabsdet and tight.dev_bytes_high_water == plain.dev_bytes_needed
 
+
+@pytest.mark.parametrize("store", ["float16", "bfloat16"])
+@pytest.mark.parametrize("n,bs", [(600, 128), (1030, 256)])
+def test_sixteen_bit_storage_with_fp64_arithmetic(M, store, n, bs):
+    # App. C (data-precision pipeline): whatever format the matrix is stored in, the
+    # log-determinant is computed in 64 bit.  The library widens the stored bits exactly.
+    rng = np.random.default_rng(n)
+    g = rng.standard_normal((n, 2 * n))
+    a = g @ g.T / (2 * n) + np.eye(n)
+    stored = torch.from_numpy(a).to(getattr(torch, store))
+    exact = stored.to(torch.float64).numpy()              # the same bits, widened exactly
+    o = oracle.ldlt_logdet(exact, want_diag=True)
+    diag = torch.empty(n, dtype=torch.float64, device="cuda")
+    keep = stored.clone()
+    dstored = stored.cuda()
+    res = M.mdet_logdet_device(dstored, block_size=bs, flags=M.FLAG_COMPUTE_F64, diag=diag)
+    assert res.status == 0 and res.sign == o.sign and res.negative_pivots == o.negative_pivots
+    assert rel(res.logabsdet, o.logabsdet) <= TOL["f64"]
+    assert np.max(np.abs(diag.cpu().numpy() - o.diag) / np.abs(o.diag)) <= 1e-9
+    assert torch.equal(dstored.cpu().view(torch.int16), keep.view(torch.int16))   # input untouched
+    # the 16-bit types are storage formats only
+    with pytest.raises(M.MemdetError) as e:
+        M.mdet_logdet_device(dstored, block_size=bs)
+    assert e.value.status == M.Status.EINVAL
+
