@@ -1,7 +1,7 @@
 """GPU parity of the principal-minor sequence and the FLODANCE fit (Sec. 3.2, Alg. 2):
 the HIP kernels, through the C ABI, against oracle/flodance_oracle.py on the same bits.
 
-Tolerances (derived from the arithmetic, see DESIGN.md):
+Tolerances (derived from the arithmetic):
 * ell_k: both sides add k logarithms, each within a couple of ulp of the exact one, in
   different orders: |diff| <= 8 eps sum_{i<=k} |log|d_i||.
 * regression: both sides solve the same least-squares problem with backward-stable
