@@ -436,6 +436,16 @@ __global__ __launch_bounds__(UPD_THREADS, 2) void trailing_update_kernel(
     int swl, int lower, int per, int k0, FusedLeaf<T> fl) {
   schur_update_body<T, 4, SCALED>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn, swl, lower != 0, per, k0, fl);
 }
+// The trailing update of a short block column: with 128 x 128 blocks it would have
+// fewer workgroups than the device has compute units and last as long as one
+// workgroup's walk along K; 64 x 64 blocks quarter that walk.
+template <typename T, bool SCALED = false>
+__global__ __launch_bounds__(UPD_THREADS) void trailing_update64_kernel(
+    T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
+    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int K, int nsn,
+    int swl, int lower, int per, int k0, FusedLeaf<T> fl) {
+  schur_update_body<T, 2, SCALED>(C, ldc, A, lda, B, ldb, d, M, N, K, nsn, swl, lower != 0, per, k0, fl);
+}
 template <typename T, bool SCALED = false>
 __global__ __launch_bounds__(UPD_THREADS, 2) void panel_update_kernel(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,

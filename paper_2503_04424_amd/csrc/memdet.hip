@@ -167,8 +167,16 @@ struct Launcher {
     // block column a K = 64 update runs single-shot from LDS and short launches
     // use 64 x 64 blocks so that they reach more compute units
     const bool leaf_k = !trailing && K == 64;
-    const bool small = !trailing && !leaf_k && 8 * update_grid(M, N, lower, 128).per < 1024;
-    const int tile = (leaf_k || small) ? 64 : 128;
+    const int64_t wg128 = 8 * update_grid(M, N, lower, 128).per;
+    const bool small = !trailing && !leaf_k && wg128 < 1024;
+    // A one-launch trailing update whose 128 x 128 blocks would not fill the device's
+    // slots (the next block column of a small matrix, or near the end of a large one)
+    // lasts as long as one workgroup's walk along K, twice that where two workgroups
+    // share a compute unit; 64 x 64 blocks quarter the walk and spread evenly
+    // (n = 8192: the seven next-column updates 1.48 -> 1.20 ms; measured cross-over at
+    // about 0.8 of the slots).
+    const bool small_trailing = trailing && leave_free < 0 && slots > 0 && 5 * wg128 <= 4 * slots;
+    const int tile = (leaf_k || small || small_trailing) ? 64 : 128;
     const UpdGrid ug = update_grid(M, N, lower, tile);
     if (8 * ug.per > INT32_MAX) return MDET_EINVAL;
     FusedLeaf<T> fl{0, nullptr, nullptr, nullptr, 0, nullptr, 0};
@@ -200,7 +208,8 @@ struct Launcher {
     if (scaled) MDET_LAUNCH_UPD_AS(KERNEL, true);                                                 \
     else MDET_LAUNCH_UPD_AS(KERNEL, false);                                                       \
   } while (0)
-      if (trailing) MDET_LAUNCH_UPD(trailing_update_kernel);
+      if (small_trailing) MDET_LAUNCH_UPD(trailing_update64_kernel);
+      else if (trailing) MDET_LAUNCH_UPD(trailing_update_kernel);
       else if (leaf_k) {
         if (scaled)
           hipLaunchKernelGGL((leaf_update_kernel<T, true>), grid, block, 0, st, C, ldc, A, lda, B, ldb,
