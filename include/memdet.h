@@ -99,8 +99,11 @@ typedef struct mdet_params {
                                      counted against the budget; the input is never
                                      modified) and diag receives n DOUBLES.  The host
                                      and provider entry points return MDET_EINVAL.     */
-#define MDET_FLAG_PROFILE 4u      /* bracket every trailing-update launch with HIP
-                                     events on its own stream and report the sums in
+#define MDET_FLAG_PROFILE 4u      /* bracket every launch of the trailing-update kernel
+                                     (the 128 x 128-block one that does the bulk of the
+                                     work; small updates run a 64 x 64-block variant
+                                     that is not counted) with HIP events on its own
+                                     stream and report the sums in
                                      result->t_trailing_update etc.                 */
 #define MDET_FLAG_SCALED_COPY 32u /* speed for memory: 2 n block_size further elements of
                                      device workspace hold, for the block column being

@@ -190,7 +190,7 @@ struct Launcher {
     if (trailing && leave_free >= 0 && slots - leave_free >= 8 && 8 * ug.per > slots - leave_free)
       per_launch = (slots - leave_free) / 8;
     dim3 block(UPD_THREADS);
-    const bool timed = profile && trailing;
+    const bool timed = profile && trailing && !small_trailing;   // trailing_update_kernel proper
     for (int64_t k0 = 0; k0 < ug.per; k0 += per_launch) {
       const int64_t kn = ug.per - k0 < per_launch ? ug.per - k0 : per_launch;
       dim3 grid((unsigned)(8 * kn));
