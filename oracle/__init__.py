@@ -35,6 +35,12 @@ def _load():
             fn.restype = ctypes.c_int
             fn.argtypes = [ctypes.c_void_p, i64, i64, pd, ctypes.POINTER(i64),
                            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        for name in ("oracle_ldlt_pivoted_f64", "oracle_ldlt_pivoted_f32"):
+            fn = getattr(lib, name)
+            fn.restype = ctypes.c_int
+            fn.argtypes = [ctypes.c_void_p, i64, i64, i64, ctypes.c_int, pd, ctypes.POINTER(ctypes.c_int),
+                           ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.c_void_p, ctypes.c_void_p,
+                           ctypes.c_void_p, ctypes.c_void_p]
         lib.oracle_leibniz_f64.restype = ctypes.c_int
         lib.oracle_leibniz_f64.argtypes = [ctypes.c_void_p, ctypes.c_int, pd,
                                            ctypes.POINTER(ctypes.c_int), pd]
@@ -123,6 +129,51 @@ def cholesky_logdet(a: np.ndarray, want_diag: bool = False, want_L: bool = False
         raise MemoryError("oracle allocation failed")
     return CholeskyResult(ld.value, st, bad.value, d if st == 0 else None, cum if st == 0 else None,
                           L if st == 0 else None)
+
+
+@dataclass
+class PivotedResult:
+    logabsdet: float
+    sign: int
+    status: int               # 0 ok, 1 exact zero pivot
+    bad_pivot_index: int      # step at which every candidate pivot was zero, else -1
+    negative_pivots: int
+    perm: np.ndarray          # a[perm][:, perm] = L diag(d) L^T
+    slack: np.ndarray         # |pivot taken| / |largest candidate| at each step
+    diag: np.ndarray          # pivots d_j in the order they were taken
+    L: Optional[np.ndarray] = None
+
+
+def ldlt_pivoted(a: np.ndarray, group: int = 64, choose: bool = True, want_L: bool = False) -> PivotedResult:
+    """LDL^T of the symmetric matrix whose LOWER triangle is in ``a`` with diagonal
+    pivoting inside groups of ``group`` consecutive indices (Sec. 2.2: pivoting inside a
+    block, none between blocks), long double on the exact input bits.  ``choose=False``
+    swaps nothing and only reports, in ``slack``, how each pivot compares with the one the
+    rule would have taken (to check a permutation found elsewhere, permute first)."""
+    lib = _load()
+    if a.ndim != 2 or a.shape[0] != a.shape[1]:
+        raise ValueError("square matrix expected")
+    if a.dtype not in (np.float64, np.float32):
+        raise ValueError("float64 or float32 expected")
+    a = np.ascontiguousarray(a)
+    n = a.shape[0]
+    lda = a.strides[0] // a.itemsize if n > 0 else 1
+    fn = lib.oracle_ldlt_pivoted_f64 if a.dtype == np.float64 else lib.oracle_ldlt_pivoted_f32
+    lad = ctypes.c_double(0.0)
+    sg = ctypes.c_int(0)
+    bad = ctypes.c_int64(-1)
+    neg = ctypes.c_int64(0)
+    perm = np.empty(n, dtype=np.int64)
+    slack = np.empty(n, dtype=np.float64)
+    d = np.empty(n, dtype=np.float64)
+    L = np.empty((n, n), dtype=np.float64) if want_L else None
+    st = fn(a.ctypes.data, n, max(lda, 1), int(group), 1 if choose else 0, ctypes.byref(lad),
+            ctypes.byref(sg), ctypes.byref(bad), ctypes.byref(neg), perm.ctypes.data,
+            slack.ctypes.data, d.ctypes.data, L.ctypes.data if L is not None else None)
+    if st == 2:
+        raise MemoryError("oracle allocation failed or bad group size")
+    return PivotedResult(lad.value, sg.value, st, bad.value, neg.value, perm, slack, d,
+                         L if st == 0 else None)
 
 
 def leibniz_logdet(a: np.ndarray):

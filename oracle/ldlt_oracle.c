@@ -37,6 +37,15 @@
  *
  *      l_jj = sqrt(a_jj - sum_{k<j} l_jk^2)
  *      l_ij = (a_ij - sum_{k<j} l_ik l_jk) / l_jj           (i > j)
+ *
+ * And the symmetric case with a permutation, P A P^T = L D L^T (Sec. 2.2: the
+ * symmetric form handles permutations and the diagonal scaling; pivoting is
+ * confined to a block, there is none between blocks; the software section lists
+ * `perm` among the outputs): elimination on the whole symmetric matrix, where at
+ * step j the pivot is the entry of largest magnitude on the diagonal of the
+ * current Schur complement among the indices of j's group of `group` consecutive
+ * indices (the first such entry on ties), brought to position j by swapping rows
+ * and columns.  See ldlt_pivoted_core.
  */
 #include <math.h>
 #include <stdint.h>
@@ -155,6 +164,112 @@ int oracle_ldlt_f32(const float *a, int64_t n, int64_t lda, double *logabsdet,
                     double *cum_out, double *l_out) {
   return ldlt_core(a, (size_t)n, (size_t)lda, get_f32, logabsdet, sign, bad,
                    negative, d_out, cum_out, l_out);
+}
+
+/*
+ * LDL^T with diagonal pivoting inside groups of `group` consecutive indices.
+ *
+ * Works on a full long-double copy S of the symmetric matrix (built from the lower
+ * triangle of the input).  Step j, with hi = end of j's group:
+ *     p      = argmax_{j <= k < hi} |S_kk|   (smallest k on ties)   if choose != 0,
+ *              j                                                     otherwise;
+ *     slack_j = |S_pp| / max_{j <= k < hi} |S_kk|   (1 when the maximum was chosen);
+ *     swap rows and columns j <-> p of S (rows of the finished part of L with them),
+ *     d_j = S_jj,  l_ij = S_ij / d_j,  S_ik -= l_ij d_j l_kj   for i, k > j.
+ * perm_out[j] = original index of the row/column that ended at position j, so that
+ * A[perm][:, perm] = L D L^T.  With choose == 0 nothing is swapped: the plain
+ * factorisation in right-looking order, slack_j then tells how far each pivot was
+ * from the one the rule would have chosen (the caller permutes the input first to
+ * check somebody else's permutation).
+ * Outputs (any may be NULL): perm_out[n], slack_out[n], d_out[n], l_out[n*n] (unit
+ * lower L, row-major).  Returns 0, 1 on an exact zero pivot (then *bad = j, sign 0,
+ * logabsdet -inf), 2 on allocation failure or group < 1.
+ */
+static int ldlt_pivoted_core(const void *a, size_t n, size_t lda, getter get, size_t group,
+                             int choose, double *logabsdet, int *sign, int64_t *bad,
+                             int64_t *negative, int64_t *perm_out, double *slack_out,
+                             double *d_out, double *l_out) {
+  *logabsdet = 0.0;
+  *sign = 1;
+  if (bad) *bad = -1;
+  if (negative) *negative = 0;
+  if (group < 1) return 2;
+  if (n == 0) return 0;
+  xreal *S = (xreal *)malloc(n * n * sizeof(xreal));
+  size_t *perm = (size_t *)malloc(n * sizeof(size_t));
+  if (!S || !perm) { free(S); free(perm); return 2; }
+  for (size_t i = 0; i < n; ++i) {
+    perm[i] = i;
+    for (size_t k = 0; k <= i; ++k) S[i * n + k] = S[k * n + i] = get(a, i, k, lda);
+  }
+  int status = 0, sg = 1;
+  int64_t neg = 0;
+  xreal acc_log = 0.0L;
+  for (size_t j = 0; j < n; ++j) {
+    size_t hi = (j / group + 1) * group;
+    if (hi > n) hi = n;
+    size_t best = j;
+    for (size_t k = j + 1; k < hi; ++k)
+      if (fabsl(S[k * n + k]) > fabsl(S[best * n + best])) best = k;
+    const size_t p = choose ? best : j;
+    const xreal top = fabsl(S[best * n + best]);
+    if (slack_out) slack_out[j] = top == 0.0L ? 1.0 : (double)(fabsl(S[p * n + p]) / top);
+    if (p != j) {
+      for (size_t k = 0; k < n; ++k) { xreal t = S[j * n + k]; S[j * n + k] = S[p * n + k]; S[p * n + k] = t; }
+      for (size_t k = 0; k < n; ++k) { xreal t = S[k * n + j]; S[k * n + j] = S[k * n + p]; S[k * n + p] = t; }
+      size_t t = perm[j]; perm[j] = perm[p]; perm[p] = t;
+    }
+    const xreal d = S[j * n + j];
+    if (d == 0.0L) {
+      status = 1;
+      if (bad) *bad = (int64_t)j;
+      break;
+    }
+    if (d < 0.0L) { sg = -sg; ++neg; }
+    acc_log += logl(fabsl(d));
+    /* row j right of the diagonal keeps the un-normalised column, w_k = l_kj d_j; every
+       updated entry is written to both triangles, so S stays exactly symmetric */
+    long i;
+#pragma omp parallel for schedule(static)
+    for (i = (long)j + 1; i < (long)n; ++i) {
+      const size_t r = (size_t)i;
+      const xreal l = S[r * n + j] / d;
+      for (size_t k = j + 1; k <= r; ++k) {
+        const xreal v = S[r * n + k] - l * S[j * n + k];
+        S[r * n + k] = v;
+        S[k * n + r] = v;
+      }
+      S[r * n + j] = l;
+    }
+  }
+  if (status == 0) { *logabsdet = (double)acc_log; *sign = sg; }
+  else { *logabsdet = -INFINITY; *sign = 0; }
+  if (negative) *negative = neg;
+  if (perm_out) for (size_t j = 0; j < n; ++j) perm_out[j] = (int64_t)perm[j];
+  if (d_out) for (size_t j = 0; j < n; ++j) d_out[j] = (double)S[j * n + j];
+  if (l_out && status == 0) {
+    memset(l_out, 0, n * n * sizeof(double));
+    for (size_t i = 0; i < n; ++i) {
+      for (size_t k = 0; k < i; ++k) l_out[i * n + k] = (double)S[i * n + k];
+      l_out[i * n + i] = 1.0;
+    }
+  }
+  free(S); free(perm);
+  return status;
+}
+
+int oracle_ldlt_pivoted_f64(const double *a, int64_t n, int64_t lda, int64_t group, int choose,
+                            double *logabsdet, int *sign, int64_t *bad, int64_t *negative,
+                            int64_t *perm_out, double *slack_out, double *d_out, double *l_out) {
+  return ldlt_pivoted_core(a, (size_t)n, (size_t)lda, get_f64, group < 1 ? 0 : (size_t)group, choose,
+                           logabsdet, sign, bad, negative, perm_out, slack_out, d_out, l_out);
+}
+
+int oracle_ldlt_pivoted_f32(const float *a, int64_t n, int64_t lda, int64_t group, int choose,
+                            double *logabsdet, int *sign, int64_t *bad, int64_t *negative,
+                            int64_t *perm_out, double *slack_out, double *d_out, double *l_out) {
+  return ldlt_pivoted_core(a, (size_t)n, (size_t)lda, get_f32, group < 1 ? 0 : (size_t)group, choose,
+                           logabsdet, sign, bad, negative, perm_out, slack_out, d_out, l_out);
 }
 
 /*
