@@ -44,8 +44,8 @@
  * `perm` among the outputs): elimination on the whole symmetric matrix, where at
  * step j the pivot is the entry of largest magnitude on the diagonal of the
  * current Schur complement among the indices of j's group of `group` consecutive
- * indices (the first such entry on ties), brought to position j by swapping rows
- * and columns.  See ldlt_pivoted_core.
+ * indices (on ties the one that came first in the input), brought to position j by
+ * swapping rows and columns.  See ldlt_pivoted_core.
  */
 #include <math.h>
 #include <stdint.h>
@@ -171,7 +171,8 @@ int oracle_ldlt_f32(const float *a, int64_t n, int64_t lda, double *logabsdet,
  *
  * Works on a full long-double copy S of the symmetric matrix (built from the lower
  * triangle of the input).  Step j, with hi = end of j's group:
- *     p      = argmax_{j <= k < hi} |S_kk|   (smallest k on ties)   if choose != 0,
+ *     p      = argmax_{j <= k < hi} |S_kk|   (on ties the candidate with the smallest
+ *              index in the input)                                   if choose != 0,
  *              j                                                     otherwise;
  *     slack_j = |S_pp| / max_{j <= k < hi} |S_kk|   (1 when the maximum was chosen);
  *     swap rows and columns j <-> p of S (rows of the finished part of L with them),
@@ -208,9 +209,13 @@ static int ldlt_pivoted_core(const void *a, size_t n, size_t lda, getter get, si
   for (size_t j = 0; j < n; ++j) {
     size_t hi = (j / group + 1) * group;
     if (hi > n) hi = n;
+    /* among equal magnitudes the candidate that came first in the input: a rule that
+       does not depend on where the swaps of earlier steps have put the candidates */
     size_t best = j;
-    for (size_t k = j + 1; k < hi; ++k)
-      if (fabsl(S[k * n + k]) > fabsl(S[best * n + best])) best = k;
+    for (size_t k = j + 1; k < hi; ++k) {
+      const xreal vk = fabsl(S[k * n + k]), vb = fabsl(S[best * n + best]);
+      if (vk > vb || (vk == vb && perm[k] < perm[best])) best = k;
+    }
     const size_t p = choose ? best : j;
     const xreal top = fabsl(S[best * n + best]);
     if (slack_out) slack_out[j] = top == 0.0L ? 1.0 : (double)(fabsl(S[p * n + p]) / top);

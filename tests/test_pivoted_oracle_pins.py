@@ -88,6 +88,15 @@ def test_the_rule_is_the_largest_remaining_diagonal_entry():
     assert r.perm.tolist() == order
 
 
+def test_ties_go_to_the_candidate_that_came_first_in_the_input():
+    # repeated magnitudes on a diagonal matrix: a stable sort by magnitude, whatever the
+    # swaps of earlier steps did to the positions
+    dv = np.array([1.0, -2.0, 2.0, 0.5, -2.0, 1.0, 3.0, 3.0] * 3)
+    r = oracle.ldlt_pivoted(np.diag(dv), group=24)
+    assert r.perm.tolist() == np.argsort(-np.abs(dv), kind="stable").tolist()
+    assert np.array_equal(r.diag, dv[r.perm])
+
+
 def test_diagonal_matrix_is_sorted_by_magnitude_inside_each_group():
     rng = np.random.default_rng(8)
     n, group = 40, 16
