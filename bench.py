@@ -140,6 +140,25 @@ def kernel_report(reps=5):
                     "note": "both launches timed together; the solve's own duration and GB/s are in the "
                             "rocprofv3 summary of this command", "bound": "hbm", "peak": HBM, "unit": "GB/s",
                     "achieved": gb / (ms * 1e-3), "frac": gb / (ms * 1e-3) / HBM})
+    # the same leaf with pivoting: its own 64 x 64 factorisation kernel, then the solve
+    for m in (32768,):
+        w = 64
+        g = torch.Generator(device="cuda").manual_seed(12)
+        src = torch.randn(m, w, dtype=torch.float64, device="cuda", generator=g) * 0.01
+        src[:w] += torch.diag(torch.linspace(1.0, 3.0, w, dtype=torch.float64, device="cuda"))
+        src[:w] = (src[:w] + src[:w].T) / 2
+        panel = torch.empty_like(src)
+        dv = torch.zeros(w, dtype=torch.float64, device="cuda")
+        di = torch.zeros_like(dv)
+        pm = torch.zeros(w, dtype=torch.int32, device="cuda")
+        flags = torch.zeros(16 + 8192, dtype=torch.uint8, device="cuda")
+        flags[:16] = 255
+        ms = timed(lambda: M.mdet_step_panel_factor_pivoted(panel, w, dv, di, pm, flags),
+                   prep=lambda: panel.copy_(src))
+        out.append({"kernel": "leaf_factor_pivoted_kernel + leaf_solve_kernel", "dtype": "f64",
+                    "shape": f"m={m} w={w}", "ms": ms,
+                    "note": "both launches timed together; each kernel's own duration is in the "
+                            "rocprofv3 summary of this command (64 dependent pivot steps, latency-bound)"})
     for n in (196608,):          # one workgroup per block column; here a single column
         dvec = torch.rand(n, dtype=torch.float64, device="cuda") + 0.5
         res = torch.zeros(8, dtype=torch.float64, device="cuda")
@@ -191,6 +210,8 @@ def main():
                     help="in-core: MDET_FLAG_SCALED_COPY (2 n block_size elements more workspace)")
     ap.add_argument("--assume-spd", action="store_true",
                     help="the positive-definite (Cholesky) form of the method instead of LDL^T")
+    ap.add_argument("--pivot", action="store_true",
+                    help="MDET_FLAG_PIVOT: pivoting on the diagonal inside each group of 64 columns")
     ap.add_argument("--kernels", action="store_true",
                     help="instead of the path: stand-alone rates of its kernels (one JSON line)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -233,6 +254,8 @@ def main():
         xflags |= M.FLAG_ASSUME_SPD
     if args.scaled_copy:
         xflags |= M.FLAG_SCALED_COPY
+    if args.pivot:
+        xflags |= M.FLAG_PIVOT
     results = []
     if not out_of_core:
         a = form_matrix_device(w, torch)
@@ -329,7 +352,8 @@ def main():
                    "mem_budget_bytes": w.mem_budget, "seed": w.seed,
                    **({"storage": "f32, widened exactly; arithmetic f64"} if widen else {}),
                    **({"form": "positive definite (Cholesky), MDET_FLAG_ASSUME_SPD"} if args.assume_spd else {}),
-                   **({"workspace": "MDET_FLAG_SCALED_COPY"} if args.scaled_copy else {})},
+                   **({"workspace": "MDET_FLAG_SCALED_COPY"} if args.scaled_copy else {}),
+                   **({"pivoting": "inside groups of 64, MDET_FLAG_PIVOT"} if args.pivot else {})},
         "time_to_logdet_s": sec, "frac_of_matrix_peak": value / peak,
         "logabsdet": final.logabsdet, "sign": final.sign, "negative_pivots": final.negative_pivots,
         "kernel_launches_per_step": final.kernel_launches,

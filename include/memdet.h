@@ -82,6 +82,10 @@ typedef struct mdet_params {
                                 host_bytes that receives the updated blocks; NULL =
                                 the library allocates pinned memory itself.        */
   uint64_t host_scratch_bytes;
+  void* perm;                /* MDET_FLAG_PIVOT: n int32 that receive the permutation
+                                (a DEVICE pointer for mdet_logdet_device, a HOST pointer
+                                for the host and provider entry points); NULL = not
+                                wanted.  Ignored without the flag.                  */
 } mdet_params;
 
 #define MDET_FLAG_NO_LOOKAHEAD 1u /* run every step on one stream, strictly in order
@@ -121,6 +125,27 @@ typedef struct mdet_params {
                                      scaling).  A negative pivot ends the call with
                                      MDET_ENOTPOSDEF and its index in bad_pivot_index;
                                      `diag` still receives the pivots d_j = L_jj^2.    */
+
+#define MDET_FLAG_PIVOT 64u       /* symmetric pivoting inside each group of 64 consecutive
+                                     rows/columns (Sec. 2.2: the symmetric form handles
+                                     permutations; pivoting stays inside a block, there is
+                                     none between blocks): at every step the pivot is the
+                                     entry of largest magnitude left on the diagonal of the
+                                     current Schur complement within the group (the first
+                                     on ties), P A P^T = L D L^T.  perm[j] = index of the
+                                     input row/column that stands at position j, so
+                                     A[perm][:, perm] = L D L^T; `diag` receives the
+                                     pivots in that order.  log|det| and sign are those of
+                                     A.  An exact zero left as the largest candidate ends
+                                     the call with MDET_ESINGULAR (a matrix like
+                                     [[0, 1], [1, 0]] would need a 2 x 2 pivot, which is
+                                     not provided).  The stored factor S (overwrite = 1)
+                                     holds L with the rows of every group left in input
+                                     order for the columns before the group: A = M D M^T
+                                     with M = S except that row perm[j] of each diagonal
+                                     64 x 64 block of M is row j of that block of S.
+                                     Costs one more launch per 64 columns; n < 2^31; not
+                                     with MDET_FLAG_ASSUME_SPD (MDET_EINVAL).            */
 
 typedef struct mdet_result {
   double logabsdet;            /* log|det A|; -inf when sign == 0                    */
@@ -266,6 +291,14 @@ int mdet_step_schur_update(int32_t dtype, void* C, int64_t ldc, const void* A,
 int mdet_step_panel_factor(int32_t dtype, void* P, int64_t ld, int64_t m, int64_t w,
                            void* d, void* dinv, int64_t pivot_index0, void* flags,
                            void* stream);
+
+/* The same with pivoting inside each 64-column leaf (MDET_FLAG_PIVOT): perm receives
+ * w int32, perm[j] = pivot_index0 + (row of P, counted from its first, that stands at
+ * position j); on return the top w x w block holds L and D of the permuted block and the
+ * rows below hold their columns in that order. */
+int mdet_step_panel_factor_pivoted(int32_t dtype, void* P, int64_t ld, int64_t m, int64_t w,
+                                   void* d, void* dinv, int32_t* perm, int64_t pivot_index0,
+                                   void* flags, void* stream);
 
 /* sum log|d_j|, sign and negative count of d[0..n) -> out[0] = logabsdet (double),
  * out[1] = sign (as double), out[2] = negative count (as double).  out: DEVICE

@@ -21,6 +21,7 @@ FLAG_PROFILE = 4
 FLAG_COMPUTE_F64 = 8
 FLAG_ASSUME_SPD = 16
 FLAG_SCALED_COPY = 32
+FLAG_PIVOT = 64
 
 
 class Status:
@@ -34,7 +35,7 @@ class _Params(C.Structure):
         ("overwrite", C.c_int32), ("reserved0", C.c_int32), ("flags", C.c_uint32),
         ("stream", C.c_void_p), ("dev_workspace", C.c_void_p),
         ("dev_workspace_bytes", C.c_uint64), ("host_scratch", C.c_void_p),
-        ("host_scratch_bytes", C.c_uint64),
+        ("host_scratch_bytes", C.c_uint64), ("perm", C.c_void_p),
     ]
 
 
@@ -70,6 +71,7 @@ EXPORTS = [
     "mdet_plan", "mdet_workspace_query", "mdet_logdet_device", "mdet_logdet_host",
     "mdet_logdet_provider", "mdet_host_layout_offset", "mdet_paper_block_rule",
     "mdet_paper_fma_count", "mdet_step_schur_update", "mdet_step_panel_factor",
+    "mdet_step_panel_factor_pivoted",
     "mdet_step_logdet_reduce", "mdet_strerror", "mdet_version",
     "mdet_sequence_workspace_query", "mdet_principal_logdets", "mdet_flodance_fit",
     "mdet_flodance_eval",
@@ -104,6 +106,7 @@ def load():
     L.mdet_paper_fma_count.restype = C.c_double
     L.mdet_step_schur_update.argtypes = [i32, vp, i64, vp, i64, vp, i64, vp, i64, i64, i64, i32, vp]
     L.mdet_step_panel_factor.argtypes = [i32, vp, i64, i64, i64, vp, vp, i64, vp, vp]
+    L.mdet_step_panel_factor_pivoted.argtypes = [i32, vp, i64, i64, i64, vp, vp, vp, i64, vp, vp]
     L.mdet_step_logdet_reduce.argtypes = [i32, vp, i64, vp, vp]
     L.mdet_sequence_workspace_query.argtypes = [i64, i64, i32, C.POINTER(u64)]
     L.mdet_principal_logdets.argtypes = [i32, vp, i64, vp, vp, u64, vp]
@@ -194,7 +197,8 @@ def _dtype_code(dtype) -> int:
 
 
 def _params(n, dtype, block_size=0, mem_budget=0, overwrite=True, flags=0, stream=None,
-            dev_workspace=None, dev_workspace_bytes=0, host_scratch=None, host_scratch_bytes=0):
+            dev_workspace=None, dev_workspace_bytes=0, host_scratch=None, host_scratch_bytes=0,
+            perm=None):
     p = _Params()
     p.struct_size = C.sizeof(_Params)
     p.dtype = _dtype_code(dtype)
@@ -208,6 +212,7 @@ def _params(n, dtype, block_size=0, mem_budget=0, overwrite=True, flags=0, strea
     p.dev_workspace_bytes = int(dev_workspace_bytes)
     p.host_scratch = host_scratch
     p.host_scratch_bytes = int(host_scratch_bytes)
+    p.perm = perm
     return p
 
 
@@ -263,17 +268,29 @@ def _stream_handle(stream):
     return C.c_void_p(int(stream))
 
 
+def _perm_ptr(perm, n, on_device):
+    import torch
+    if perm is None:
+        return None
+    if perm.dtype != torch.int32 or perm.numel() < n or perm.is_cuda != on_device or not perm.is_contiguous():
+        raise ValueError("perm must be a contiguous int32 tensor of n elements, on the %s"
+                         % ("GPU" if on_device else "host"))
+    return perm.data_ptr()
+
+
 def mdet_logdet_device(a, block_size=0, mem_budget=0, overwrite=False, flags=0, diag=None,
-                       stream=None, workspace=None, raise_on_error=True) -> LogdetResult:
+                       stream=None, workspace=None, raise_on_error=True, perm=None) -> LogdetResult:
     """log|det| and sign of the symmetric matrix whose lower triangle is in the
-    2-D CUDA tensor ``a`` (float64 / float32, row-major, unit column stride)."""
+    2-D CUDA tensor ``a`` (float64 / float32, row-major, unit column stride).
+    ``perm`` (int32 CUDA tensor, with FLAG_PIVOT) receives the permutation."""
     if a.dim() != 2 or a.shape[0] != a.shape[1] or not a.is_cuda or (a.numel() and a.stride(1) != 1):
         raise ValueError("square row-major CUDA tensor expected")
     n = a.shape[0]
     ld = a.stride(0) if n > 1 else max(n, 1)
     p = _params(n, a.dtype, block_size, mem_budget, overwrite, flags, _stream_handle(stream),
                 workspace.data_ptr() if workspace is not None else None,
-                workspace.numel() * workspace.element_size() if workspace is not None else 0)
+                workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                perm=_perm_ptr(perm, n, True))
     import torch
     diag_dtype = torch.float64 if (flags & FLAG_COMPUTE_F64) else a.dtype
     if diag is not None and (diag.dtype != diag_dtype or diag.numel() < n or not diag.is_cuda):
@@ -287,7 +304,8 @@ def mdet_logdet_device(a, block_size=0, mem_budget=0, overwrite=False, flags=0, 
 
 
 def mdet_logdet_host(packed, n, block_size, mem_budget=0, overwrite=True, flags=0, diag=None,
-                     stream=None, workspace=None, host_scratch=None, raise_on_error=True) -> LogdetResult:
+                     stream=None, workspace=None, host_scratch=None, raise_on_error=True,
+                     perm=None) -> LogdetResult:
     """``packed``: 1-D CPU tensor (ideally pinned) in the packed lower block-column layout."""
     if packed.is_cuda or packed.dim() != 1:
         raise ValueError("1-D host tensor expected")
@@ -295,7 +313,8 @@ def mdet_logdet_host(packed, n, block_size, mem_budget=0, overwrite=True, flags=
                 workspace.data_ptr() if workspace is not None else None,
                 workspace.numel() * workspace.element_size() if workspace is not None else 0,
                 host_scratch.data_ptr() if host_scratch is not None else None,
-                host_scratch.numel() * host_scratch.element_size() if host_scratch is not None else 0)
+                host_scratch.numel() * host_scratch.element_size() if host_scratch is not None else 0,
+                perm=_perm_ptr(perm, n, False))
     b = (int(block_size) + 63) // 64 * 64
     need = mdet_host_layout_offset(n, b, (n + b - 1) // b) if n > 0 else 0
     if packed.numel() < need:
@@ -311,7 +330,7 @@ def mdet_logdet_host(packed, n, block_size, mem_budget=0, overwrite=True, flags=
 
 
 def mdet_logdet_provider(provider: Callable, n, dtype, block_size, mem_budget=0, flags=0,
-                         diag=None, stream=None, raise_on_error=True) -> LogdetResult:
+                         diag=None, stream=None, raise_on_error=True, perm=None) -> LogdetResult:
     """``provider(bi, bj, rows, cols, dst_ptr, ld) -> int`` fills one block (host memory)."""
     def _cb(user, bi, bj, rows, cols, dst, ld):
         try:
@@ -319,7 +338,8 @@ def mdet_logdet_provider(provider: Callable, n, dtype, block_size, mem_budget=0,
         except Exception:  # never let an exception cross the C boundary
             return -1
     cb = PROVIDER_CB(_cb)
-    p = _params(n, dtype, block_size, mem_budget, True, flags, _stream_handle(stream))
+    p = _params(n, dtype, block_size, mem_budget, True, flags, _stream_handle(stream),
+                perm=_perm_ptr(perm, n, False))
     r = _Result()
     st = load().mdet_logdet_provider(C.byref(p), cb, None, C.byref(r),
                                      C.c_void_p(diag.data_ptr()) if diag is not None else None)
@@ -362,6 +382,17 @@ def mdet_step_panel_factor(panel, w, d, dinv, flags_buf, pivot_index0=0, stream=
     st = load().mdet_step_panel_factor(_dtype_code(panel.dtype), panel.data_ptr(), panel.stride(0), m,
                                        int(w), d.data_ptr(), dinv.data_ptr(), int(pivot_index0),
                                        flags_buf.data_ptr(), _stream_handle(stream))
+    if st != Status.OK:
+        raise MemdetError(st)
+
+
+def mdet_step_panel_factor_pivoted(panel, w, d, dinv, perm, flags_buf, pivot_index0=0, stream=None) -> None:
+    """As mdet_step_panel_factor with pivoting inside each 64-column leaf; perm: int32, w entries."""
+    m = panel.shape[0]
+    st = load().mdet_step_panel_factor_pivoted(_dtype_code(panel.dtype), panel.data_ptr(), panel.stride(0),
+                                               m, int(w), d.data_ptr(), dinv.data_ptr(),
+                                               _perm_ptr(perm, int(w), True), int(pivot_index0),
+                                               flags_buf.data_ptr(), _stream_handle(stream))
     if st != Status.OK:
         raise MemdetError(st)
 

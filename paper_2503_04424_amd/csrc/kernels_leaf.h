@@ -3,6 +3,9 @@
 // leaf_factor_kernel : in-place A = L D L^T of one <= 64 x 64 diagonal leaf
 //                      (Sec. 2.2: "in-place ... decomposition" of the diagonal block,
 //                      symmetric case: unit-lower L, diagonal D, no pivoting).
+// leaf_factor_pivoted_kernel : the same with the pivot taken from the diagonal inside the
+//                      leaf, P A P^T = L D L^T (Sec. 2.2: the symmetric form handles
+//                      permutations; pivoting inside a block, none between blocks).
 // leaf_solve_kernel  : rows below the leaf, X = A_rows L^-T D^-1
 //                      (Sec. 2.2: in-place triangular solve of the off-diagonal
 //                      blocks; App. E.1 "solve lower triangular system"; the
@@ -369,6 +372,214 @@ __global__ __launch_bounds__(FACTOR_THREADS) void leaf_factor_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// leaf factor with pivoting
+// ---------------------------------------------------------------------------
+// Maximum of x over the 64 lanes, delivered in a scalar register: four exchanges inside
+// each row of 16 lanes on the data-parallel-primitive path, then the last lane of a row
+// handed to the next row, and the last lane of the first two rows to the last two; lane
+// 63 then holds the maximum.  Must be reached by all 64 lanes.
+__device__ __forceinline__ unsigned wave_max_u32(unsigned x) {
+  int m = (int)x;
+  auto take = [&](int other) { m = (int)max((unsigned)m, (unsigned)other); };
+  take(__builtin_amdgcn_update_dpp(0, m, 0xB1, 0xF, 0xF, false));    // lanes 1 0 3 2 of each four
+  take(__builtin_amdgcn_update_dpp(0, m, 0x4E, 0xF, 0xF, false));    // lanes 2 3 0 1
+  take(__builtin_amdgcn_update_dpp(0, m, 0x141, 0xF, 0xF, false));   // mirror inside each eight
+  take(__builtin_amdgcn_update_dpp(0, m, 0x140, 0xF, 0xF, false));   // mirror inside each sixteen
+  take(__builtin_amdgcn_update_dpp(m, m, 0x142, 0xA, 0xF, false));   // lane 15 -> rows 1 and 3
+  take(__builtin_amdgcn_update_dpp(m, m, 0x143, 0xC, 0xF, false));   // lane 31 -> rows 2 and 3
+  return (unsigned)__builtin_amdgcn_readlane(m, 63);
+}
+
+// The pivot rule: among the lanes with `candidate` set, the one whose `diag` is largest in
+// magnitude (the lowest lane on ties; a NaN counts as the largest, so that it is taken
+// and reported).  Magnitudes of IEEE numbers order like their bit patterns.  Returns 0 if
+// there is no candidate.  Must be reached by all 64 lanes.
+__device__ __forceinline__ int pick_pivot(double diag, bool candidate) {
+  unsigned long long key = (unsigned long long)__double_as_longlong(fabs(diag));
+  if (!(diag == diag)) key = 0x7ff0000000000000ull;
+  if (!candidate) key = 0ull;
+  const unsigned hi = (unsigned)(key >> 32), lo = (unsigned)key;
+  const unsigned top_hi = wave_max_u32(hi);
+  unsigned long long hit = __ballot(candidate && hi == top_hi);
+  // the upper words (exponent, 20 bits of the fraction) nearly always decide
+  if (hit & (hit - 1ull)) {
+    const unsigned top_lo = wave_max_u32(hi == top_hi ? lo : 0u);
+    hit = __ballot(candidate && hi == top_hi && lo == top_lo);
+  }
+  return hit ? __ffsll((long long)hit) - 1 : 0;
+}
+__device__ __forceinline__ int pick_pivot(float diag, bool candidate) {
+  unsigned key = (unsigned)__float_as_int(fabsf(diag));
+  if (!(diag == diag)) key = 0x7f800000u;
+  if (!candidate) key = 0u;
+  const unsigned top = wave_max_u32(key);
+  const unsigned long long hit = __ballot(candidate && key == top);
+  return hit ? __ffsll((long long)hit) - 1 : 0;
+}
+
+// a[idx] for an index that is the same in all lanes, without a memory round trip: four
+// levels of two-way selects on the bits of idx.  Written as C++ conditionals the
+// compiler recognises an indexed array, moves the array to scratch memory and stores
+// all of it every time it changes; the select instruction itself keeps the 16 values
+// in the registers they live in.
+__device__ __forceinline__ int select_word(int x0, int x1, unsigned long long take1) {
+  int r;
+  asm("v_cndmask_b32_e64 %0, %1, %2, %3" : "=v"(r) : "v"(x0), "v"(x1), "s"(take1));
+  return r;
+}
+__device__ __forceinline__ double select_value(double x0, double x1, unsigned long long take1) {
+  return __hiloint2double(select_word(__double2hiint(x0), __double2hiint(x1), take1),
+                          select_word(__double2loint(x0), __double2loint(x1), take1));
+}
+__device__ __forceinline__ float select_value(float x0, float x1, unsigned long long take1) {
+  return __int_as_float(select_word(__float_as_int(x0), __float_as_int(x1), take1));
+}
+template <typename T>
+__device__ __forceinline__ T select16(const T (&a)[SUB], int idx) {
+  const unsigned long long b0 = (idx & 1) ? ~0ull : 0ull, b1 = (idx & 2) ? ~0ull : 0ull;
+  const unsigned long long b2 = (idx & 4) ? ~0ull : 0ull, b3 = (idx & 8) ? ~0ull : 0ull;
+  T t8[8], t4[4], t2[2];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) t8[k] = select_value(a[2 * k], a[2 * k + 1], b0);
+#pragma unroll
+  for (int k = 0; k < 4; ++k) t4[k] = select_value(t8[2 * k], t8[2 * k + 1], b1);
+#pragma unroll
+  for (int k = 0; k < 2; ++k) t2[k] = select_value(t4[2 * k], t4[2 * k + 1], b2);
+  return select_value(t2[0], t2[1], b3);
+}
+
+// One leaf, P A P^T = L D L^T with P chosen inside the leaf: at every step the largest
+// remaining diagonal entry of the Schur complement is the pivot.  Nothing is swapped
+// while the elimination runs.  The leaf is held as a full symmetric matrix, column c in
+// lane c of each of the four wavefronts, wavefront q holding rows 16 q .. 16 q + 15 in
+// registers.  Step j, pivot p: row p is one register of wavefront p / 16, a value per
+// lane, and goes to LDS in one store; from there every lane reads w_c, its own column's
+// entry, and the entries w_r of its wavefront's 16 rows (row p is column p, by symmetry);
+// l_r = w_r / d; a_rc -= l_r w_c.  The chain from one step to the next is short: the pivot
+// d itself comes from the owner lane's register before the exchange, so its reciprocal
+// is ready when w_c arrives; then one product and one fused multiply-add give the lane's
+// new diagonal entry, which every wavefront keeps with the same arithmetic as the
+// entry in the matrix, so that each finds the next pivot by itself and no decision is
+// exchanged.  The multipliers are collected by original row; once every row knows the
+// step at which it was taken they move to that row of the result.  Rows and columns of
+// pivots already taken keep being updated with values that nothing reads.
+// Outputs as leaf_factor_kernel (L and D in pivot order into A, pivots, reciprocals,
+// inverses of the diagonal sub-blocks of L), and perm[j] = pivot0 + (row taken at step j).
+template <typename T>
+__global__ __launch_bounds__(FACTOR_THREADS) void leaf_factor_pivoted_kernel(
+    T* __restrict__ A, int64_t ld, int w, T* __restrict__ dvec, T* __restrict__ dinv,
+    T* __restrict__ linv, int* __restrict__ perm, long long pivot0, DevFlags* flags) {
+  __shared__ T tile[FACTOR_LDS_ELEMS];
+  __shared__ T prow[2][LEAF];     // the pivot row, two steps alternating
+  __shared__ T dl[LEAF];          // pivots in the order taken
+  __shared__ int pos[LEAF];       // step at which a row was taken
+  __shared__ int src[LEAF];       // row taken at a step
+  __builtin_amdgcn_s_setprio(3);
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15;
+  constexpr int PER = LEAF * LEAF / FACTOR_THREADS;
+  {
+    T v[PER];
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
+      v[q] = (r < w && c <= r) ? A[(int64_t)r * ld + c] : T(0);
+    }
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
+      tile[r * LEAF_PAD + c] = v[q];
+    }
+  }
+  __syncthreads();
+  T a[SUB];        // a[k] = entry (16 wave + k, lane)
+#pragma unroll
+  for (int k = 0; k < SUB; ++k) {
+    const int r = wave * SUB + k;
+    a[k] = lane <= r ? tile[r * LEAF_PAD + lane] : tile[lane * LEAF_PAD + r];
+  }
+  T diag = tile[lane * LEAF_PAD + lane];
+  __syncthreads();
+  for (int e = tid; e < FACTOR_LDS_ELEMS; e += FACTOR_THREADS) tile[e] = T(0);
+  if (wave == 0) {
+    pos[lane] = lane;      // rows of the padding (w < 64) stay where they are
+    src[lane] = lane;
+    dl[lane] = T(1);
+  }
+  bool taken = lane >= w;
+  int p = pick_pivot(diag, !taken);
+#pragma unroll 1
+  for (int j = 0; j < w; ++j) {
+    T* pr = prow[j & 1];
+    if (wave == (p >> 4)) pr[lane] = select16<T>(a, p & 15);
+    const T d = lane_value(diag, p);
+    const T rd = fast_rcp(d);
+    // also orders the clearing of the tile before the first multiplier written to it
+    __syncthreads();
+    const T wc = pr[lane];
+    T wr[SUB];
+#pragma unroll
+    for (int k = 0; k < SUB; ++k) wr[k] = pr[wave * SUB + k];
+    const bool live = !taken && lane != p;
+    const T lc = live ? wc * rd : T(0);
+    diag = fma(-lc, wc, diag);      // the same operands as this column's diagonal entry in a[]
+    if (wave == 0) {
+      if (live) tile[lane * LEAF_PAD + j] = lc;
+      if (lane == p) {
+        pos[lane] = j;
+        src[j] = lane;
+        dl[j] = d;
+      }
+    }
+    if (lane == p) taken = true;
+    p = pick_pivot(diag, !taken);
+#pragma unroll
+    for (int k = 0; k < SUB; ++k) a[k] = fma(-(wr[k] * rd), wc, a[k]);
+  }
+  __syncthreads();
+  // rows into the order in which they were taken; row r has multipliers in columns < pos[r]
+  {
+    T v[PER];
+#pragma unroll
+    for (int q = 0; q < PER; ++q) v[q] = tile[((q * FACTOR_THREADS + tid) >> 6) * LEAF_PAD + (tid & 63)];
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int r = (q * FACTOR_THREADS + tid) >> 6, c = tid & 63, to = pos[r];
+      tile[to * LEAF_PAD + c] = c == to ? dl[to] : v[q];
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < LEAF * LEAF; e += FACTOR_THREADS) {
+    const int r = e >> 6, c = e & 63;
+    if (r < w && c <= r) A[(int64_t)r * ld + c] = tile[r * LEAF_PAD + c];
+  }
+  leaf_invert_sub<T>(tile, linv, wave, l16);
+  if (wave == 0) {
+    const T myd = dl[lane];
+    const bool zero = myd == T(0);
+    const bool finite = fabs((double)myd) <= 1.7976931348623157e308;
+    const bool bad = lane < w && (zero || !finite);
+    if (lane < w) {
+      dvec[lane] = myd;
+      dinv[lane] = fast_rcp(myd);
+      perm[lane] = (int)pivot0 + src[lane];
+    }
+    const unsigned long long mask = __ballot(bad);
+    if (mask != 0ull) {
+      const int first = __ffsll((long long)mask) - 1;
+      if (lane == first) {
+        unsigned long long idx = (unsigned long long)(pivot0 + first);
+        unsigned long long old = atomicMin(&flags->first_bad, idx);
+        if (idx <= old) atomicExch(&flags->bad_kind, zero ? 1ull : 2ull);
+      }
+    }
+  }
+  __builtin_amdgcn_s_setprio(0);
+}
+
+// ---------------------------------------------------------------------------
 // leaf solve
 // ---------------------------------------------------------------------------
 // Rows below a factored leaf: X (m x w, in place) <- X L^-T D^-1.
@@ -377,13 +588,16 @@ __global__ __launch_bounds__(FACTOR_THREADS) void leaf_factor_kernel(
 // (products on the matrix cores, terms in the order p = 0, 1, ...), then
 // W_b = T_b L_bb^-T with the inverse of the unit-lower diagonal sub-block prepared
 // by the factor kernel, then L_b = W_b D_b^-1 goes back to memory.
+// perm (or null): the leaf was factored with pivoting; perm[j] - perm0 is the column of
+// the panel that belongs at position j.  A wavefront reads all 64 columns of its rows
+// before it writes any of them.
 constexpr int SOLVE_ROWS = 64;   // rows per workgroup
 
 template <typename T>
 __global__ __launch_bounds__(256) void leaf_solve_kernel(
     T* __restrict__ Xg, int64_t ld, int m, int w, const T* __restrict__ Lleaf, int64_t ldl,
     const T* __restrict__ dinv, const T* __restrict__ linv, T* __restrict__ Wg, int64_t ldw,
-    const T* __restrict__ dvec, int wfrom) {
+    const T* __restrict__ dvec, int wfrom, const int* __restrict__ perm, int perm0) {
   using X = Mfma<T>;
   using acc_t = typename X::acc_t;
   // Only the sub-blocks L[b, p], p < b, and the solved W_p, p < NSUB - 1, are ever
@@ -411,7 +625,10 @@ __global__ __launch_bounds__(256) void leaf_solve_kernel(
     for (int r = 0; r < 4; ++r) {
       const int64_t row = r0 + X::acc_row(lane, r);
       const int col = b * SUB + l16;
-      xb[b][r] = (row < m && col < w) ? Xg[row * ld + col] : T(0);
+      // with a permutation of the leaf, column `col` of the result is the column that
+      // was taken at that step
+      const int from = (perm != nullptr && col < w) ? perm[col] - perm0 : col;
+      xb[b][r] = (row < m && col < w) ? Xg[row * ld + from] : T(0);
     }
   // leaf data shared by the four wavefronts
   {
@@ -439,6 +656,10 @@ __global__ __launch_bounds__(256) void leaf_solve_kernel(
     if (tid < LEAF) { rinv[tid] = myr; dsc[tid] = myd; }
   }
   __syncthreads();
+  // with a permutation a store below may hit an entry that another lane of this wavefront
+  // loads above: every load has returned before the first store is issued (free here:
+  // the leaf data, requested after the rows, has already arrived)
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   T* ws = wsc[wave];
   T* ts = tsc[wave];

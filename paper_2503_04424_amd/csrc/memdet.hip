@@ -125,6 +125,10 @@ struct Launcher {
   T* linv = nullptr;          // inverses of the current leaf's diagonal sub-blocks
   DevFlags* flags = nullptr;
   bool spd = false;           // positive-definite form (MDET_FLAG_ASSUME_SPD)
+  // n indices (or none): every leaf is factored with the pivot taken from its own
+  // diagonal, and perm[j] is the row/column of the input that ended at position j
+  // (MDET_FLAG_PIVOT).  The leaf then has a launch of its own.
+  int* perm = nullptr;
   // Two arrays of n x wld elements (or none): while a block column is factored its rows
   // are also stored scaled by the pivots, W = L D, so that the updates that use the
   // column read their left operand ready-made (MDET_FLAG_SCALED_COPY).  Column k uses
@@ -180,7 +184,7 @@ struct Launcher {
     const UpdGrid ug = update_grid(M, N, lower, tile);
     if (8 * ug.per > INT32_MAX) return MDET_EINVAL;
     FusedLeaf<T> fl{0, nullptr, nullptr, nullptr, 0, nullptr, 0};
-    if (fuse) {
+    if (fuse && !perm) {
       if (!lower || fuse->w > LEAF || fuse->w > N || fuse->w > M) return MDET_EINVAL;
       fl = *fuse;
     }
@@ -270,7 +274,13 @@ struct Launcher {
                   bool first_done = false, T* Wp = nullptr, int64_t wskip = 0) {
     if (w <= 0) return MDET_OK;
     if (w <= LEAF) {
-      if (!first_done) {
+      if (perm) {
+        if (spd) return MDET_EINVAL;
+        hipLaunchKernelGGL((leaf_factor_pivoted_kernel<T>), dim3(1), dim3(FACTOR_THREADS), 0, st, P, ld,
+                           (int)w, dvec + d0, dinv + d0, linv, perm + d0, (long long)d0, flags);
+        fail->check(hipGetLastError());
+        ++launches;
+      } else if (!first_done) {
         hipLaunchKernelGGL((leaf_factor_kernel<T>), dim3(1), dim3(FACTOR_THREADS), 0, st, P, ld,
                            (int)w, dvec + d0, dinv + d0, linv, (long long)d0, flags, spd ? 1 : 0);
         fail->check(hipGetLastError());
@@ -284,7 +294,8 @@ struct Launcher {
         hipLaunchKernelGGL((leaf_solve_kernel<T>), dim3((unsigned)nblk), dim3(256), 0,
                            st, P + w * ld, ld, (int)below, (int)w, (const T*)P, ld,
                            (const T*)(dinv + d0), (const T*)linv, Wp ? Wp + w * wld : (T*)nullptr, wld,
-                           (const T*)(dvec + d0), (int)(wskip > w ? wskip - w : 0));
+                           (const T*)(dvec + d0), (int)(wskip > w ? wskip - w : 0),
+                           perm ? (const int*)(perm + d0) : (const int*)nullptr, (int)d0);
         fail->check(hipGetLastError());
         ++launches;
         fma += (double)below * ((double)w * (w - 1) / 2.0);
@@ -527,6 +538,7 @@ static void bind_small(Launcher<T>& L, char* base, const SmallArea& sa) {
   L.dinv = (T*)(base + sa.dinv);
   L.linv = (T*)(base + sa.linv);
   L.flags = (DevFlags*)(base + sa.flags);
+  L.perm = sa.total > sa.perm ? (int*)(base + sa.perm) : nullptr;
   // two workgroups of the trailing update fit one compute unit (registers and LDS)
   int dev = 0, cus = 0;
   if (hipGetDevice(&dev) == hipSuccess &&
@@ -558,7 +570,7 @@ static int logdet_device_t(const mdet_params& p, const Plan& pl, T* dA, int64_t 
   if (rc != MDET_OK) { res->hip_error = fail.code; return rc; }
   res->dev_bytes_high_water = pl.dev_bytes;
 
-  const SmallArea sa = small_area(pl.n, pl.T, pl.beta);
+  const SmallArea sa = small_area(pl.n, pl.T, pl.beta, pl.pivot);
   Launcher<T> L;
   L.fail = &fail;
   L.profile = (p.flags & MDET_FLAG_PROFILE) != 0;
@@ -615,6 +627,8 @@ static int logdet_device_t(const mdet_params& p, const Plan& pl, T* dA, int64_t 
     L.reduce(s0, pl.n, pl.bs, pl.T, partial, out, running);
     if (diag && pl.n > 0)
       MDET_HIP(fail, hipMemcpyAsync(diag, L.dvec, pl.n * sizeof(T), hipMemcpyDeviceToDevice, s0));
+    if (L.perm && p.perm && pl.n > 0)
+      MDET_HIP(fail, hipMemcpyAsync(p.perm, L.perm, pl.n * sizeof(int), hipMemcpyDeviceToDevice, s0));
   }
   DeviceOut o;
   std::memset(&o, 0, sizeof(o));
@@ -709,7 +723,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
   if (rc != MDET_OK) { res->hip_error = fail.code; return rc; }
   res->dev_bytes_high_water = pl.dev_bytes;
 
-  const SmallArea sa = small_area(pl.n, pl.T, pl.beta);
+  const SmallArea sa = small_area(pl.n, pl.T, pl.beta, pl.pivot);
   Launcher<T> L;
   L.fail = &fail;
   L.profile = (p.flags & MDET_FLAG_PROFILE) != 0;
@@ -913,6 +927,8 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
     MDET_HIP(fail, hipMemcpyAsync(&o.flags, L.flags, sizeof(DevFlags), hipMemcpyDeviceToHost, s0));
     if (diag_host && n > 0)
       MDET_HIP(fail, hipMemcpyAsync(diag_host, L.dvec, n * sizeof(T), hipMemcpyDeviceToHost, s0));
+    if (L.perm && p.perm && n > 0)
+      MDET_HIP(fail, hipMemcpyAsync(p.perm, L.perm, n * sizeof(int), hipMemcpyDeviceToHost, s0));
   }
   MDET_HIP(fail, hipStreamSynchronize(sh));
   MDET_HIP(fail, hipStreamSynchronize(s1));
@@ -1091,27 +1107,42 @@ int mdet_step_schur_update(int32_t dtype, void* C, int64_t ldc, const void* A, i
   return rc;
 }
 
-int mdet_step_panel_factor(int32_t dtype, void* P, int64_t ld, int64_t m, int64_t w, void* d,
-                           void* dinv, int64_t pivot_index0, void* flags, void* stream) {
+static int step_panel_factor(int32_t dtype, void* P, int64_t ld, int64_t m, int64_t w, void* d,
+                             void* dinv, int32_t* perm, int64_t pivot_index0, void* flags, void* stream) {
   if (!P || !d || !dinv || !flags || m < 0 || w < 0 || w > m || ld < w) return MDET_EINVAL;
+  if (perm && pivot_index0 + w > INT32_MAX) return MDET_EINVAL;
   HipFail fail;
   int rc;
   if (dtype == MDET_F64) {
     if (ld % 2 || ((uintptr_t)P & 15u)) return MDET_EINVAL;
     Launcher<double> L; L.fail = &fail;
-    // the launcher indexes dvec/dinv by global pivot index
+    // the launcher indexes dvec/dinv/perm by global pivot index
     L.dvec = (double*)d - pivot_index0; L.dinv = (double*)dinv - pivot_index0; L.flags = (DevFlags*)flags;
     L.linv = (double*)((char*)flags + 16);
+    L.perm = perm ? perm - pivot_index0 : nullptr;
     rc = L.factor_cols((hipStream_t)stream, (double*)P, ld, m, w, pivot_index0);
   } else if (dtype == MDET_F32) {
     if (ld % 4 || ((uintptr_t)P & 15u)) return MDET_EINVAL;
     Launcher<float> L; L.fail = &fail;
     L.dvec = (float*)d - pivot_index0; L.dinv = (float*)dinv - pivot_index0; L.flags = (DevFlags*)flags;
     L.linv = (float*)((char*)flags + 16);
+    L.perm = perm ? perm - pivot_index0 : nullptr;
     rc = L.factor_cols((hipStream_t)stream, (float*)P, ld, m, w, pivot_index0);
   } else return MDET_EINVAL;
   if (!fail.ok()) return MDET_EHIP;
   return rc;
+}
+
+int mdet_step_panel_factor(int32_t dtype, void* P, int64_t ld, int64_t m, int64_t w, void* d,
+                           void* dinv, int64_t pivot_index0, void* flags, void* stream) {
+  return step_panel_factor(dtype, P, ld, m, w, d, dinv, nullptr, pivot_index0, flags, stream);
+}
+
+int mdet_step_panel_factor_pivoted(int32_t dtype, void* P, int64_t ld, int64_t m, int64_t w, void* d,
+                                   void* dinv, int32_t* perm, int64_t pivot_index0, void* flags,
+                                   void* stream) {
+  if (!perm) return MDET_EINVAL;
+  return step_panel_factor(dtype, P, ld, m, w, d, dinv, perm, pivot_index0, flags, stream);
 }
 
 int mdet_step_logdet_reduce(int32_t dtype, const void* d, int64_t n, double* out, void* stream) {

@@ -29,6 +29,7 @@ struct Plan {
   bool device_input = false;
   bool out_of_core = false;
   bool need_copy = false;          // device input: work on a copy (overwrite = 0)
+  bool pivot = false;              // MDET_FLAG_PIVOT
   uint64_t small_bytes = 0;        // pivots, reciprocals, flags, reduction scratch
   uint64_t layout_bytes = 0;       // packed lower block-column layout
   uint64_t copy_bytes = 0;
@@ -71,9 +72,10 @@ inline uint64_t align256(uint64_t x) { return (x + 255) / 256 * 256; }
 
 // Layout of the small scratch area (offsets in bytes from its start).
 struct SmallArea {
-  uint64_t dvec, dinv, linv, flags, partial, out, running, total;
+  uint64_t dvec, dinv, linv, flags, partial, out, running, perm, total;
 };
-inline SmallArea small_area(int64_t n, int64_t T, int beta) {
+// pivot: room for the permutation (n 32-bit indices) of MDET_FLAG_PIVOT
+inline SmallArea small_area(int64_t n, int64_t T, int beta, bool pivot) {
   SmallArea a;
   uint64_t o = 0;
   a.dvec = o; o += align256((uint64_t)(n > 0 ? n : 1) * beta);
@@ -83,6 +85,7 @@ inline SmallArea small_area(int64_t n, int64_t T, int beta) {
   a.partial = o; o += align256((uint64_t)(T > 0 ? T : 1) * 3 * 8);
   a.out = o; o += 256;
   a.running = o; o += align256((uint64_t)(T > 0 ? T : 1) * 8);
+  a.perm = o; if (pivot) o += align256((uint64_t)(n > 0 ? n : 1) * 4);
   a.total = o;
   return a;
 }
@@ -102,7 +105,10 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
   pl.T = p.n > 0 ? (p.n + pl.bs - 1) / pl.bs : 0;
   pl.device_input = device_input;
   pl.tile_bytes = (uint64_t)pl.bs * pl.bs * pl.beta;
-  pl.small_bytes = small_area(pl.n, pl.T, pl.beta).total;
+  pl.pivot = (p.flags & MDET_FLAG_PIVOT) != 0;
+  if (pl.pivot && (p.flags & MDET_FLAG_ASSUME_SPD)) return MDET_EINVAL;   // nothing to choose from
+  if (pl.pivot && p.n > INT32_MAX) return MDET_EINVAL;
+  pl.small_bytes = small_area(pl.n, pl.T, pl.beta, pl.pivot).total;
   pl.layout_bytes = pl.T > 0 ? (uint64_t)pl.col_offset(pl.T) * pl.beta : 0;
   pl.panels.clear();
   pl.h2d = pl.d2h = 0;
