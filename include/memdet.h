@@ -116,7 +116,11 @@ typedef struct mdet_params {
                                      ready-made instead of scaling it on the fly.  Same
                                      bits in the result.  Used where the whole matrix is
                                      resident and the budget allows; ignored otherwise
-                                     and with MDET_FLAG_ASSUME_SPD (nothing to scale).  */
+                                     and with MDET_FLAG_ASSUME_SPD (nothing to scale).
+                                     Without the flag the library does the same by itself
+                                     when mem_budget_bytes == 0 and n >= 24576 (where it
+                                     pays; mdet_plan and mdet_workspace_query count it),
+                                     and goes without if that memory cannot be had.      */
 #define MDET_FLAG_ASSUME_SPD 16u  /* the matrix is symmetric positive definite: use the
                                      Cholesky form of the method (the paper's algorithm
                                      for positive-definite matrices, App. D; block

@@ -532,6 +532,19 @@ struct Workspace {
   ~Workspace() { if (owned && base) (void)hipFree(base); }
 };
 
+// The plan's workspace; if it cannot be had and the plan holds the pivot-scaled copies
+// without having been asked for them, once more without them.
+static int acquire_workspace(Workspace& ws, const mdet_params& p, Plan& pl, HipFail& fail) {
+  int rc = ws.acquire(p, pl.dev_bytes, fail);
+  if (rc == MDET_ENOMEM_DEVICE && pl.wcopy_optional && pl.wcopy_bytes) {
+    pl.dev_bytes -= pl.wcopy_bytes;
+    pl.wcopy_bytes = 0;
+    fail.code = hipSuccess;
+    rc = ws.acquire(p, pl.dev_bytes, fail);
+  }
+  return rc;
+}
+
 template <typename T>
 static void bind_small(Launcher<T>& L, char* base, const SmallArea& sa) {
   L.dvec = (T*)(base + sa.dvec);
@@ -556,7 +569,7 @@ static void reset_flags(Launcher<T>& L, hipStream_t st) {
 // mdet_logdet_device
 // ---------------------------------------------------------------------------
 template <typename T>
-static int logdet_device_t(const mdet_params& p, const Plan& pl, T* dA, int64_t ld, mdet_result* res,
+static int logdet_device_t(const mdet_params& p, const Plan& plan, T* dA, int64_t ld, mdet_result* res,
                            T* diag, const void* widen_from = nullptr) {
   HipFail fail;
   int dev = 0;
@@ -565,8 +578,9 @@ static int logdet_device_t(const mdet_params& p, const Plan& pl, T* dA, int64_t 
   MDET_HIP(fail, get_streams(dev, &ss, false));
   if (!fail.ok()) { res->hip_error = fail.code; return MDET_EHIP; }
 
+  Plan pl = plan;
   Workspace ws;
-  int rc = ws.acquire(p, pl.dev_bytes, fail);
+  int rc = acquire_workspace(ws, p, pl, fail);
   if (rc != MDET_OK) { res->hip_error = fail.code; return rc; }
   res->dev_bytes_high_water = pl.dev_bytes;
 
@@ -709,7 +723,7 @@ static void copy_col_rows(HipFail& fail, const Plan& pl, int64_t j, int64_t r0, 
 }
 
 template <typename T>
-static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, mdet_result* res,
+static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut, mdet_result* res,
                          T* diag_host) {
   HipFail fail;
   int dev = 0;
@@ -718,8 +732,9 @@ static int logdet_host_t(const mdet_params& p, const Plan& pl, T* hA, T* hOut, m
   MDET_HIP(fail, get_streams(dev, &ss, true));
   if (!fail.ok()) { res->hip_error = fail.code; return MDET_EHIP; }
 
+  Plan pl = plan;
   Workspace ws;
-  int rc = ws.acquire(p, pl.dev_bytes, fail);
+  int rc = acquire_workspace(ws, p, pl, fail);
   if (rc != MDET_OK) { res->hip_error = fail.code; return rc; }
   res->dev_bytes_high_water = pl.dev_bytes;
 

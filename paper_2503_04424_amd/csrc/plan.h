@@ -34,6 +34,7 @@ struct Plan {
   uint64_t layout_bytes = 0;       // packed lower block-column layout
   uint64_t copy_bytes = 0;
   uint64_t wcopy_bytes = 0;        // two pivot-scaled copies of a block column (MDET_FLAG_SCALED_COPY)
+  bool wcopy_optional = false;     // taken without being asked for: dropped if memory is short
   uint64_t ring_tiles = 3;         // streamed row blocks in flight (out-of-core)
   uint64_t tile_bytes = 0;
   uint64_t dev_bytes = 0;          // total device bytes the call uses
@@ -117,8 +118,14 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
   // optional: room for W = L D of the block column being factored and of the one whose
   // bulk update is still running; taken only where everything is resident and it fits
   pl.wcopy_bytes = 0;
-  const uint64_t wcopy = ((p.flags & MDET_FLAG_SCALED_COPY) && !(p.flags & MDET_FLAG_ASSUME_SPD) && pl.T >= 2)
+  // asked for, or taken unasked where nothing caps the memory and the matrix is large
+  // enough for it to pay (measured cross-over between n = 16384 and 24576); the unasked
+  // one is given up again if the workspace cannot be had (wcopy_optional)
+  const bool wcopy_auto = !(p.flags & MDET_FLAG_SCALED_COPY) && budget == 0 && p.n >= 24576;
+  const uint64_t wcopy = (((p.flags & MDET_FLAG_SCALED_COPY) || wcopy_auto) &&
+                          !(p.flags & MDET_FLAG_ASSUME_SPD) && pl.T >= 2)
                              ? 2 * align256((uint64_t)pl.n * pl.bs * pl.beta) : 0;
+  pl.wcopy_optional = wcopy_auto && wcopy != 0;
 
   if (device_input) {
     const int vec = 16 / pl.beta;

@@ -128,6 +128,19 @@ def test_plan_rounds_block_size_and_handles_edges(M):
     assert a.dev_bytes_needed < 1 << 20 and b.dev_bytes_needed >= 8192 * 8192 * 8
 
 
+def test_plan_takes_the_scaled_copy_unasked_only_for_large_uncapped_calls(M):
+    def need(n, bs, **kw):
+        return M.mdet_plan(n, "f64", bs, for_device_input=True, **kw).dev_bytes_needed
+    for n, bs in ((24576, 1024), (32768, 2048), (131072, 4096)):
+        asked = need(n, bs, flags=M.FLAG_SCALED_COPY)
+        assert need(n, bs) == asked == need(n, bs, mem_budget=1 << 50) + 2 * n * bs * 8
+        assert need(n, bs, flags=M.FLAG_ASSUME_SPD) == need(n, bs, mem_budget=1 << 50)
+    assert need(16384, 1024) == need(16384, 1024, mem_budget=1 << 50)
+    # host entry point, everything resident
+    h = M.mdet_plan(32768, "f64", 2048)
+    assert h.dev_bytes_needed == M.mdet_plan(32768, "f64", 2048, flags=M.FLAG_SCALED_COPY).dev_bytes_needed
+
+
 def test_plan_fp32_storage_with_fp64_arithmetic(M):
     n = 3000
     plain = M.mdet_plan(n, "f32", 256, overwrite=True, for_device_input=True)

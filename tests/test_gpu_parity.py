@@ -335,6 +335,26 @@ def test_scaled_copy_gives_the_same_bits(M, cfg, n, bs, dtype):
     assert tight.logabsdet == ref.logabsdet and tight.dev_bytes_high_water == plain.dev_bytes_needed
 
 
+def test_scaled_copy_is_taken_unasked_for_a_large_uncapped_call_and_dropped_if_memory_is_short(M):
+    # no budget and n >= 24576: the plan holds the two arrays of MDET_FLAG_SCALED_COPY by
+    # itself; a caller's workspace that has no room for them is not an error; same bits
+    n, bs, rho = 24576, 1024, 0.5
+    plain_ws, _ = M.mdet_workspace_query(n, "f64", bs, mem_budget=1 << 50, for_device_input=True)
+    auto_ws, _ = M.mdet_workspace_query(n, "f64", bs, for_device_input=True)
+    assert auto_ws == plain_ws + 2 * n * bs * 8
+    idx = torch.arange(n, device="cuda", dtype=torch.float64)
+    a = (idx[:, None] - idx[None, :]).abs_()
+    a = torch.pow(torch.tensor(rho, dtype=torch.float64, device="cuda"), a, out=a)
+    r_auto = M.mdet_logdet_device(a.clone(), block_size=bs, overwrite=True)
+    assert r_auto.status == 0 and r_auto.dev_bytes_high_water == auto_ws
+    ws = torch.empty(plain_ws, dtype=torch.uint8, device="cuda")
+    r_short = M.mdet_logdet_device(a.clone(), block_size=bs, overwrite=True, workspace=ws)
+    assert r_short.status == 0 and r_short.dev_bytes_high_water == plain_ws
+    assert r_short.logabsdet == r_auto.logabsdet
+    closed = (n - 1) * math.log(1 - rho * rho)          # KMS matrix
+    assert abs(r_auto.logabsdet - closed) <= 1e-10 * abs(closed)
+
+
 @pytest.mark.parametrize("store", ["float16", "bfloat16"])
 @pytest.mark.parametrize("n,bs", [(600, 128), (1030, 256)])
 def test_sixteen_bit_storage_with_fp64_arithmetic(M, store, n, bs):
