@@ -92,4 +92,25 @@ __global__ __launch_bounds__(256) void widen_lower_kernel(const S* __restrict__ 
   for (int64_t j = threadIdx.x; j < end; j += 256) dst[i * ldd + j] = widen_exact(src[i * lds + j]);
 }
 
+// X[r][c] *= d[c] in place, rows x cols with leading dimension ld (cols and ld multiples
+// of the 16-byte vector): rows of L of a finished block column become rows of W = L D,
+// each product rounded once, as the update kernels round it when they scale on the fly.
+template <typename T>
+__global__ __launch_bounds__(256) void scale_columns_kernel(T* __restrict__ X, int64_t ld, int64_t rows,
+                                                            int cols, const T* __restrict__ d) {
+  constexpr int VEC = 16 / (int)sizeof(T);
+  using vec_t = T __attribute__((ext_vector_type(VEC)));
+  const int per_row = cols / VEC;
+  const int64_t total = rows * per_row;
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+    const int64_t r = e / per_row;
+    const int c = (int)(e % per_row) * VEC;
+    vec_t v = *reinterpret_cast<vec_t*>(X + r * ld + c);
+    const vec_t s = *reinterpret_cast<const vec_t*>(d + c);
+#pragma unroll
+    for (int q = 0; q < VEC; ++q) v[q] *= s[q];
+    *reinterpret_cast<vec_t*>(X + r * ld + c) = v;
+  }
+}
+
 }  // namespace mdet

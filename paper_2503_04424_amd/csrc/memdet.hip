@@ -909,10 +909,22 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
             MDET_HIP(fail, hipEventRecord(slot_ready[sl], sh));
             MDET_HIP(fail, hipStreamWaitEvent(s0, slot_ready[sl], 0));
             if (k == 0) MDET_HIP(fail, hipStreamWaitEvent(s0, row_ready[i], 0));
+            // The streamed rows are the left operand of one update per column of the
+            // group: scaled by the pivots once, in place (W = L D), they serve all of
+            // them through the kernel that scales nothing.
+            const bool prescaled = !L.spd && wc > 1;
+            if (prescaled) {
+              const int64_t vecs = wi * (bs / (16 / (int64_t)sizeof(T)));
+              const unsigned grid = (unsigned)std::min<int64_t>((vecs + 255) / 256, 4096);
+              hipLaunchKernelGGL((scale_columns_kernel<T>), dim3(grid), dim3(256), 0, s0, ring[sl], bs, wi,
+                                 (int)bs, dk);
+              MDET_HIP(fail, hipGetLastError());
+              ++L.launches;
+            }
             for (int64_t j = j0; j < j1 && rc == MDET_OK; ++j) {
               T* C = cols[j].base + (i - j) * bs * cols[j].ld;
               rc = L.update(s0, C, cols[j].ld, ring[sl], bs, bpool[q] + (j - j0) * bs * bs, bs, dk, wi,
-                            pl.col_width(j), bs, false, true);
+                            pl.col_width(j), bs, false, true, nullptr, -1, prescaled);
             }
             if (!slot_free[sl]) slot_free[sl] = events.get();
             MDET_HIP(fail, hipEventRecord(slot_free[sl], s0));
