@@ -591,13 +591,17 @@ __global__ __launch_bounds__(FACTOR_THREADS) void leaf_factor_pivoted_kernel(
 // perm (or null): the leaf was factored with pivoting; perm[j] - perm0 is the column of
 // the panel that belongs at position j.  A wavefront reads all 64 columns of its rows
 // before it writes any of them.
+// fix_src (or null): the launch has one workgroup more than its rows need, and that one
+// copies the 64 x 64 row-major block at fix_src to fix_dst (leading dimension fix_ld), a
+// block outside this launch's own rows and columns.
 constexpr int SOLVE_ROWS = 64;   // rows per workgroup
 
 template <typename T>
 __global__ __launch_bounds__(256) void leaf_solve_kernel(
     T* __restrict__ Xg, int64_t ld, int m, int w, const T* __restrict__ Lleaf, int64_t ldl,
     const T* __restrict__ dinv, const T* __restrict__ linv, T* __restrict__ Wg, int64_t ldw,
-    const T* __restrict__ dvec, int wfrom, const int* __restrict__ perm, int perm0) {
+    const T* __restrict__ dvec, int wfrom, const int* __restrict__ perm, int perm0,
+    const T* __restrict__ fix_src, T* __restrict__ fix_dst, int64_t fix_ld) {
   using X = Mfma<T>;
   using acc_t = typename X::acc_t;
   // Only the sub-blocks L[b, p], p < b, and the solved W_p, p < NSUB - 1, are ever
@@ -616,6 +620,19 @@ __global__ __launch_bounds__(256) void leaf_solve_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
 
+  // a 64 x 64 block that an earlier launch left beside its place (leaf_pair_kernel): the
+  // launch then has one workgroup more, which does only this
+  if (fix_src != nullptr && blockIdx.x == gridDim.x - 1) {
+    T v[LEAF * LEAF / 256];
+#pragma unroll
+    for (int q = 0; q < LEAF * LEAF / 256; ++q) v[q] = fix_src[q * 256 + tid];
+#pragma unroll
+    for (int q = 0; q < LEAF * LEAF / 256; ++q) {
+      const int e = q * 256 + tid;
+      fix_dst[(int64_t)(e >> 6) * fix_ld + (e & 63)] = v[q];
+    }
+    return;
+  }
   // this wavefront's rows, straight into accumulator layout (16 lanes = 128 bytes of a row)
   const int64_t r0 = ((int64_t)blockIdx.x * 4 + wave) * SUB;
   acc_t xb[NSUB];

@@ -599,4 +599,225 @@ __global__ __launch_bounds__(UPD_THREADS) void leaf_update_kernel(
   }
 }
 
+// Two leaves side by side (a 128-column strip of a block column), the first one
+// factored: one launch solves the rows below the first leaf against it, updates the
+// second leaf's columns of those rows with the result (K = 64), and factors the second
+// leaf.  Separately these are a leaf_solve_kernel and a leaf_update_kernel, the second
+// waiting for all of the first; here a workgroup needs nothing from the others: it
+// solves its own 64 rows and, once more, the 64 rows of the second leaf (rows 0 .. 63
+// below the first), whose solved form is the right operand of everybody's update.
+// Those 64 rows therefore stay as they are in memory during this launch (every
+// workgroup reads them unsolved); workgroup 0, which owns them, puts their solved form
+// into `l10` (64 x 64, row-major) and the solve launch of the second leaf copies it
+// into place (leaf_solve_kernel, fix_src).
+//   Xg    row 0 of the region below the first leaf, column 0 of the strip; m rows
+//   Lleaf the first leaf, factored; dinv, dvec, linv: its reciprocal pivots, pivots and
+//         the inverses of its diagonal sub-blocks (linv must not be the array that the
+//         fused factorisation of the second leaf writes, fl.linv: workgroups start at
+//         different times)
+//   Wg    as in leaf_solve_kernel
+// The update's left operand is the solved row before its division by the pivots,
+// w = l d, which the solve keeps in LDS anyway; its right operand the second leaf's rows
+// l (SCALED, the positive-definite form, where dinv holds d^(-1/2) and l stands for the
+// row of the Cholesky factor: l d^(-1/2), so that the product is again w (1/d) w^T).
+// LDS: 94 KB in fp64, which fits beside one workgroup of the trailing update on a
+// compute unit, so that the launch need not wait for whole units to drain.
+template <typename T, bool SCALED = false>
+__global__ __launch_bounds__(256) void leaf_pair_kernel(
+    T* __restrict__ Xg, int64_t ld, int m, const T* __restrict__ Lleaf, int64_t ldl,
+    const T* __restrict__ dinv, const T* __restrict__ linv, const T* __restrict__ dvec,
+    T* __restrict__ Wg, int64_t ldw, int wfrom, T* __restrict__ l10, FusedLeaf<T> fl) {
+  using X = Mfma<T>;
+  using acc_t = typename X::acc_t;
+  using vec_t = typename X::vec_t;
+  constexpr int VEC = X::VEC, BK = X::BK, KS = BK / 4;
+  constexpr int KT = 64;
+  constexpr int S = (KT * (int)sizeof(T) + 16) / (int)sizeof(T);   // padded LDS row of an operand
+  constexpr int LW = LEAF - SUB;
+  constexpr int LW_PAD = LW + 1;
+  __shared__ T Ls[LW * LW_PAD];                 // first leaf: L[16.., ..47], strictly lower part
+  __shared__ T Li[NSUB * SUB * SUB_PAD];        // inverses of its diagonal sub-blocks
+  __shared__ T rinv[LEAF];
+  __shared__ T dsc[LEAF];
+  // As: the solved rows w of the workgroup, 16 per wavefront (while a wavefront solves the
+  // second leaf's rows, theirs); Bs: the second leaf's rows l; later the second leaf itself
+  __shared__ __attribute__((aligned(16))) T ops[2 * 64 * S];
+  static_assert(2 * 64 * S >= FACTOR_LDS_ELEMS, "the fused leaf needs the operand buffers");
+  T* As = ops;
+  T* Bs = ops + 64 * S;
+  __builtin_amdgcn_s_setprio(2);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, g = lane >> 4;
+  const int blk = blockIdx.x;
+  const bool first = blk == 0;                  // this workgroup's rows are the second leaf's
+
+  // the block of C: rows 64 blk .. of the region, columns 64 .. 127 of the strip; its
+  // (0, 0) for blk = 0 is on the matrix diagonal
+  T* C = Xg + LEAF;
+  const int row0 = blk * 64;
+  const int wm = wave >> 1, wn = wave & 1;
+  const bool active = !(row0 + wm * 32 + 31 < wn * 32);
+  acc_t acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = acc_t{0, 0, 0, 0};
+  if (active) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int grow = row0 + wm * 32 + i * 16 + X::acc_row(lane, r);
+        if (grow >= m) continue;
+        const T* crow = C + (int64_t)grow * ld;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int gcol = wn * 32 + j * 16 + l16;
+          if (gcol <= grow) acc[i][j][r] = crow[gcol];
+        }
+      }
+  }
+  // rows to solve, in accumulator layout: this wavefront's 16 of the workgroup's own
+  // rows and its 16 of the second leaf's
+  const int64_t r_own = ((int64_t)blk * 4 + wave) * SUB, r_leaf = (int64_t)wave * SUB;
+  acc_t x_own[NSUB], x_leaf[NSUB];
+#pragma unroll
+  for (int b = 0; b < NSUB; ++b)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int col = b * SUB + l16;
+      const int64_t ro = r_own + X::acc_row(lane, r), rl = r_leaf + X::acc_row(lane, r);
+      x_own[b][r] = ro < m ? Xg[ro * ld + col] : T(0);
+      x_leaf[b][r] = (!first && rl < m) ? Xg[rl * ld + col] : T(0);
+    }
+  {
+    T v[LEAF * LEAF / 256];
+#pragma unroll
+    for (int q = 0; q < LEAF * LEAF / 256; ++q) {
+      const int e = q * 256 + tid, r = e >> 6, c = e & 63;
+      v[q] = c < r ? Lleaf[(int64_t)r * ldl + c] : T(0);
+    }
+    T u[NSUB * SUB * SUB / 256];
+#pragma unroll
+    for (int q = 0; q < NSUB * SUB * SUB / 256; ++q) u[q] = linv[q * 256 + tid];
+    const T myr = tid < LEAF ? dinv[tid < LEAF ? tid : 0] : T(0);
+    const T myd = tid < LEAF ? dvec[tid < LEAF ? tid : 0] : T(0);
+#pragma unroll
+    for (int q = 0; q < LEAF * LEAF / 256; ++q) {
+      const int e = q * 256 + tid, r = e >> 6, c = e & 63;
+      if (r >= SUB && c < LW) Ls[(r - SUB) * LW_PAD + c] = v[q];
+    }
+#pragma unroll
+    for (int q = 0; q < NSUB * SUB * SUB / 256; ++q) {
+      const int e = q * 256 + tid, bq = e >> 8, i = (e >> 4) & 15, k = e & 15;
+      Li[(bq * SUB + i) * SUB_PAD + k] = u[q];
+    }
+    if (tid < LEAF) { rinv[tid] = myr; dsc[tid] = myd; }
+  }
+  __syncthreads();
+
+  // X L^-T D^-1 for 16 rows, as leaf_solve_kernel; the wavefront's 16 rows of As hold the
+  // solved sub-blocks, and sub-block b's columns of them also serve for the change of
+  // layout of T_b (a wavefront's LDS operations complete in order).  own: the
+  // workgroup's rows (stored, As keeps them as the left operand); otherwise the second
+  // leaf's rows (right operand only).
+  T* ws = As + wave * SUB * S;
+  auto solve16 = [&](acc_t (&x)[NSUB], const int64_t r0, const bool own) {
+#pragma unroll
+    for (int b = 0; b < NSUB; ++b) {
+      acc_t a = x[b];
+#pragma unroll 1
+      for (int p = 0; p < b; ++p) {
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+          const int k = p * SUB + 4 * s4 + g;
+          a = X::mfma(-ws[l16 * S + k], Ls[((b - 1) * SUB + l16) * LW_PAD + k], a);
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ws[X::acc_row(lane, r) * S + b * SUB + l16] = a[r];
+      acc_t wb = acc_t{0, 0, 0, 0};
+#pragma unroll
+      for (int s4 = 0; s4 < 4; ++s4) {
+        const int k = 4 * s4 + g;
+        wb = X::mfma(ws[l16 * S + b * SUB + k], Li[(b * SUB + l16) * SUB_PAD + k], wb);
+      }
+      const T rj = rinv[b * SUB + l16];
+      const T dj = dsc[b * SUB + l16];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int row16 = X::acc_row(lane, r);
+        ws[row16 * S + b * SUB + l16] = wb[r];
+        const int64_t row = r0 + row16;
+        const int col = b * SUB + l16;
+        const T lv = wb[r] * rj;
+        if (own && row < m) {
+          if (first) l10[(int)row * LEAF + col] = lv;
+          else Xg[row * ld + col] = lv;
+          if (Wg != nullptr && row >= wfrom) Wg[row * ldw + col] = lv * dj;
+        }
+        if (!own || first) Bs[(wave * SUB + row16) * S + col] = SCALED ? lv * rj : lv;
+      }
+    }
+  };
+  if (!first) solve16(x_leaf, r_leaf, false);
+  solve16(x_own, r_own, true);
+  __syncthreads();
+
+  if (active) {
+#pragma unroll
+    for (int slab = 0; slab < KT / BK; ++slab) {
+      const T* as = &As[(wm * 32 + l16) * S + slab * BK + g * KS];
+      const T* bs = &Bs[(wn * 32 + l16) * S + slab * BK + g * KS];
+#pragma unroll
+      for (int h = 0; h < KS / VEC; ++h) {
+        vec_t fa[2], fb[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          fa[t] = -*reinterpret_cast<const vec_t*>(as + t * 16 * S + h * VEC);
+          fb[t] = *reinterpret_cast<const vec_t*>(bs + t * 16 * S + h * VEC);
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i][j] = X::mfma(fa[i][e], fb[j][e], acc[i][j]);
+      }
+    }
+  }
+  const bool fuse = first && fl.w > 0;
+  const int wleaf = fuse ? fl.w : 0;
+  if (fuse) {
+    __syncthreads();   // everybody is done with the operands
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          leaf_tile_put<T>(ops, wm * 32 + i * 16 + X::acc_row(lane, r), wn * 32 + j * 16 + l16, wleaf,
+                           acc[i][j][r]);
+  }
+  if (active) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int grow = row0 + wm * 32 + i * 16 + X::acc_row(lane, r);
+        if (grow >= m) continue;
+        T* crow = C + (int64_t)grow * ld;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int gcol = wn * 32 + j * 16 + l16;
+          if (gcol <= grow && !(grow < wleaf && gcol < wleaf)) crow[gcol] = acc[i][j][r];
+        }
+      }
+  }
+  if (fuse) {
+    __syncthreads();
+    leaf_factor_body<T, true>(C, ld, fl.w, fl.dvec, fl.dinv, fl.linv, fl.pivot0, fl.flags, ops, fl.spd);
+  }
+}
+
 }  // namespace mdet

@@ -122,7 +122,15 @@ struct Launcher {
   HipFail* fail;
   T* dvec = nullptr;
   T* dinv = nullptr;
-  T* linv = nullptr;          // inverses of the current leaf's diagonal sub-blocks
+  T* linv = nullptr;          // inverses of a leaf's diagonal sub-blocks (see linv_of)
+  // 64 x 64 elements (or none): where leaf_pair_kernel leaves the solved rows of the
+  // second leaf of a pair until the next solve launch copies them into place.  With it
+  // linv is two arrays, used by leaves in turn: that kernel reads one leaf's while one
+  // of its workgroups already writes the next leaf's.
+  T* l10 = nullptr;
+  const T* fix_src = nullptr; // pending copy for the next solve launch
+  T* fix_dst = nullptr;
+  int64_t fix_ld = 0;
   DevFlags* flags = nullptr;
   bool spd = false;           // positive-definite form (MDET_FLAG_ASSUME_SPD)
   // n indices (or none): every leaf is factored with the pivot taken from its own
@@ -258,9 +266,11 @@ struct Launcher {
   // What an update launch needs to factor the leaf of width w whose first pivot has
   // index d0 (see FusedLeaf).
   FusedLeaf<T> fused_leaf(int64_t w, int64_t d0) const {
-    return FusedLeaf<T>{(int)(w < LEAF ? w : LEAF), dvec + d0, dinv + d0, linv, (long long)d0, flags,
+    return FusedLeaf<T>{(int)(w < LEAF ? w : LEAF), dvec + d0, dinv + d0, linv_of(d0), (long long)d0, flags,
                         spd ? 1 : 0};
   }
+  // The array that holds the inverses of the leaf whose first pivot has index d0.
+  T* linv_of(int64_t d0) const { return l10 ? linv + ((d0 / LEAF) & 1) * (LEAF * SUB) : linv; }
 
   // Factor block column: P at its diagonal entry, m rows, w columns (w <= m).
   // d0: index of its first pivot in dvec/dinv.  first_done: the first leaf has
@@ -277,12 +287,12 @@ struct Launcher {
       if (perm) {
         if (spd) return MDET_EINVAL;
         hipLaunchKernelGGL((leaf_factor_pivoted_kernel<T>), dim3(1), dim3(FACTOR_THREADS), 0, st, P, ld,
-                           (int)w, dvec + d0, dinv + d0, linv, perm + d0, (long long)d0, flags);
+                           (int)w, dvec + d0, dinv + d0, linv_of(d0), perm + d0, (long long)d0, flags);
         fail->check(hipGetLastError());
         ++launches;
       } else if (!first_done) {
         hipLaunchKernelGGL((leaf_factor_kernel<T>), dim3(1), dim3(FACTOR_THREADS), 0, st, P, ld,
-                           (int)w, dvec + d0, dinv + d0, linv, (long long)d0, flags, spd ? 1 : 0);
+                           (int)w, dvec + d0, dinv + d0, linv_of(d0), (long long)d0, flags, spd ? 1 : 0);
         fail->check(hipGetLastError());
         ++launches;
       }
@@ -291,16 +301,52 @@ struct Launcher {
       if (below > 0) {
         if (below > INT32_MAX) return MDET_EINVAL;
         int64_t nblk = (below + SOLVE_ROWS - 1) / SOLVE_ROWS;
-        hipLaunchKernelGGL((leaf_solve_kernel<T>), dim3((unsigned)nblk), dim3(256), 0,
+        hipLaunchKernelGGL((leaf_solve_kernel<T>), dim3((unsigned)(nblk + (fix_src ? 1 : 0))), dim3(256), 0,
                            st, P + w * ld, ld, (int)below, (int)w, (const T*)P, ld,
-                           (const T*)(dinv + d0), (const T*)linv, Wp ? Wp + w * wld : (T*)nullptr, wld,
+                           (const T*)(dinv + d0), (const T*)linv_of(d0), Wp ? Wp + w * wld : (T*)nullptr, wld,
                            (const T*)(dvec + d0), (int)(wskip > w ? wskip - w : 0),
-                           perm ? (const int*)(perm + d0) : (const int*)nullptr, (int)d0);
+                           perm ? (const int*)(perm + d0) : (const int*)nullptr, (int)d0, fix_src, fix_dst,
+                           fix_ld);
+        fix_src = nullptr;
         fail->check(hipGetLastError());
         ++launches;
         fma += (double)below * ((double)w * (w - 1) / 2.0);
       }
       return MDET_OK;
+    }
+    // Two whole leaves with rows below them: the first leaf's solve, the update of the
+    // second leaf's columns and the second leaf's factorisation are one launch.  The
+    // solve launch of the second leaf, which must exist, puts a block in place that this
+    // one leaves aside.
+    if (w == 2 * LEAF && m > w && l10 && !perm && m - LEAF <= INT32_MAX) {
+      if (!first_done) {
+        hipLaunchKernelGGL((leaf_factor_kernel<T>), dim3(1), dim3(FACTOR_THREADS), 0, st, P, ld, (int)LEAF,
+                           dvec + d0, dinv + d0, linv_of(d0), (long long)d0, flags, spd ? 1 : 0);
+        ++launches;
+      }
+      const int64_t below = m - LEAF;
+      const FusedLeaf<T> fl = fused_leaf(LEAF, d0 + LEAF);
+      const dim3 grid((unsigned)((below + SOLVE_ROWS - 1) / SOLVE_ROWS)), block(256);
+      T* Wrows = Wp ? Wp + LEAF * wld : (T*)nullptr;
+      const int wfrom = (int)(wskip > LEAF ? wskip - LEAF : 0);
+      if (spd)
+        hipLaunchKernelGGL((leaf_pair_kernel<T, true>), grid, block, 0, st, P + LEAF * ld, ld, (int)below,
+                           (const T*)P, ld, (const T*)(dinv + d0), (const T*)linv_of(d0),
+                           (const T*)(dvec + d0), Wrows, wld, wfrom, l10, fl);
+      else
+        hipLaunchKernelGGL((leaf_pair_kernel<T, false>), grid, block, 0, st, P + LEAF * ld, ld, (int)below,
+                           (const T*)P, ld, (const T*)(dinv + d0), (const T*)linv_of(d0),
+                           (const T*)(dvec + d0), Wrows, wld, wfrom, l10, fl);
+      fail->check(hipGetLastError());
+      ++launches;
+      fma += ((double)LEAF * LEAF * LEAF - (double)LEAF) / 6.0;                 // first leaf
+      fma += (double)below * ((double)LEAF * (LEAF - 1) / 2.0);                  // its solve
+      fma += ((double)LEAF * (LEAF + 1) / 2 + (double)(below - LEAF) * LEAF) * LEAF;   // the update
+      fix_src = l10;
+      fix_dst = P + LEAF * ld;
+      fix_ld = ld;
+      return factor_cols(st, P + LEAF * ld + LEAF, ld, below, LEAF, d0 + LEAF, true,
+                         Wp ? Wp + LEAF * wld + LEAF : (T*)nullptr, wskip > LEAF ? wskip - LEAF : 0);
     }
     // split at a multiple of the leaf width nearest the middle
     int64_t leaves = (w + LEAF - 1) / LEAF;
@@ -550,6 +596,7 @@ static void bind_small(Launcher<T>& L, char* base, const SmallArea& sa) {
   L.dvec = (T*)(base + sa.dvec);
   L.dinv = (T*)(base + sa.dinv);
   L.linv = (T*)(base + sa.linv);
+  L.l10 = (T*)(base + sa.l10);
   L.flags = (DevFlags*)(base + sa.flags);
   L.perm = sa.total > sa.perm ? (int*)(base + sa.perm) : nullptr;
   // two workgroups of the trailing update fit one compute unit (registers and LDS)

@@ -73,7 +73,7 @@ inline uint64_t align256(uint64_t x) { return (x + 255) / 256 * 256; }
 
 // Layout of the small scratch area (offsets in bytes from its start).
 struct SmallArea {
-  uint64_t dvec, dinv, linv, flags, partial, out, running, perm, total;
+  uint64_t dvec, dinv, linv, l10, flags, partial, out, running, perm, total;
 };
 // pivot: room for the permutation (n 32-bit indices) of MDET_FLAG_PIVOT
 inline SmallArea small_area(int64_t n, int64_t T, int beta, bool pivot) {
@@ -81,7 +81,8 @@ inline SmallArea small_area(int64_t n, int64_t T, int beta, bool pivot) {
   uint64_t o = 0;
   a.dvec = o; o += align256((uint64_t)(n > 0 ? n : 1) * beta);
   a.dinv = o; o += align256((uint64_t)(n > 0 ? n : 1) * beta);
-  a.linv = o; o += align256((uint64_t)64 * 16 * beta);   // one leaf's inverse diagonal sub-blocks
+  a.linv = o; o += 2 * align256((uint64_t)64 * 16 * beta);   // inverse diagonal sub-blocks of two leaves
+  a.l10 = o; o += align256((uint64_t)64 * 64 * beta);        // a 64 x 64 block on its way into place
   a.flags = o; o += 256;
   a.partial = o; o += align256((uint64_t)(T > 0 ? T : 1) * 3 * 8);
   a.out = o; o += 256;
