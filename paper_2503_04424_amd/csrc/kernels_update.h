@@ -17,6 +17,10 @@
 // straight into LDS, double buffered, the next slab's loads in flight while the
 // current one is multiplied.  The scaling by -d is applied to the A fragments as
 // they are read from LDS; the accumulators are seeded with C.
+//
+// Also here, because they end with the same hand-over of the next leaf:
+// leaf_update_kernel (K = 64, one shot from LDS) and leaf_pair_kernel (a leaf's solve,
+// the K = 64 update by it and the next leaf's factorisation in one launch).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
