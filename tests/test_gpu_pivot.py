@@ -277,6 +277,25 @@ def test_host_paths_in_core_and_streamed(M, n, bs):
     assert res2.logabsdet == res.logabsdet and torch.equal(perm, perm2) and torch.equal(diag, diag2)
 
 
+def test_block_provider_with_pivoting(M):
+    import ctypes
+    n, bs = 900, 128
+    a = indefinite(41, n)
+
+    def provider(bi, bj, rows, cols, dst, ld):
+        buf = (ctypes.c_double * (rows * ld)).from_address(dst)
+        view = np.frombuffer(buf, dtype=np.float64).reshape(rows, ld)
+        view[:, :cols] = a[bi * bs:bi * bs + rows, bj * bs:bj * bs + cols]
+        return 0
+
+    diag = torch.empty(n, dtype=torch.float64)
+    perm = torch.full((n,), -1, dtype=torch.int32)
+    res = M.mdet_logdet_provider(provider, n, "f64", bs, flags=M.FLAG_PIVOT, diag=diag, perm=perm)
+    check_against_oracle(a, perm.numpy().astype(np.int64), diag.numpy(), res)
+    ref, p_ref, d_ref, _ = run_device(M, a, bs)
+    assert res.logabsdet == ref.logabsdet and np.array_equal(perm.numpy(), p_ref)
+
+
 def test_no_usable_pivot_is_reported_as_singular(M):
     # [[0, 1], [1, 0]] inside a larger matrix: determinant -1, but every candidate on the
     # diagonal is zero when its turn comes (a 2 x 2 pivot would be needed)
