@@ -133,6 +133,37 @@ def test_pageable_host_memory_and_caller_workspace(M):
     assert ei.value.status == M.Status.ENOMEM_DEVICE
 
 
+def test_pageable_host_memory_goes_through_the_library_s_own_staging(M):
+    # block columns of 64 MiB: several pinned chunks per copy, several threads per chunk;
+    # pageable and pinned memory must give the same bits in the result and in the factor
+    # that is written back
+    n, bs = 8192, 1024
+    a = W.config(2).dense()
+    pinned = packed(M, a, bs, pin=True)
+    plain = pinned.clone()                    # ordinary memory
+    assert not plain.is_pinned()
+    budget = 3 * n * bs * 8                   # three block columns' worth: streamed
+    kw = dict(mem_budget=budget, flags=M.FLAG_FORCE_OUT_OF_CORE, overwrite=True)
+    d1 = torch.empty(n, dtype=torch.float64)
+    d2 = torch.empty(n, dtype=torch.float64)
+    r1 = M.mdet_logdet_host(pinned, n, bs, diag=d1, **kw)
+    r2 = M.mdet_logdet_host(plain, n, bs, diag=d2, **kw)
+    assert r1.out_of_core and r2.out_of_core and r1.num_superpanels > 1
+    assert r1.status == 0 and r2.logabsdet == r1.logabsdet and torch.equal(d1, d2)
+    assert r2.bytes_h2d == r1.bytes_h2d and r2.bytes_d2h == r1.bytes_d2h
+    # the last group is not written back (nothing streams it again); everything that was is equal
+    T = n // bs
+    last_group_start = M.mdet_host_layout_offset(n, bs, T - 1)
+    k = 0
+    while k < T and torch.equal(pinned[M.mdet_host_layout_offset(n, bs, k):M.mdet_host_layout_offset(n, bs, k + 1)],
+                                plain[M.mdet_host_layout_offset(n, bs, k):M.mdet_host_layout_offset(n, bs, k + 1)]):
+        k += 1
+    assert k == T and last_group_start > 0
+    # in-core from ordinary memory
+    r3 = M.mdet_logdet_host(packed(M, a, bs, pin=False), n, bs)
+    assert not r3.out_of_core and r3.logabsdet == r1.logabsdet
+
+
 def test_matrix_in_a_file_through_a_memory_map(M, tmp_path):
     # the third tier of the paper (Sec. 2.2: the matrix lives on disk, a scratch file takes
     # the updated blocks): the host entry point takes any host pointer, so a shared memory
