@@ -233,8 +233,9 @@ int mdet_logdet_device(const mdet_params* params, void* dA, int64_t ld,
                        mdet_result* result, void* diag);
 
 /*
- * mdet_logdet_host: matrix in HOST memory (pinned memory gives full link speed;
- * pageable memory works but is slower), in the packed lower block-column layout:
+ * mdet_logdet_host: matrix in HOST memory (pinned or not: memory that is not pinned
+ * is moved through pinned chunks of the library's own, by a few threads that live for
+ * the length of the call), in the packed lower block-column layout:
  * with b = block_size rounded up to a multiple of 64 and n_b = ceil(n/b), block
  * column j (columns [j*b, min(n, (j+1)*b)), width w_j) stores rows [j*b, n)
  * row-major with leading dimension w_j, and block columns follow each other:
