@@ -252,7 +252,8 @@ int mdet_logdet_host(const mdet_params* params, void* hA, mdet_result* result,
                      void* diag);
 
 /* As mdet_logdet_host, but blocks are fetched through `provider` (e.g. from disk)
- * into library-owned pinned memory laid out as above.  overwrite is ignored. */
+ * into library-owned host memory laid out as above (pinned if that much can be pinned).
+ * overwrite is ignored. */
 int mdet_logdet_provider(const mdet_params* params, mdet_block_provider provider,
                          void* user, mdet_result* result, void* diag);
 

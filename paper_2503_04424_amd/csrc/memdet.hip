@@ -22,6 +22,7 @@
 #include <functional>
 #include <memory>
 #include <mutex>
+#include <new>
 #include <thread>
 #include <vector>
 
@@ -1230,15 +1231,19 @@ static int logdet_host_any(const mdet_params* p, void* hA, mdet_result* res, voi
   init_result(res, pl);
   if (rc != MDET_OK) return rc;
   PinnedBuf scratch;
+  std::unique_ptr<char[]> plain_scratch;
   void* hOut = hA;
   if (pl.out_of_core && !p->overwrite) {
     if (p->host_scratch) {
       if (p->host_scratch_bytes < pl.layout_bytes) return MDET_ENOMEM_HOST;
       hOut = p->host_scratch;
-    } else {
-      rc = scratch.alloc(pl.layout_bytes);
-      if (rc != MDET_OK) return rc;
+    } else if (scratch.alloc(pl.layout_bytes) == MDET_OK) {
       hOut = scratch.p;
+    } else {
+      // more than can be pinned: ordinary memory, which the host path stages itself
+      plain_scratch.reset(new (std::nothrow) char[pl.layout_bytes ? pl.layout_bytes : 1]);
+      if (!plain_scratch) return MDET_ENOMEM_HOST;
+      hOut = plain_scratch.get();
     }
   }
   auto t0 = std::chrono::steady_clock::now();
@@ -1442,13 +1447,20 @@ extern "C" int mdet_logdet_provider(const mdet_params* p, mdet_block_provider pr
   int rc = make_plan(*p, false, 0, pl);
   init_result(res, pl);
   if (rc != MDET_OK) return rc;
+  // pinned memory if it can be had (there are limits well below the size of host memory),
+  // ordinary memory otherwise: the host path moves that through pinned chunks
   PinnedBuf buf;
-  rc = buf.alloc(pl.layout_bytes);
-  if (rc != MDET_OK) return rc;
+  std::unique_ptr<char[]> plain;
+  if (buf.alloc(pl.layout_bytes) != MDET_OK) {
+    plain.reset(new (std::nothrow) char[pl.layout_bytes ? pl.layout_bytes : 1]);
+    if (!plain) return MDET_ENOMEM_HOST;
+    buf.p = nullptr;
+  }
+  void* const store = buf.p ? buf.p : (void*)plain.get();
   const int64_t bs = pl.bs;
   for (int64_t j = 0; j < pl.T; ++j) {
     const int64_t wj = pl.col_width(j);
-    char* col = (char*)buf.p + (uint64_t)pl.col_offset(j) * pl.beta;
+    char* col = (char*)store + (uint64_t)pl.col_offset(j) * pl.beta;
     for (int64_t i = j; i < pl.T; ++i) {
       const int64_t wi = pl.col_width(i);
       void* dst = col + (uint64_t)(i - j) * bs * wj * pl.beta;
@@ -1457,5 +1469,5 @@ extern "C" int mdet_logdet_provider(const mdet_params* p, mdet_block_provider pr
   }
   mdet_params q = *p;
   q.overwrite = 1;        // the staging buffer is ours
-  return logdet_host_any(&q, buf.p, res, diag);
+  return logdet_host_any(&q, store, res, diag);
 }
