@@ -49,7 +49,9 @@ typedef enum {
   MDET_ESINGULAR = 6,     /* exact zero pivot: sign = 0, logabsdet = -inf          */
   MDET_ENONFINITE = 7,    /* NaN/Inf pivot met (input not finite or overflow)      */
   MDET_EPROVIDER = 8,     /* the block provider returned non-zero                  */
-  MDET_ENOTPOSDEF = 9     /* MDET_FLAG_ASSUME_SPD and a negative pivot was met      */
+  MDET_ENOTPOSDEF = 9,    /* MDET_FLAG_ASSUME_SPD and a negative pivot was met      */
+  MDET_EIO = 10           /* mdet_logdet_file: open, read or write failed, or the
+                             file is shorter than the matrix                        */
 } mdet_status;
 
 /* Parameters of one log-determinant call.  Zero-initialise, then set fields. */
@@ -256,6 +258,23 @@ int mdet_logdet_host(const mdet_params* params, void* hA, mdet_result* result,
  * overwrite is ignored. */
 int mdet_logdet_provider(const mdet_params* params, mdet_block_provider provider,
                          void* user, mdet_result* result, void* diag);
+
+/* As mdet_logdet_host, with the matrix in a FILE (the paper's third tier, Sec. 2.2: the
+ * matrix lives on disk, blocks are loaded as needed, a scratchpad on disk takes the
+ * updated blocks; the software appendix: scratch_dir, parallel_io): `matrix_path` holds
+ * the packed lower block-column layout, elements of params->dtype, from byte 0.  Blocks
+ * are read (and, when the run streams, factored block columns written and read again)
+ * with pread/pwrite by a few threads at a time, through pinned chunks; host memory use
+ * does not grow with the matrix.
+ *   overwrite = 1  the factored block columns go back into matrix_path (when the whole
+ *                  matrix fits the budget nothing is written at all);
+ *   overwrite = 0  matrix_path is opened read-only and, if the run streams, the factored
+ *                  block columns go to `scratch_path`, which is created or overwritten
+ *                  (MDET_EINVAL if it is NULL then); host_scratch is ignored.
+ *   diag, params->perm  HOST pointers as for mdet_logdet_host.
+ * MDET_EIO if a file cannot be opened, is too short, or a read or write fails. */
+int mdet_logdet_file(const mdet_params* params, const char* matrix_path,
+                     const char* scratch_path, mdet_result* result, void* diag);
 
 /* Element offset of block column j in the packed host layout; total elements for
  * j = n_b.  b must already be a multiple of 64.  Returns -1 on bad arguments. */

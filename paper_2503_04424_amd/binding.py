@@ -25,7 +25,7 @@ FLAG_PIVOT = 64
 
 
 class Status:
-    OK, EINVAL, EBUDGET, ENOMEM_DEVICE, ENOMEM_HOST, EHIP, ESINGULAR, ENONFINITE, EPROVIDER, ENOTPOSDEF = range(10)
+    OK, EINVAL, EBUDGET, ENOMEM_DEVICE, ENOMEM_HOST, EHIP, ESINGULAR, ENONFINITE, EPROVIDER, ENOTPOSDEF, EIO = range(11)
 
 
 class _Params(C.Structure):
@@ -69,7 +69,7 @@ PROVIDER_CB = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, 
 
 EXPORTS = [
     "mdet_plan", "mdet_workspace_query", "mdet_logdet_device", "mdet_logdet_host",
-    "mdet_logdet_provider", "mdet_host_layout_offset", "mdet_paper_block_rule",
+    "mdet_logdet_provider", "mdet_logdet_file", "mdet_host_layout_offset", "mdet_paper_block_rule",
     "mdet_paper_fma_count", "mdet_step_schur_update", "mdet_step_panel_factor",
     "mdet_step_panel_factor_pivoted",
     "mdet_step_logdet_reduce", "mdet_strerror", "mdet_version",
@@ -99,6 +99,7 @@ def load():
     L.mdet_logdet_device.argtypes = [C.POINTER(_Params), vp, i64, C.POINTER(_Result), vp]
     L.mdet_logdet_host.argtypes = [C.POINTER(_Params), vp, C.POINTER(_Result), vp]
     L.mdet_logdet_provider.argtypes = [C.POINTER(_Params), PROVIDER_CB, vp, C.POINTER(_Result), vp]
+    L.mdet_logdet_file.argtypes = [C.POINTER(_Params), C.c_char_p, C.c_char_p, C.POINTER(_Result), vp]
     L.mdet_host_layout_offset.argtypes = [i64, i64, i64]
     L.mdet_host_layout_offset.restype = i64
     L.mdet_paper_block_rule.argtypes = [i64, i32, u64, C.POINTER(i64), C.POINTER(i64)]
@@ -343,6 +344,25 @@ def mdet_logdet_provider(provider: Callable, n, dtype, block_size, mem_budget=0,
     r = _Result()
     st = load().mdet_logdet_provider(C.byref(p), cb, None, C.byref(r),
                                      C.c_void_p(diag.data_ptr()) if diag is not None else None)
+    if st not in _SOFT and raise_on_error:
+        raise MemdetError(st, r)
+    return _result(st, r)
+
+
+def mdet_logdet_file(matrix_path, n, dtype, block_size, mem_budget=0, overwrite=True, flags=0, diag=None,
+                     scratch_path=None, stream=None, workspace=None, raise_on_error=True,
+                     perm=None) -> LogdetResult:
+    """The matrix in a file holding the packed lower block-column layout (see mdet_logdet_host)."""
+    p = _params(n, dtype, block_size, mem_budget, overwrite, flags, _stream_handle(stream),
+                workspace.data_ptr() if workspace is not None else None,
+                workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                perm=_perm_ptr(perm, n, False))
+    if diag is not None and (diag.numel() < n or diag.is_cuda):
+        raise ValueError("diag must be a host tensor of n elements of the matrix dtype")
+    r = _Result()
+    st = load().mdet_logdet_file(C.byref(p), os.fsencode(matrix_path),
+                                 os.fsencode(scratch_path) if scratch_path is not None else None,
+                                 C.byref(r), C.c_void_p(diag.data_ptr()) if diag is not None else None)
     if st not in _SOFT and raise_on_error:
         raise MemdetError(st, r)
     return _result(st, r)

@@ -13,6 +13,10 @@
 // resident a group at a time while factored columns stream past from host memory.
 #include <hip/hip_runtime.h>
 
+#include <fcntl.h>
+#include <sys/stat.h>
+#include <unistd.h>
+
 #include <chrono>
 #include <cmath>
 #include <cstdio>
@@ -762,7 +766,9 @@ struct CopyProfile {
 // emptied by several threads at once, one chunk's transfer under way while the next is
 // copied.  The calling thread is held for the length of the copy either way.
 
-// A few threads that split one memcpy between them (and the caller).
+// A few threads that split one transfer between them (and the caller): a memcpy, or a
+// read or write of a file at a given offset (pread and pwrite take their own offsets, so
+// the parts do not disturb each other).  A short read or a failed call sets `failed`.
 class CopyThreads {
  public:
   explicit CopyThreads(int n) {
@@ -776,14 +782,31 @@ class CopyThreads {
     cv_.notify_all();
     for (auto& t : workers_) t.join();
   }
-  void copy(void* dst, const void* src, size_t bytes) {
-    constexpr size_t PART = 4u << 20;
-    if (bytes < 2 * PART || workers_.empty()) { std::memcpy(dst, src, bytes); return; }
+  void copy(void* dst, const void* src, size_t bytes) { run_job(0, (char*)dst, (const char*)src, -1, 0, bytes); }
+  void read_file(void* dst, int fd, uint64_t off, size_t bytes) { run_job(1, (char*)dst, nullptr, fd, off, bytes); }
+  void write_file(int fd, uint64_t off, const void* src, size_t bytes) {
+    run_job(2, nullptr, (const char*)src, fd, off, bytes);
+  }
+  std::atomic<bool> failed{false};
+
+ private:
+  static constexpr size_t PART = 4u << 20;
+  struct Job {
+    int op;                 // 0 memcpy, 1 file -> memory, 2 memory -> file
+    char* dst;
+    const char* src;
+    int fd;
+    uint64_t off;
+    size_t bytes, parts;
+    std::atomic<size_t> next{0}, done{0};
+  };
+  void run_job(int op, char* dst, const char* src, int fd, uint64_t off, size_t bytes) {
+    if (bytes == 0) return;
     auto job = std::make_shared<Job>();
-    job->dst = (char*)dst;
-    job->src = (const char*)src;
+    job->op = op; job->dst = dst; job->src = src; job->fd = fd; job->off = off;
     job->bytes = bytes;
     job->parts = (bytes + PART - 1) / PART;
+    if (job->parts < 2 || workers_.empty()) { run(*job); return; }
     {
       std::lock_guard<std::mutex> lk(m_);
       job_ = job;
@@ -795,21 +818,22 @@ class CopyThreads {
     done_cv_.wait(lk, [&] { return job->done.load() == job->parts; });
     job_.reset();
   }
-
- private:
-  struct Job {
-    char* dst;
-    const char* src;
-    size_t bytes, parts;
-    std::atomic<size_t> next{0}, done{0};
-  };
+  void one_part(const Job& j, size_t off, size_t len) {
+    if (j.op == 0) { std::memcpy(j.dst + off, j.src + off, len); return; }
+    size_t got = 0;
+    while (got < len) {
+      const ssize_t r = j.op == 1 ? ::pread(j.fd, j.dst + off + got, len - got, (off_t)(j.off + off + got))
+                                  : ::pwrite(j.fd, j.src + off + got, len - got, (off_t)(j.off + off + got));
+      if (r <= 0) { failed = true; return; }       // error, or the file ends early
+      got += (size_t)r;
+    }
+  }
   void run(Job& j) {
-    constexpr size_t PART = 4u << 20;
     for (;;) {
       const size_t p = j.next.fetch_add(1);
       if (p >= j.parts) return;
       const size_t off = p * PART, len = j.bytes - off < PART ? j.bytes - off : PART;
-      std::memcpy(j.dst + off, j.src + off, len);
+      one_part(j, off, len);
       if (j.done.fetch_add(1) + 1 == j.parts) {
         std::lock_guard<std::mutex> lk(m_);
         done_cv_.notify_all();
@@ -838,64 +862,99 @@ class CopyThreads {
   bool stop_ = false;
 };
 
-// Pinned chunks between pageable host memory and the device.  One per call; the chunks
-// are allocated when the first large copy needs them.
+// Pinned chunks between the device and either pageable host memory or a file.  One per
+// store and call; the chunks are allocated when the first copy needs them.  With a file
+// (fd >= 0) the host "pointers" handed to it are byte offsets into that file, and every
+// copy goes through the chunks; with memory, small copies are left to the runtime.
 class HostStager {
  public:
   static constexpr size_t CHUNK = 32u << 20;
   static constexpr int NCHUNK = 4;
-  static constexpr size_t DIRECT_BELOW = 1u << 20;   // small copies: leave them to the runtime
-  explicit HostStager(HipFail* f) : fail_(f) {}
+  static constexpr size_t DIRECT_BELOW = 1u << 20;
+  HostStager(HipFail* f, int fd) : fail_(f), fd_(fd) {}
   ~HostStager() {
     for (int c = 0; c < NCHUNK; ++c) {
       if (ev_[c]) { (void)hipEventSynchronize(ev_[c]); (void)hipEventDestroy(ev_[c]); }
       if (buf_[c]) (void)hipHostFree(buf_[c]);
     }
   }
+  bool is_file() const { return fd_ >= 0; }
+  // a read or write of the file failed or came up short, or the chunks could not be had
+  bool io_failed() const { return broken_ || (threads_ && threads_->failed.load()); }
   // true if p is ordinary (pageable) host memory
   static bool pageable(const void* p) {
     hipPointerAttribute_t a;
     if (hipPointerGetAttributes(&a, p) != hipSuccess) { (void)hipGetLastError(); return true; }
     return a.type == hipMemoryTypeUnregistered;
   }
-  void to_device(void* dst, const void* src, size_t bytes, hipStream_t st) {
-    if (bytes < DIRECT_BELOW || !ready()) {
-      fail_->check(hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, st));
+  // rows x row_bytes, packed on the host side, pitch_bytes apart on the device
+  void to_device(void* dst, size_t pitch_bytes, const void* src, size_t row_bytes, size_t rows,
+                 hipStream_t st) {
+    const bool flat = pitch_bytes == row_bytes;
+    const size_t bytes = row_bytes * rows;
+    if (bytes == 0) return;
+    if (!is_file() && (bytes < DIRECT_BELOW || !ready())) {
+      fail_->check(flat ? hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, st)
+                        : hipMemcpy2DAsync(dst, pitch_bytes, src, row_bytes, row_bytes, rows,
+                                           hipMemcpyHostToDevice, st));
       return;
     }
-    for (size_t off = 0; off < bytes; off += CHUNK) {
-      const size_t len = bytes - off < CHUNK ? bytes - off : CHUNK;
+    if (!ready()) { broken_ = true; return; }
+    const size_t rows_per = flat ? rows : (CHUNK / row_bytes ? CHUNK / row_bytes : 1);
+    const size_t step = flat ? CHUNK : rows_per * row_bytes;
+    if (step > CHUNK) { broken_ = true; return; }
+    for (size_t off = 0; off < bytes; off += step) {
+      const size_t len = bytes - off < step ? bytes - off : step;
       const int c = take();
-      threads_->copy(buf_[c], (const char*)src + off, len);
-      fail_->check(hipMemcpyAsync((char*)dst + off, buf_[c], len, hipMemcpyHostToDevice, st));
+      if (is_file()) threads_->read_file(buf_[c], fd_, (uint64_t)(uintptr_t)src + off, len);
+      else threads_->copy(buf_[c], (const char*)src + off, len);
+      if (flat)
+        fail_->check(hipMemcpyAsync((char*)dst + off, buf_[c], len, hipMemcpyHostToDevice, st));
+      else
+        fail_->check(hipMemcpy2DAsync((char*)dst + (off / row_bytes) * pitch_bytes, pitch_bytes, buf_[c],
+                                      row_bytes, row_bytes, len / row_bytes, hipMemcpyHostToDevice, st));
       fail_->check(hipEventRecord(ev_[c], st));
       busy_[c] = true;
     }
   }
-  void to_host(void* dst, const void* src, size_t bytes, hipStream_t st) {
-    if (bytes < DIRECT_BELOW || !ready()) {
-      fail_->check(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, st));
+  void to_host(void* dst, const void* src, size_t pitch_bytes, size_t row_bytes, size_t rows,
+               hipStream_t st) {
+    const bool flat = pitch_bytes == row_bytes;
+    const size_t bytes = row_bytes * rows;
+    if (bytes == 0) return;
+    if (!is_file() && (bytes < DIRECT_BELOW || !ready())) {
+      fail_->check(flat ? hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, st)
+                        : hipMemcpy2DAsync(dst, row_bytes, src, pitch_bytes, row_bytes, rows,
+                                           hipMemcpyDeviceToHost, st));
       return;
     }
+    if (!ready()) { broken_ = true; return; }
+    const size_t rows_per = flat ? rows : (CHUNK / row_bytes ? CHUNK / row_bytes : 1);
+    const size_t step = flat ? CHUNK : rows_per * row_bytes;
+    if (step > CHUNK) { broken_ = true; return; }
     int prev = -1;
-    char* prev_dst = nullptr;
-    size_t prev_len = 0;
+    size_t prev_off = 0, prev_len = 0;
     auto drain = [&] {
       if (prev < 0) return;
       fail_->check(hipEventSynchronize(ev_[prev]));
-      threads_->copy(prev_dst, buf_[prev], prev_len);
+      if (is_file()) threads_->write_file(fd_, (uint64_t)(uintptr_t)dst + prev_off, buf_[prev], prev_len);
+      else threads_->copy((char*)dst + prev_off, buf_[prev], prev_len);
       busy_[prev] = false;
       prev = -1;
     };
-    for (size_t off = 0; off < bytes; off += CHUNK) {
-      const size_t len = bytes - off < CHUNK ? bytes - off : CHUNK;
+    for (size_t off = 0; off < bytes; off += step) {
+      const size_t len = bytes - off < step ? bytes - off : step;
       const int c = take(prev);
-      fail_->check(hipMemcpyAsync(buf_[c], (const char*)src + off, len, hipMemcpyDeviceToHost, st));
+      if (flat)
+        fail_->check(hipMemcpyAsync(buf_[c], (const char*)src + off, len, hipMemcpyDeviceToHost, st));
+      else
+        fail_->check(hipMemcpy2DAsync(buf_[c], row_bytes, (const char*)src + (off / row_bytes) * pitch_bytes,
+                                      pitch_bytes, row_bytes, len / row_bytes, hipMemcpyDeviceToHost, st));
       fail_->check(hipEventRecord(ev_[c], st));
       busy_[c] = true;
       drain();                 // the chunk before this one, while this one is on its way
       prev = c;
-      prev_dst = (char*)dst + off;
+      prev_off = off;
       prev_len = len;
     }
     drain();
@@ -924,11 +983,13 @@ class HostStager {
     return c;
   }
   HipFail* fail_;
+  int fd_;
+  bool broken_ = false;
   void* buf_[NCHUNK] = {nullptr, nullptr, nullptr, nullptr};
   hipEvent_t ev_[NCHUNK] = {nullptr, nullptr, nullptr, nullptr};
   bool busy_[NCHUNK] = {false, false, false, false};
   int next_ = 0;
-  int state_ = 0;   // 0 not tried, 1 ready, -1 unavailable (copies then go the plain way)
+  int state_ = 0;   // 0 not tried, 1 ready, -1 unavailable
   std::unique_ptr<CopyThreads> threads_;
 };
 
@@ -942,9 +1003,9 @@ static void copy_col_rows(HipFail& fail, const Plan& pl, int64_t j, int64_t r0, 
   T* d = dev_col + (r0 - j * pl.bs) * ldd;
   T* h = host_col + (r0 - j * pl.bs) * w;
   const size_t nbytes = (size_t)(r1 - r0) * w * sizeof(T);
-  if (ldd == w && stager) {
-    if (to_device) stager->to_device(d, h, nbytes, st);
-    else stager->to_host(h, d, nbytes, st);
+  if (stager) {
+    if (to_device) stager->to_device(d, ldd * sizeof(T), h, w * sizeof(T), (size_t)(r1 - r0), st);
+    else stager->to_host(h, d, ldd * sizeof(T), w * sizeof(T), (size_t)(r1 - r0), st);
   } else if (ldd == w) {
     fail.check(to_device ? hipMemcpyAsync(d, h, nbytes, hipMemcpyHostToDevice, st)
                          : hipMemcpyAsync(h, d, nbytes, hipMemcpyDeviceToHost, st));
@@ -957,9 +1018,11 @@ static void copy_col_rows(HipFail& fail, const Plan& pl, int64_t j, int64_t r0, 
   *bytes += nbytes;
 }
 
+// fd_in / fd_out >= 0: the store is a file and hA / hOut the byte offset of the layout in it
+// (as a pointer), see mdet_logdet_file.
 template <typename T>
 static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut, mdet_result* res,
-                         T* diag_host) {
+                         T* diag_host, int fd_in = -1, int fd_out = -1) {
   HipFail fail;
   int dev = 0;
   MDET_HIP(fail, hipGetDevice(&dev));
@@ -1001,9 +1064,9 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
   cprof.fail = &fail;
   auto host_col = [&](T* base, int64_t j) { return base + pl.col_offset(j); };
   // pageable host memory goes through pinned chunks (see HostStager)
-  HostStager stager(&fail);
-  HostStager* stage_in = (n > 0 && HostStager::pageable(hA)) ? &stager : nullptr;
-  HostStager* stage_out = (n > 0 && HostStager::pageable(hOut)) ? &stager : nullptr;
+  HostStager stager_in(&fail, fd_in), stager_out(&fail, fd_out);
+  HostStager* stage_in = (fd_in >= 0 || (n > 0 && HostStager::pageable(hA))) ? &stager_in : nullptr;
+  HostStager* stage_out = (fd_out >= 0 || (n > 0 && HostStager::pageable(hOut))) ? &stager_out : nullptr;
 
   if (!pl.out_of_core) {
     // ---- everything resident: upload column by column, factor as columns arrive
@@ -1118,7 +1181,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
           {
             const size_t nbytes = (size_t)(rows_end_J - j0 * bs) * bs * sizeof(T);
             CopyProfile::Scope timed(&cprof, 0, sh);
-            if (stage_out) stage_out->to_device(bpool[q], hk + (j0 - k) * bs * bs, nbytes, sh);
+            if (stage_out) stage_out->to_device(bpool[q], nbytes, hk + (j0 - k) * bs * bs, nbytes, 1, sh);
             else MDET_HIP(fail, hipMemcpyAsync(bpool[q], hk + (j0 - k) * bs * bs, nbytes, hipMemcpyHostToDevice, sh));
             h2d_bytes += nbytes;
           }
@@ -1142,7 +1205,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
             const size_t nbytes = (size_t)wi * bs * sizeof(T);
             {
               CopyProfile::Scope timed(&cprof, 0, sh);
-              if (stage_out) stage_out->to_device(ring[sl], hk + (i - k) * bs * bs, nbytes, sh);
+              if (stage_out) stage_out->to_device(ring[sl], nbytes, hk + (i - k) * bs * bs, nbytes, 1, sh);
               else MDET_HIP(fail, hipMemcpyAsync(ring[sl], hk + (i - k) * bs * bs, nbytes, hipMemcpyHostToDevice, sh));
             }
             h2d_bytes += nbytes;
@@ -1209,6 +1272,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
   res->bytes_d2h = d2h_bytes;
   res->t_h2d = cprof.collect(0);
   res->t_d2h = cprof.collect(1);
+  if (stager_in.io_failed() || stager_out.io_failed()) return MDET_EIO;
   if (!fail.ok()) { res->hip_error = fail.code; return MDET_EHIP; }
   if (rc != MDET_OK) return rc;
   return finish_result(o, res);
@@ -1253,6 +1317,41 @@ static int logdet_host_any(const mdet_params* p, void* hA, mdet_result* res, voi
   return rc;
 }
 
+// The matrix in a file (packed layout at the start of it), optionally a second file for
+// the factors.
+static int logdet_file_any(const mdet_params* p, const char* matrix_path, const char* scratch_path,
+                           mdet_result* res, void* diag) {
+  Plan pl;
+  int rc = make_plan(*p, false, 0, pl);
+  init_result(res, pl);
+  if (rc != MDET_OK) return rc;
+  struct Fd {
+    int fd = -1;
+    ~Fd() { if (fd >= 0) ::close(fd); }
+  } in, out;
+  const bool writes = pl.out_of_core;              // factored columns are stored only when they stream
+  const bool in_place = writes && p->overwrite;
+  in.fd = ::open(matrix_path, in_place ? O_RDWR : O_RDONLY);
+  if (in.fd < 0) return MDET_EIO;
+  struct stat sb;
+  if (::fstat(in.fd, &sb) != 0 || (uint64_t)sb.st_size < pl.layout_bytes) return MDET_EIO;
+  int fd_out = in.fd;
+  if (writes && !p->overwrite) {
+    if (!scratch_path) return MDET_EINVAL;
+    out.fd = ::open(scratch_path, O_RDWR | O_CREAT, 0600);
+    if (out.fd < 0) return MDET_EIO;
+    if (::ftruncate(out.fd, (off_t)pl.layout_bytes) != 0) return MDET_EIO;
+    fd_out = out.fd;
+  }
+  auto t0 = std::chrono::steady_clock::now();
+  if (p->dtype == MDET_F64)
+    rc = logdet_host_t<double>(*p, pl, (double*)nullptr, (double*)nullptr, res, (double*)diag, in.fd, fd_out);
+  else
+    rc = logdet_host_t<float>(*p, pl, (float*)nullptr, (float*)nullptr, res, (float*)diag, in.fd, fd_out);
+  res->t_total = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+  return rc;
+}
+
 }  // namespace mdet
 
 // ===========================================================================
@@ -1279,6 +1378,7 @@ const char* mdet_strerror(int s) {
     case MDET_ENONFINITE: return "non-finite pivot";
     case MDET_EPROVIDER: return "block provider failed";
     case MDET_ENOTPOSDEF: return "matrix is not positive definite: a pivot is negative";
+    case MDET_EIO: return "file could not be opened, is too short, or a read or write failed";
     default: return "unknown status";
   }
 }
@@ -1438,6 +1538,12 @@ extern "C" int mdet_logdet_host(const mdet_params* p, void* hA, mdet_result* res
   if (!params_ok(p) || !res) return MDET_EINVAL;
   if (p->n > 0 && !hA) return MDET_EINVAL;
   return logdet_host_any(p, hA, res, diag);
+}
+
+extern "C" int mdet_logdet_file(const mdet_params* p, const char* matrix_path, const char* scratch_path,
+                                mdet_result* res, void* diag) {
+  if (!params_ok(p) || !res || !matrix_path) return MDET_EINVAL;
+  return logdet_file_any(p, matrix_path, scratch_path, res, diag);
 }
 
 extern "C" int mdet_logdet_provider(const mdet_params* p, mdet_block_provider provider, void* user,

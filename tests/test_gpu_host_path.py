@@ -198,6 +198,76 @@ def test_matrix_in_a_file_through_a_memory_map(M, tmp_path):
                   / np.abs(first_diag)) <= 1e-9
 
 
+@pytest.mark.parametrize("n,bs,dtype", [(2304, 256, "f64"), (1001, 128, "f64"), (1500, 192, "f32")])
+def test_matrix_in_a_file_with_explicit_reads_and_writes(M, tmp_path, n, bs, dtype):
+    # mdet_logdet_file: the same tier with pread/pwrite through pinned chunks instead of a
+    # memory map; every byte that reaches the device or the file is the one the host-memory
+    # path moves, so results and files agree with it to the last bit
+    w = W.scaled_down(W.config(4, dtype), n, bs)
+    npdt = np.float64 if dtype == "f64" else np.float32
+    a = w.dense().astype(npdt)
+    src = packed(M, a, bs, pin=False)
+    path, scratch_path = str(tmp_path / "matrix.bin"), str(tmp_path / "scratch.bin")
+    src.numpy().tofile(path)
+    lo = min_budget(M, n, dtype, bs)
+    in_memory = src.clone()
+    tdt = torch.float64 if dtype == "f64" else torch.float32
+    d_ref = torch.empty(n, dtype=tdt)
+    ref = M.mdet_logdet_host(in_memory, n, bs, mem_budget=lo, flags=M.FLAG_FORCE_OUT_OF_CORE, diag=d_ref)
+    assert ref.out_of_core and ref.num_superpanels > 1
+    # (a) streamed, factors to a scratch file, the matrix file untouched
+    d = torch.empty(n, dtype=tdt)
+    res = M.mdet_logdet_file(path, n, dtype, bs, mem_budget=lo, overwrite=False, scratch_path=scratch_path,
+                             flags=M.FLAG_FORCE_OUT_OF_CORE, diag=d)
+    assert res.out_of_core and res.dev_bytes_high_water <= lo
+    assert res.logabsdet == ref.logabsdet and res.sign == ref.sign and torch.equal(d, d_ref)
+    assert res.bytes_h2d == ref.bytes_h2d and res.bytes_d2h == ref.bytes_d2h
+    assert np.array_equal(np.fromfile(path, dtype=npdt), src.numpy())
+    # (b) in place: the file ends up with what the host-memory run left in its array
+    res = M.mdet_logdet_file(path, n, dtype, bs, mem_budget=lo, flags=M.FLAG_FORCE_OUT_OF_CORE)
+    assert res.logabsdet == ref.logabsdet
+    assert np.array_equal(np.fromfile(path, dtype=npdt), in_memory.numpy())
+    # (c) everything resident: nothing is written
+    src.numpy().tofile(path)
+    res = M.mdet_logdet_file(path, n, dtype, bs)
+    whole = M.mdet_logdet_host(src.clone(), n, bs)
+    assert not res.out_of_core and res.logabsdet == whole.logabsdet and res.bytes_d2h == 0
+    assert np.array_equal(np.fromfile(path, dtype=npdt), src.numpy())
+
+
+def test_file_entry_point_with_pivoting_and_errors(M, tmp_path):
+    n, bs = 1100, 192
+    rng = np.random.default_rng(17)
+    g = rng.standard_normal((n, n))
+    a = (g + g.T) / math.sqrt(n) + np.diag(rng.uniform(4, 8, n) * rng.choice([-1.0, 1.0], n))
+    a[0, 0] = 0.0
+    src = packed(M, a, bs, pin=False)
+    path = str(tmp_path / "m.bin")
+    src.numpy().tofile(path)
+    lo = min_budget(M, n, "f64", bs)
+    perm = torch.full((n,), -1, dtype=torch.int32)
+    perm_ref = torch.full((n,), -1, dtype=torch.int32)
+    flags = M.FLAG_FORCE_OUT_OF_CORE | M.FLAG_PIVOT
+    ref = M.mdet_logdet_host(src.clone(), n, bs, mem_budget=lo + (1 << 16), flags=flags, perm=perm_ref)
+    res = M.mdet_logdet_file(path, n, "f64", bs, mem_budget=lo + (1 << 16), flags=flags, perm=perm)
+    o = oracle.ldlt_pivoted(a)
+    assert res.logabsdet == ref.logabsdet and torch.equal(perm, perm_ref)
+    assert res.sign == o.sign and rel(res.logabsdet, o.logabsdet) <= TOL["f64"]
+    S = M.Status
+    with pytest.raises(M.MemdetError) as e:
+        M.mdet_logdet_file(str(tmp_path / "missing.bin"), n, "f64", bs)
+    assert e.value.status == S.EIO
+    short = str(tmp_path / "short.bin")
+    src.numpy()[:1000].tofile(short)
+    with pytest.raises(M.MemdetError) as e:
+        M.mdet_logdet_file(short, n, "f64", bs)
+    assert e.value.status == S.EIO
+    with pytest.raises(M.MemdetError) as e:       # streams, may not overwrite, and has nowhere to write
+        M.mdet_logdet_file(path, n, "f64", bs, mem_budget=lo, overwrite=False, flags=M.FLAG_FORCE_OUT_OF_CORE)
+    assert e.value.status == S.EINVAL
+    assert "file" in M.mdet_strerror(S.EIO)
+
+
 def test_budget_below_minimum_working_set(M):
     n, bs = 1024, 128
     lo = min_budget(M, n, "f64", bs)
