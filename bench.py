@@ -210,6 +210,9 @@ def main():
                     help="in-core: MDET_FLAG_SCALED_COPY (2 n block_size elements more workspace)")
     ap.add_argument("--assume-spd", action="store_true",
                     help="the positive-definite (Cholesky) form of the method instead of LDL^T")
+    ap.add_argument("--file-dir", default="",
+                    help="out-of-core configurations: write the matrix to a file in this directory "
+                         "and run mdet_logdet_file on it (factors go to a scratch file beside it)")
     ap.add_argument("--pivot", action="store_true",
                     help="MDET_FLAG_PIVOT: pivoting on the diagonal inside each group of 64 columns")
     ap.add_argument("--kernels", action="store_true",
@@ -324,12 +327,27 @@ def main():
                 form_matrix_host_packed(w, torch, M, out=h)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            r = M.mdet_logdet_host(h, n, bs, mem_budget=w.mem_budget, overwrite=True,
-                                   flags=M.FLAG_PROFILE | xflags, diag=diag)
+            if args.file_dir:
+                if i == 0:
+                    os.makedirs(args.file_dir, exist_ok=True)
+                    mpath = os.path.join(args.file_dir, "memdet_matrix.bin")
+                    spath = os.path.join(args.file_dir, "memdet_scratch.bin")
+                    h.numpy().tofile(mpath)          # untimed; the run leaves this file as it is
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                r = M.mdet_logdet_file(mpath, n, w.dtype, bs, mem_budget=w.mem_budget, overwrite=False,
+                                       scratch_path=spath, flags=M.FLAG_PROFILE | xflags, diag=diag)
+            else:
+                r = M.mdet_logdet_host(h, n, bs, mem_budget=w.mem_budget, overwrite=True,
+                                       flags=M.FLAG_PROFILE | xflags, diag=diag)
             torch.cuda.synchronize()
             if i >= warmup:
                 t_total += time.perf_counter() - t0
                 results.append(r)
+        if args.file_dir:
+            for f in (mpath, spath):
+                if os.path.exists(f):
+                    os.remove(f)
         final = results[-1]
         diag_host = diag.numpy().astype(np.float64)
 
@@ -347,7 +365,8 @@ def main():
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f64" if widen else w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "n": n, "block_size": bs,
-                   "placement": (("pinned" if pinned else "pageable") + " host memory, streamed")
+                   "placement": ("file (pread/pwrite through pinned chunks), streamed" if args.file_dir else
+                                 ("pinned" if pinned else "pageable") + " host memory, streamed")
                    if out_of_core else "HBM, in-core",
                    "mem_budget_bytes": w.mem_budget, "seed": w.seed,
                    **({"storage": "f32, widened exactly; arithmetic f64"} if widen else {}),
