@@ -487,7 +487,14 @@ static int factor_resident(Launcher<T>& L, const Plan& pl, std::vector<ColRef<T>
     }
     if (k + 2 < je) {
       if (lookahead) L.fail->check(hipStreamWaitEvent(s1, ev_panel, 0));
-      if (dense) {
+      // One launch for all remaining columns, or one per block column: where a block
+      // column alone fills the device many times over (here: 16 times), its launch
+      // re-uses one set of B rows throughout and the ends of the launches cost little
+      // (n = 131072, b = 4096: 11.18 -> 10.92 s); smaller ones lose more at their ends
+      // than they gain (n = 32768, b = 2048: 190.8 -> 196.0 ms).
+      const int64_t col_blocks = ((n - (k + 2) * bs + 127) / 128) * ((bs + 127) / 128);
+      const bool one_launch = dense && (L.slots <= 0 || col_blocks < 16 * (int64_t)L.slots);
+      if (one_launch) {
         const int64_t j = k + 2;
         const T* B = cols[k].base + (j - k) * bs * cols[k].ld;
         // all remaining resident columns in one launch (they are contiguous in memory)
