@@ -87,7 +87,10 @@ def test_config4_streamed_equals_in_core_and_oracle_on_leading_block(env):
     o = oracle.ldlt_logdet(lead)
     part = float(np.sum(np.log(np.abs(diag[:4096].numpy()))))
     assert rel(part, o.logabsdet) <= 1e-10
+    del f, lead, diag
+    torch.cuda.empty_cache()
     a = bench.form_matrix_device(w, torch)
+    torch.cuda.synchronize()
     r_in = M.mdet_logdet_device(a, block_size=w.block_size, overwrite=True)
     print(f"\ncfg4: streamed logdet={r_ooc.logabsdet:.12f} ({r_ooc.t_total:.2f}s, {r_ooc.num_superpanels} groups, "
           f"h2d {r_ooc.bytes_h2d/1e9:.1f} GB)  in-core logdet={r_in.logabsdet:.12f} ({r_in.t_total:.2f}s)  "
