@@ -379,3 +379,36 @@ def test_sixteen_bit_storage_with_fp64_arithmetic(M, store, n, bs):
         M.mdet_logdet_device(dstored, block_size=bs)
     assert e.value.status == M.Status.EINVAL
 
+
+def test_concurrent_calls_from_two_threads(M):
+    # the header allows concurrent calls with distinct workspaces: two threads, each with
+    # its own matrix (device path) or host array (host path, streamed), several calls each;
+    # every result must be the bits of the same call made alone
+    import threading
+    mats = [W.scaled_down(W.config(c), 1200 + 64 * c, 128).dense() for c in (1, 2, 3, 4)]
+    alone = [M.mdet_logdet_device(dev(a), block_size=128).logabsdet for a in mats]
+    packs = [M.pack_lower_block_columns(torch.from_numpy(a), 128, pin=True) for a in mats]
+    budget = 4 * 1500 * 128 * 8
+    out, errs = {}, []
+
+    def work(tid):
+        try:
+            torch.cuda.set_device(0)
+            for rep in range(3):
+                for i in range(tid, len(mats), 2):
+                    r1 = M.mdet_logdet_device(dev(mats[i]), block_size=128)
+                    r2 = M.mdet_logdet_host(packs[i].clone(), mats[i].shape[0], 128, mem_budget=budget,
+                                            flags=M.FLAG_FORCE_OUT_OF_CORE)
+                    out[(tid, rep, i)] = (r1.logabsdet, r2.logabsdet, r1.status, r2.status)
+        except Exception as e:           # surfaced below
+            errs.append(e)
+
+    ts = [threading.Thread(target=work, args=(t,)) for t in (0, 1)]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    assert not errs and len(out) == 12
+    for (tid, rep, i), (l1, l2, s1, s2) in out.items():
+        assert s1 == 0 and s2 == 0 and l1 == alone[i] and l2 == alone[i]
+
