@@ -190,13 +190,13 @@ struct Launcher {
     const bool leaf_k = !trailing && K == 64;
     const int64_t wg128 = 8 * update_grid(M, N, lower, 128).per;
     const bool small = !trailing && !leaf_k && wg128 < 1024;
-    // A one-launch trailing update whose 128 x 128 blocks would not fill the device's
-    // slots (the next block column of a small matrix, or near the end of a large one)
+    // A trailing update whose 128 x 128 blocks would not fill the device's slots (the
+    // next block column of a small matrix, the bulk of the last few block columns)
     // lasts as long as one workgroup's walk along K, twice that where two workgroups
     // share a compute unit; 64 x 64 blocks quarter the walk and spread evenly
     // (n = 8192: the seven next-column updates 1.48 -> 1.20 ms; measured cross-over at
     // about 0.8 of the slots).
-    const bool small_trailing = trailing && leave_free < 0 && slots > 0 && 5 * wg128 <= 4 * slots;
+    const bool small_trailing = trailing && slots > 0 && 5 * wg128 <= 4 * slots;
     const int tile = (leaf_k || small || small_trailing) ? 64 : 128;
     const UpdGrid ug = update_grid(M, N, lower, tile);
     if (8 * ug.per > INT32_MAX) return MDET_EINVAL;
@@ -208,7 +208,7 @@ struct Launcher {
     // workgroups per launch and XCD: everything at once, or rounds that fill all but
     // leave_free of the device's slots
     int64_t per_launch = ug.per;
-    if (trailing && leave_free >= 0 && slots - leave_free >= 8 && 8 * ug.per > slots - leave_free)
+    if (trailing && !small_trailing && leave_free >= 0 && slots - leave_free >= 8 && 8 * ug.per > slots - leave_free)
       per_launch = (slots - leave_free) / 8;
     dim3 block(UPD_THREADS);
     const bool timed = profile && trailing && !small_trailing;   // trailing_update_kernel proper
