@@ -236,6 +236,10 @@ def main():
     torch.cuda.set_device(0)
 
     w = W.config(args.config, args.dtype)
+    if args.dtype and w.dtype != args.dtype:
+        print(f"bench.py: configuration {args.config} is defined in {w.dtype} only "
+              "(configuration 3 has an f32 variant)", file=sys.stderr)
+        sys.exit(2)
     if args.n:
         w = W.scaled_down(w, args.n, args.block_size or None)
     if args.block_size:
