@@ -41,6 +41,12 @@ def _load():
             fn.argtypes = [ctypes.c_void_p, i64, i64, i64, ctypes.c_int, pd, ctypes.POINTER(ctypes.c_int),
                            ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.c_void_p, ctypes.c_void_p,
                            ctypes.c_void_p, ctypes.c_void_p]
+        for name in ("oracle_lu_f64", "oracle_lu_f32"):
+            fn = getattr(lib, name)
+            fn.restype = ctypes.c_int
+            fn.argtypes = [ctypes.c_void_p, i64, i64, i64, pd, ctypes.POINTER(ctypes.c_int),
+                           ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.c_void_p, ctypes.c_void_p,
+                           ctypes.c_void_p]
         lib.oracle_leibniz_f64.restype = ctypes.c_int
         lib.oracle_leibniz_f64.argtypes = [ctypes.c_void_p, ctypes.c_int, pd,
                                            ctypes.POINTER(ctypes.c_int), pd]
@@ -174,6 +180,46 @@ def ldlt_pivoted(a: np.ndarray, group: int = 64, choose: bool = True, want_L: bo
         raise MemoryError("oracle allocation failed or bad group size")
     return PivotedResult(lad.value, sg.value, st, bad.value, neg.value, perm, slack, d,
                          L if st == 0 else None)
+
+
+@dataclass
+class LUResult:
+    logabsdet: float
+    sign: int                 # sign of the permutation times the signs of the pivots
+    status: int               # 0 ok, 1 exact zero pivot
+    bad_pivot_index: int
+    negative_pivots: int
+    perm: np.ndarray          # a[perm, :] = L U
+    diag: np.ndarray          # pivots U_jj
+    LU: Optional[np.ndarray] = None   # L strictly below the diagonal (unit diagonal implied), U on and above
+
+
+def lu_logdet(a: np.ndarray, group: int = 64, want_LU: bool = False) -> LUResult:
+    """log|det A| and sign of a general square matrix (all entries are read) by Gaussian
+    elimination with the pivot of each column taken among the rows of its group of ``group``
+    consecutive indices (Sec. 2.2, Alg. 1: M = P L U; pivoting inside a block, none between
+    blocks), long double on the exact input bits."""
+    lib = _load()
+    if a.ndim != 2 or a.shape[0] != a.shape[1]:
+        raise ValueError("square matrix expected")
+    if a.dtype not in (np.float64, np.float32):
+        raise ValueError("float64 or float32 expected")
+    a = np.ascontiguousarray(a)
+    n = a.shape[0]
+    lda = a.strides[0] // a.itemsize if n > 0 else 1
+    fn = lib.oracle_lu_f64 if a.dtype == np.float64 else lib.oracle_lu_f32
+    lad = ctypes.c_double(0.0)
+    sg = ctypes.c_int(0)
+    bad = ctypes.c_int64(-1)
+    neg = ctypes.c_int64(0)
+    perm = np.empty(n, dtype=np.int64)
+    d = np.empty(n, dtype=np.float64)
+    LU = np.empty((n, n), dtype=np.float64) if want_LU else None
+    st = fn(a.ctypes.data, n, max(lda, 1), int(group), ctypes.byref(lad), ctypes.byref(sg), ctypes.byref(bad),
+            ctypes.byref(neg), perm.ctypes.data, d.ctypes.data, LU.ctypes.data if LU is not None else None)
+    if st == 2:
+        raise MemoryError("oracle allocation failed or bad group size")
+    return LUResult(lad.value, sg.value, st, bad.value, neg.value, perm, d, LU if st == 0 else None)
 
 
 def leibniz_logdet(a: np.ndarray):

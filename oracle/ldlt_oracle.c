@@ -46,6 +46,11 @@
  * current Schur complement among the indices of j's group of `group` consecutive
  * indices (on ties the one that came first in the input), brought to position j by
  * swapping rows and columns.  See ldlt_pivoted_core.
+ *
+ * And the generic case (Sec. 2.2, Eq. 1 and Alg. 1: M = P L U, the determinant is the
+ * product of the pivots times the sign of the permutation; pivoting inside a block, none
+ * between blocks): Gaussian elimination on the full matrix with the pivot of column j
+ * taken among the rows of j's group of `group` consecutive indices.  See lu_core.
  */
 #include <math.h>
 #include <stdint.h>
@@ -275,6 +280,98 @@ int oracle_ldlt_pivoted_f32(const float *a, int64_t n, int64_t lda, int64_t grou
                             int64_t *perm_out, double *slack_out, double *d_out, double *l_out) {
   return ldlt_pivoted_core(a, (size_t)n, (size_t)lda, get_f32, group < 1 ? 0 : (size_t)group, choose,
                            logabsdet, sign, bad, negative, perm_out, slack_out, d_out, l_out);
+}
+
+/*
+ * LU with partial (row) pivoting inside groups of `group` consecutive rows.
+ *
+ * Works on a full long-double copy S of the matrix (all n x n entries are read).  Step j,
+ * with hi = end of j's group:
+ *     p = argmax_{j <= r < hi} |S_rj|   (on ties the row that came first in the input);
+ *     swap rows j <-> p of S (the finished part of L with them); sign flips if p != j;
+ *     d_j = S_jj,  l_rj = S_rj / d_j,  S_rc -= l_rj S_jc   for r, c > j.
+ * perm_out[j] = original index of the row that ended at position j: A[perm, :] = L U with
+ * unit lower L and upper U, U_jj = d_j.  Outputs (any may be NULL): perm_out[n], d_out[n],
+ * lu_out[n*n] (row-major: L strictly below the diagonal, U on and above it).
+ * *sign = sign of the permutation times the signs of the pivots.  Returns 0, 1 on an exact
+ * zero pivot (every candidate of the column is zero; then *bad = j, sign 0, logabsdet
+ * -inf), 2 on allocation failure or group < 1.
+ */
+static xreal getfull_f64(const void *a, size_t i, size_t j, size_t lda) {
+  return (xreal)((const double *)a)[i * lda + j];
+}
+static xreal getfull_f32(const void *a, size_t i, size_t j, size_t lda) {
+  return (xreal)((const float *)a)[i * lda + j];
+}
+static int lu_core(const void *a, size_t n, size_t lda, getter get, size_t group, double *logabsdet,
+                   int *sign, int64_t *bad, int64_t *negative, int64_t *perm_out, double *d_out,
+                   double *lu_out) {
+  *logabsdet = 0.0;
+  *sign = 1;
+  if (bad) *bad = -1;
+  if (negative) *negative = 0;
+  if (group < 1) return 2;
+  if (n == 0) return 0;
+  xreal *S = (xreal *)malloc(n * n * sizeof(xreal));
+  size_t *perm = (size_t *)malloc(n * sizeof(size_t));
+  if (!S || !perm) { free(S); free(perm); return 2; }
+  for (size_t i = 0; i < n; ++i) {
+    perm[i] = i;
+    for (size_t k = 0; k < n; ++k) S[i * n + k] = get(a, i, k, lda);
+  }
+  int status = 0, sg = 1;
+  int64_t neg = 0;
+  xreal acc_log = 0.0L;
+  for (size_t j = 0; j < n; ++j) {
+    size_t hi = (j / group + 1) * group;
+    if (hi > n) hi = n;
+    size_t p = j;
+    for (size_t r = j + 1; r < hi; ++r) {
+      const xreal vr = fabsl(S[r * n + j]), vp = fabsl(S[p * n + j]);
+      if (vr > vp || (vr == vp && perm[r] < perm[p])) p = r;
+    }
+    if (p != j) {
+      for (size_t k = 0; k < n; ++k) { xreal t = S[j * n + k]; S[j * n + k] = S[p * n + k]; S[p * n + k] = t; }
+      size_t t = perm[j]; perm[j] = perm[p]; perm[p] = t;
+      sg = -sg;
+    }
+    const xreal d = S[j * n + j];
+    if (d == 0.0L) {
+      status = 1;
+      if (bad) *bad = (int64_t)j;
+      break;
+    }
+    if (d < 0.0L) { sg = -sg; ++neg; }
+    acc_log += logl(fabsl(d));
+    long i;
+#pragma omp parallel for schedule(static)
+    for (i = (long)j + 1; i < (long)n; ++i) {
+      const size_t r = (size_t)i;
+      const xreal l = S[r * n + j] / d;
+      for (size_t c = j + 1; c < n; ++c) S[r * n + c] -= l * S[j * n + c];
+      S[r * n + j] = l;
+    }
+  }
+  if (status == 0) { *logabsdet = (double)acc_log; *sign = sg; }
+  else { *logabsdet = -INFINITY; *sign = 0; }
+  if (negative) *negative = neg;
+  if (perm_out) for (size_t j = 0; j < n; ++j) perm_out[j] = (int64_t)perm[j];
+  if (d_out) for (size_t j = 0; j < n; ++j) d_out[j] = (double)S[j * n + j];
+  if (lu_out && status == 0) for (size_t e = 0; e < n * n; ++e) lu_out[e] = (double)S[e];
+  free(S); free(perm);
+  return status;
+}
+
+int oracle_lu_f64(const double *a, int64_t n, int64_t lda, int64_t group, double *logabsdet, int *sign,
+                  int64_t *bad, int64_t *negative, int64_t *perm_out, double *d_out, double *lu_out) {
+  return lu_core(a, (size_t)n, (size_t)lda, getfull_f64, group < 1 ? 0 : (size_t)group, logabsdet, sign,
+                 bad, negative, perm_out, d_out, lu_out);
+}
+
+int oracle_lu_f32(const float *a, int64_t n, int64_t lda, int64_t group, double *logabsdet, int *sign,
+                  int64_t *bad, int64_t *negative, int64_t *perm_out, double *d_out, double *lu_out) {
+  return lu_core(a, (size_t)n, (size_t)lda, getfull_f32, group < 1 ? 0 : (size_t)group, logabsdet, sign,
+                 bad, negative, perm_out, d_out, lu_out);
 }
 
 /*
