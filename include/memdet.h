@@ -153,6 +153,38 @@ typedef struct mdet_params {
                                      Costs one more launch per 64 columns; n < 2^31; not
                                      with MDET_FLAG_ASSUME_SPD (MDET_EINVAL).            */
 
+#define MDET_FLAG_GENERAL 128u    /* the matrix is not symmetric (Sec. 2.2, Eq. 1 and Alg. 1:
+                                     M = P L U for generic matrices, with pivoting inside a
+                                     block and none between blocks).  mdet_logdet_device
+                                     only, fp32 or fp64 in their own arithmetic; every other
+                                     entry point, MDET_FLAG_ASSUME_SPD, MDET_FLAG_PIVOT and
+                                     MDET_FLAG_COMPUTE_F64 with it give MDET_EINVAL.  All
+                                     n x n entries of the input are read.  Gaussian
+                                     elimination in the order of the symmetric path (block
+                                     columns, leaves of 64); in column j the pivot is the
+                                     entry of largest magnitude among the rows j .. end of
+                                     j's group of 64 consecutive rows (the first on ties),
+                                     and the two rows change places.  The factors are kept
+                                     as P A = L D U, L unit lower and U unit upper
+                                     triangular; log|det| = sum log|d_j|, sign = the
+                                     permutation's sign times the pivots' signs.
+                                     `diag` receives d; perm (as for MDET_FLAG_PIVOT, n
+                                     int32 on the device) the row order: perm[j] = row of
+                                     the input that stands at position j inside its group.
+                                     As in the symmetric pivoted form the exchanges are not
+                                     applied to the columns left of a group, so with
+                                     overwrite = 1 the array returns S = L below the
+                                     diagonal with the rows of every group in input order
+                                     left of the group, d on the diagonal and U above it:
+                                     A[perm] = L' D U with L' = S's lower part, rows of each
+                                     diagonal 64-block's columns already in pivot order.
+                                     Device memory: one more array of the matrix's shape
+                                     (the entries above the diagonal are kept transposed,
+                                     so that both triangles are read along rows), counted by
+                                     mdet_plan and mdet_workspace_query.  A column whose
+                                     candidates are all zero ends the call with
+                                     MDET_ESINGULAR.                                     */
+
 typedef struct mdet_result {
   double logabsdet;            /* log|det A|; -inf when sign == 0                    */
   int32_t sign;                /* -1, 0, +1 (numpy.linalg.slogdet convention)        */

@@ -6,6 +6,10 @@
 // leaf_factor_pivoted_kernel : the same with the pivot taken from the diagonal inside the
 //                      leaf, P A P^T = L D L^T (Sec. 2.2: the symmetric form handles
 //                      permutations; pivoting inside a block, none between blocks).
+// leaf_lu_kernel     : a leaf of a general matrix, P A = L D U with unit-lower L, diagonal D
+//                      and unit-upper U, the pivot of each column taken among the leaf's
+//                      rows (Sec. 2.2, Eq. 1 and Alg. 1: M = P L U for generic matrices;
+//                      pivoting inside a block, none between blocks).
 // leaf_solve_kernel  : rows below the leaf, X = A_rows L^-T D^-1
 //                      (Sec. 2.2: in-place triangular solve of the off-diagonal
 //                      blocks; App. E.1 "solve lower triangular system"; the
@@ -38,6 +42,7 @@ constexpr int SUB_PAD = SUB + 1;
 struct DevFlags {
   unsigned long long first_bad;   // global index of the first zero / non-finite pivot; ~0 = none
   unsigned long long bad_kind;    // 1 = zero, 2 = non-finite
+  unsigned long long odd_leaves;  // general matrices: leaves whose row order is an odd permutation
 };
 
 // Value of `v` in lane `src` (uniform lane index), delivered in scalar registers.
@@ -577,6 +582,174 @@ __global__ __launch_bounds__(FACTOR_THREADS) void leaf_factor_pivoted_kernel(
     }
   }
   __builtin_amdgcn_s_setprio(0);
+}
+
+// ---------------------------------------------------------------------------
+// leaf factor, general matrix
+// ---------------------------------------------------------------------------
+// The library keeps a general matrix as two lower-triangular arrays of the same shape:
+// Pl holds the entries on and below the diagonal, Qu the entries above it, transposed
+// (Qu[i][j] = M[j][i], i > j), so that both halves of every block row and column are read
+// along rows, as the update and solve kernels want their operands.  This kernel factors
+// one <= 64 x 64 diagonal leaf, given as its two halves: P A = L D U by Gaussian
+// elimination with the pivot of column j taken among the leaf's rows not taken before
+// (largest magnitude; the lowest row of the input on ties).  Rows stay where they are
+// while the elimination runs, each lane of a wavefront one row and each wavefront 16 of
+// the columns, and are put into the order of their choice at the end.  On return Pl holds
+// L below the diagonal and D on it, Qu holds U^T (strictly lower, unit diagonal implied),
+// dvec / dinv the pivots and their reciprocals, linvL / linvU the inverses of the 16 x 16
+// diagonal sub-blocks of L and of U^T (for leaf_solve_kernel: rows below in Pl are solved
+// against U^T, rows below in Qu against L with the leaf's row order as their column
+// gather), perm[j] = pivot0 + (row of the leaf taken at step j); flags->odd_leaves is
+// raised by one if that order is an odd permutation.
+template <typename T>
+__global__ __launch_bounds__(FACTOR_THREADS) void leaf_lu_kernel(
+    T* __restrict__ Pl, T* __restrict__ Qu, int64_t ld, int w, T* __restrict__ dvec,
+    T* __restrict__ dinv, T* __restrict__ linvL, T* __restrict__ linvU, int* __restrict__ perm,
+    long long pivot0, DevFlags* flags) {
+  __shared__ T S[FACTOR_LDS_ELEMS];      // the leaf, rows in input order while it is eliminated
+  __shared__ T Lm[FACTOR_LDS_ELEMS];     // multipliers by input row; afterwards U^T
+  __shared__ int ord[LEAF];
+  __builtin_amdgcn_s_setprio(3);
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15;
+  constexpr int PER = LEAF * LEAF / FACTOR_THREADS;
+  {
+    T v[PER];
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
+      // (r, c) of the lower half and (c, r) of the upper half come from the same place of
+      // the two arrays: row max(r, c), column min(r, c)
+      const bool in = r < w && c < w;
+      const int hi = r > c ? r : c, lo = r > c ? c : r;
+      v[q] = in ? (c <= r ? Pl[(int64_t)hi * ld + lo] : Qu[(int64_t)hi * ld + lo]) : (r == c ? T(1) : T(0));
+    }
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
+      S[r * LEAF_PAD + c] = v[q];
+      Lm[r * LEAF_PAD + c] = T(0);
+    }
+  }
+  if (tid < LEAF) ord[tid] = tid;
+  __syncthreads();
+  unsigned long long taken = 0ull;            // the same in every lane and wavefront
+  const int c0 = wave * SUB;                  // this wavefront's columns
+#pragma unroll 1
+  for (int j = 0; j < w; ++j) {
+    // every wavefront reads column j and finds the pivot row by itself
+    const T cj = S[lane * LEAF_PAD + j];
+    const int p = pick_pivot(cj, lane < w && !((taken >> lane) & 1ull));
+    taken |= 1ull << p;
+    const bool live = lane < w && !((taken >> lane) & 1ull);
+    const T rd = fast_rcp(S[p * LEAF_PAD + j]);
+    const T l = live ? cj * rd : T(0);
+    if (wave == 0) {
+      if (live) Lm[lane * LEAF_PAD + j] = l;
+      if (lane == 0) ord[j] = p;
+    }
+    // column j itself is not written in this step, nor the pivot row
+#pragma unroll
+    for (int q = 0; q < SUB; ++q) {
+      const int c = c0 + q;
+      if (live && c > j && c < w) S[lane * LEAF_PAD + c] = fma(-l, S[p * LEAF_PAD + c], S[lane * LEAF_PAD + c]);
+    }
+    __syncthreads();
+  }
+  // rows into the order in which they were taken: L below the diagonal, D U on and above
+  {
+    T v[PER];
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
+      const int from = r < w ? ord[r] : r;
+      v[q] = c < r ? Lm[from * LEAF_PAD + c] : S[from * LEAF_PAD + c];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
+      S[r * LEAF_PAD + c] = v[q];
+    }
+    __syncthreads();
+    // U = D U~: rows of the upper part divided by their pivot; its transpose, unit diagonal
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+      const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
+      T u = r == c ? T(1) : T(0);
+      if (c > r && c < w) u = v[q] * fast_rcp(S[r * LEAF_PAD + r]);
+      if (c >= r) Lm[c * LEAF_PAD + r] = u;
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < LEAF * LEAF; e += FACTOR_THREADS) {
+    const int r = e >> 6, c = e & 63;
+    if (r < w && c <= r) Pl[(int64_t)r * ld + c] = S[r * LEAF_PAD + c];
+    if (r < w && c < r) Qu[(int64_t)r * ld + c] = Lm[r * LEAF_PAD + c];
+  }
+  leaf_invert_sub<T>(S, linvL, wave, l16);
+  leaf_invert_sub<T>(Lm, linvU, wave, l16);
+  if (wave == 0) {
+    const T myd = S[lane * LEAF_PAD + lane];
+    const bool zero = myd == T(0);
+    const bool finite = fabs((double)myd) <= 1.7976931348623157e308;
+    const bool bad = lane < w && (zero || !finite);
+    const int mine = ord[lane];
+    if (lane < w) {
+      dvec[lane] = myd;
+      dinv[lane] = fast_rcp(myd);
+      perm[lane] = (int)pivot0 + mine;
+    }
+    // sign of the order: parity of the number of pairs that stand the wrong way round
+    int inv = 0;
+    for (int k = 0; k < LEAF; ++k) inv += (k > lane && ord[k] < mine) ? 1 : 0;
+    const unsigned long long odd_lanes = __ballot(inv & 1);
+    if (lane == 0 && (__popcll(odd_lanes) & 1)) atomicAdd(&flags->odd_leaves, 1ull);
+    const unsigned long long mask = __ballot(bad);
+    if (mask != 0ull) {
+      const int first = __ffsll((long long)mask) - 1;
+      if (lane == first) {
+        unsigned long long idx = (unsigned long long)(pivot0 + first);
+        unsigned long long old = atomicMin(&flags->first_bad, idx);
+        if (idx <= old) atomicExch(&flags->bad_kind, zero ? 1ull : 2ull);
+      }
+    }
+  }
+  __builtin_amdgcn_s_setprio(0);
+}
+
+// Moves the strict upper triangle of a general matrix into its transposed store, or back,
+// by 64 x 64 blocks through LDS (both arrays n x n with leading dimension ld).
+// back = 0: dst[i][j] = src[j][i] for i > j;  back = 1: dst[j][i] = src[i][j] for i > j.
+// Workgroup b handles the block pair (bi, bj), bi >= bj, of the lower triangle.
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_strict_kernel(const T* __restrict__ src,
+                                                               T* __restrict__ dst, int64_t ld,
+                                                               int64_t n, int nb, int back) {
+  __shared__ T t[LEAF * LEAF_PAD];
+  const int64_t b = blockIdx.x;
+  int64_t bi = (int64_t)((sqrt(8.0 * (double)b + 1.0) - 1.0) * 0.5);
+  while (bi * (bi + 1) / 2 > b) --bi;
+  while ((bi + 1) * (bi + 2) / 2 <= b) ++bi;
+  const int64_t bj = b - bi * (bi + 1) / 2;
+  if (bi >= nb) return;
+  // the block that is read and the block that is written: (row block, column block)
+  const int64_t sr = back ? bi : bj, sc = back ? bj : bi;
+  const int tid = threadIdx.x;
+  for (int e = tid; e < LEAF * LEAF; e += 256) {
+    const int r = e >> 6, c = e & 63;
+    const int64_t gr = sr * LEAF + r, gc = sc * LEAF + c;
+    t[r * LEAF_PAD + c] = (gr < n && gc < n) ? src[gr * ld + gc] : T(0);
+  }
+  __syncthreads();
+  for (int e = tid; e < LEAF * LEAF; e += 256) {
+    const int r = e >> 6, c = e & 63;                       // of the block written, (sc, sr)
+    const int64_t gr = sc * LEAF + r, gc = sr * LEAF + c;
+    const bool strict = back ? gc > gr : gr > gc;
+    if (gr < n && gc < n && strict) dst[gr * ld + gc] = t[c * LEAF_PAD + r];
+  }
 }
 
 // ---------------------------------------------------------------------------

@@ -146,6 +146,11 @@ struct Launcher {
   // diagonal, and perm[j] is the row/column of the input that ended at position j
   // (MDET_FLAG_PIVOT).  The leaf then has a launch of its own.
   int* perm = nullptr;
+  // General matrices (MDET_FLAG_GENERAL; Sec. 2.2, Eq. 1: M = P L U): distance in elements
+  // from an entry (i, j), i >= j, of the array the driver works on to the place that holds
+  // entry (j, i) of the matrix, in a second array of the same shape.  Every pointer the
+  // driver passes refers to the first array; 0 = symmetric matrix, no second array.
+  int64_t qoff = 0;
   // Two arrays of n x wld elements (or none): while a block column is factored its rows
   // are also stored scaled by the pivots, W = L D, so that the updates that use the
   // column read their left operand ready-made (MDET_FLAG_SCALED_COPY).  Column k uses
@@ -172,6 +177,18 @@ struct Launcher {
   int update(hipStream_t st, T* C, int64_t ldc, const T* A, int64_t lda, const T* B, int64_t ldb,
              const T* d, int64_t M, int64_t N, int64_t K, bool lower, bool trailing = false,
              const FusedLeaf<T>* fuse = nullptr, int leave_free = -1, bool a_scaled = false) {
+    if (qoff == 0) return update_one(st, C, ldc, A, lda, B, ldb, d, M, N, K, lower, trailing, fuse, leave_free, a_scaled);
+    // general matrix: the entries on and below the diagonal take rows of L and of U^T,
+    // the transposed entries above it the same two the other way round
+    int rc = update_one(st, C, ldc, A, lda, B + qoff, ldb, d, M, N, K, lower, trailing, nullptr, leave_free, false);
+    if (rc != MDET_OK) return rc;
+    return update_one(st, C + qoff, ldc, A + qoff, lda, B, ldb, d, M, N, K, lower, trailing, nullptr, leave_free,
+                      false);
+  }
+
+  int update_one(hipStream_t st, T* C, int64_t ldc, const T* A, int64_t lda, const T* B, int64_t ldb,
+                 const T* d, int64_t M, int64_t N, int64_t K, bool lower, bool trailing,
+                 const FusedLeaf<T>* fuse, int leave_free, bool a_scaled) {
     // a_scaled: A holds rows of L D already (see wbuf): same kernels as the
     // positive-definite form, which read no pivots
     const bool scaled = spd || a_scaled;
@@ -292,6 +309,35 @@ struct Launcher {
   int factor_cols(hipStream_t st, T* P, int64_t ld, int64_t m, int64_t w, int64_t d0,
                   bool first_done = false, T* Wp = nullptr, int64_t wskip = 0) {
     if (w <= 0) return MDET_OK;
+    if (w <= LEAF && qoff != 0) {
+      // P A = L D U of the leaf, then the rows below it in both halves: the lower half
+      // against U^T, the transposed upper half against L with the leaf's row order
+      if (spd || !perm || !l10) return MDET_EINVAL;
+      T* linvL = linv;
+      T* linvU = linv + LEAF * SUB;
+      hipLaunchKernelGGL((leaf_lu_kernel<T>), dim3(1), dim3(FACTOR_THREADS), 0, st, P, P + qoff, ld, (int)w,
+                         dvec + d0, dinv + d0, linvL, linvU, perm + d0, (long long)d0, flags);
+      fail->check(hipGetLastError());
+      ++launches;
+      fma += ((double)w * w * w - (double)w) / 3.0;
+      const int64_t below = m - w;
+      if (below > 0) {
+        if (below > INT32_MAX) return MDET_EINVAL;
+        const int64_t nblk = (below + SOLVE_ROWS - 1) / SOLVE_ROWS;
+        hipLaunchKernelGGL((leaf_solve_kernel<T>), dim3((unsigned)nblk), dim3(256), 0, st, P + w * ld, ld,
+                           (int)below, (int)w, (const T*)(P + qoff), ld, (const T*)(dinv + d0),
+                           (const T*)linvU, (T*)nullptr, (int64_t)0, (const T*)(dvec + d0), 0,
+                           (const int*)nullptr, 0, (const T*)nullptr, (T*)nullptr, (int64_t)0);
+        hipLaunchKernelGGL((leaf_solve_kernel<T>), dim3((unsigned)nblk), dim3(256), 0, st, P + qoff + w * ld, ld,
+                           (int)below, (int)w, (const T*)P, ld, (const T*)(dinv + d0), (const T*)linvL,
+                           (T*)nullptr, (int64_t)0, (const T*)(dvec + d0), 0, (const int*)(perm + d0), (int)d0,
+                           (const T*)nullptr, (T*)nullptr, (int64_t)0);
+        fail->check(hipGetLastError());
+        launches += 2;
+        fma += 2.0 * (double)below * ((double)w * (w - 1) / 2.0);
+      }
+      return MDET_OK;
+    }
     if (w <= LEAF) {
       if (perm) {
         if (spd) return MDET_EINVAL;
@@ -625,7 +671,8 @@ static void bind_small(Launcher<T>& L, char* base, const SmallArea& sa) {
 template <typename T>
 static void reset_flags(Launcher<T>& L, hipStream_t st) {
   // 0xFF bytes: first_bad = ~0 (none)
-  L.fail->check(hipMemsetAsync(L.flags, 0xFF, sizeof(DevFlags), st));
+  L.fail->check(hipMemsetAsync(L.flags, 0xFF, 2 * sizeof(unsigned long long), st));
+  L.fail->check(hipMemsetAsync(&L.flags->odd_leaves, 0, sizeof(unsigned long long), st));
 }
 
 // ---------------------------------------------------------------------------
@@ -689,6 +736,17 @@ static int logdet_device_t(const mdet_params& p, const Plan& plan, T* dA, int64_
     }
   }
   reset_flags(L, s0);
+  T* Q = nullptr;
+  const int nb64 = (int)((pl.n + LEAF - 1) / LEAF);
+  if (pl.general && pl.n > 0) {
+    // the entries above the diagonal go, transposed, into an array of their own
+    Q = (T*)(ws.base + sa.total + pl.copy_bytes + pl.wcopy_bytes);
+    L.qoff = Q - W;
+    if (L.qoff == 0 || !L.perm) return MDET_EINVAL;
+    hipLaunchKernelGGL((transpose_strict_kernel<T>), dim3((unsigned)((int64_t)nb64 * (nb64 + 1) / 2)),
+                       dim3(256), 0, s0, (const T*)W, Q, ldw, pl.n, nb64, 0);
+    MDET_HIP(fail, hipGetLastError());
+  }
   if (pl.wcopy_bytes) {
     char* wb = ws.base + sa.total + pl.copy_bytes;
     L.wbuf[0] = (T*)wb;
@@ -702,6 +760,12 @@ static int logdet_device_t(const mdet_params& p, const Plan& plan, T* dA, int64_
   rc = factor_resident(L, pl, cols, 0, pl.T, true, lookahead, s0, s1, events);
   if (rc == MDET_OK) {
     L.reduce(s0, pl.n, pl.bs, pl.T, partial, out, running);
+    if (Q && !pl.need_copy) {
+      // the caller's array is the output: U back above the diagonal
+      hipLaunchKernelGGL((transpose_strict_kernel<T>), dim3((unsigned)((int64_t)nb64 * (nb64 + 1) / 2)),
+                         dim3(256), 0, s0, (const T*)Q, W, ldw, pl.n, nb64, 1);
+      MDET_HIP(fail, hipGetLastError());
+    }
     if (diag && pl.n > 0)
       MDET_HIP(fail, hipMemcpyAsync(diag, L.dvec, pl.n * sizeof(T), hipMemcpyDeviceToDevice, s0));
     if (L.perm && p.perm && pl.n > 0)
@@ -720,7 +784,10 @@ static int logdet_device_t(const mdet_params& p, const Plan& plan, T* dA, int64_
   L.collect_profile(res);
   if (!fail.ok()) { res->hip_error = fail.code; return MDET_EHIP; }
   if (rc != MDET_OK) return rc;
-  return finish_result(o, res);
+  rc = finish_result(o, res);
+  // the permutation's sign: one factor of -1 for every leaf with an odd row order
+  if (pl.general && (o.flags.odd_leaves & 1ull)) res->sign = -res->sign;
+  return rc;
 }
 
 

@@ -30,6 +30,8 @@ struct Plan {
   bool out_of_core = false;
   bool need_copy = false;          // device input: work on a copy (overwrite = 0)
   bool pivot = false;              // MDET_FLAG_PIVOT
+  bool general = false;            // MDET_FLAG_GENERAL: P A = L D U, two triangular arrays
+  uint64_t q_bytes = 0;            // the second of them
   uint64_t small_bytes = 0;        // pivots, reciprocals, flags, reduction scratch
   uint64_t layout_bytes = 0;       // packed lower block-column layout
   uint64_t copy_bytes = 0;
@@ -108,6 +110,12 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
   pl.device_input = device_input;
   pl.tile_bytes = (uint64_t)pl.bs * pl.bs * pl.beta;
   pl.pivot = (p.flags & MDET_FLAG_PIVOT) != 0;
+  // general matrix: resident device input only, in the arithmetic of its own type; the
+  // row order inside each leaf is always recorded
+  pl.general = (p.flags & MDET_FLAG_GENERAL) != 0;
+  if (pl.general && (!device_input || widen || (p.flags & MDET_FLAG_PIVOT))) return MDET_EINVAL;
+  if (pl.general && (p.flags & MDET_FLAG_ASSUME_SPD)) return MDET_EINVAL;
+  if (pl.general) pl.pivot = true;
   if (pl.pivot && (p.flags & MDET_FLAG_ASSUME_SPD)) return MDET_EINVAL;   // nothing to choose from
   if (pl.pivot && p.n > INT32_MAX) return MDET_EINVAL;
   pl.small_bytes = small_area(pl.n, pl.T, pl.beta, pl.pivot).total;
@@ -124,7 +132,7 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
   // one is given up again if the workspace cannot be had (wcopy_optional)
   const bool wcopy_auto = !(p.flags & MDET_FLAG_SCALED_COPY) && budget == 0 && p.n >= 24576;
   const uint64_t wcopy = (((p.flags & MDET_FLAG_SCALED_COPY) || wcopy_auto) &&
-                          !(p.flags & MDET_FLAG_ASSUME_SPD) && pl.T >= 2)
+                          !(p.flags & MDET_FLAG_ASSUME_SPD) && !pl.general && pl.T >= 2)
                              ? 2 * align256((uint64_t)pl.n * pl.bs * pl.beta) : 0;
   pl.wcopy_optional = wcopy_auto && wcopy != 0;
 
@@ -136,7 +144,13 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
       int64_t ldp = round_up(p.n > 0 ? p.n : 1, vec);
       pl.copy_bytes = align256((uint64_t)p.n * ldp * pl.beta);
     }
-    pl.dev_bytes = pl.small_bytes + pl.copy_bytes;
+    pl.q_bytes = 0;
+    if (pl.general) {
+      // the transposed upper triangle: an array shaped like the one the driver works on
+      const int64_t ldq = pl.need_copy ? round_up(p.n > 0 ? p.n : 1, vec) : ld;
+      pl.q_bytes = align256((uint64_t)p.n * ldq * pl.beta);
+    }
+    pl.dev_bytes = pl.small_bytes + pl.copy_bytes + pl.q_bytes;
     pl.out_of_core = false;
     if (budget && pl.dev_bytes > budget) return MDET_EBUDGET;
     if (wcopy && (!budget || pl.dev_bytes + wcopy <= budget)) {
