@@ -213,6 +213,9 @@ def main():
     ap.add_argument("--file-dir", default="",
                     help="out-of-core configurations: write the matrix to a file in this directory "
                          "and run mdet_logdet_file on it (factors go to a scratch file beside it)")
+    ap.add_argument("--general", action="store_true",
+                    help="MDET_FLAG_GENERAL: the configuration's matrix with its rows shuffled inside groups of 64, "
+                         "factored as a general matrix (P A = L D U; in-core configurations; counts 2n^3/3)")
     ap.add_argument("--pivot", action="store_true",
                     help="MDET_FLAG_PIVOT: pivoting on the diagonal inside each group of 64 columns")
     ap.add_argument("--kernels", action="store_true",
@@ -263,9 +266,18 @@ def main():
         xflags |= M.FLAG_SCALED_COPY
     if args.pivot:
         xflags |= M.FLAG_PIVOT
+    if args.general:
+        if out_of_core or widen or args.assume_spd or args.pivot or args.scaled_copy:
+            print("bench.py: --general goes with an in-core configuration and no other form", file=sys.stderr)
+            sys.exit(2)
+        xflags |= M.FLAG_GENERAL
     results = []
     if not out_of_core:
         a = form_matrix_device(w, torch)
+        if args.general:
+            rng = np.random.default_rng(w.seed)
+            rows = np.concatenate([g0 + rng.permutation(min(64, n - g0)) for g0 in range(0, n, 64)])
+            a = a[torch.from_numpy(rows).cuda()].contiguous()
         torch.cuda.synchronize()
         free, _ = torch.cuda.mem_get_info()
         per = a.numel() * a.element_size()
@@ -299,7 +311,8 @@ def main():
 
         def run(i, flags=0, want_diag=False):
             return M.mdet_logdet_device(copies[0 if widen else i % ncopies], block_size=bs, overwrite=True,
-                                        flags=flags | (M.FLAG_COMPUTE_F64 if widen else 0),
+                                        flags=flags | (M.FLAG_COMPUTE_F64 if widen else 0) |
+                                        (M.FLAG_GENERAL if args.general else 0),
                                         diag=diag if want_diag else None)
         done = 0
         for i in range(warmup):
@@ -356,7 +369,7 @@ def main():
         diag_host = diag.numpy().astype(np.float64)
 
     sec = t_total / steps
-    flop = n ** 3 / 3.0
+    flop = n ** 3 / 3.0 * (2.0 if args.general else 1.0)
     value = flop / sec / 1e12
     upd_t = sum(r.t_trailing_update for r in results)
     upd_f = sum(r.trailing_update_flops for r in results)
@@ -364,7 +377,8 @@ def main():
     achieved = upd_f / upd_t / 1e12 if upd_t > 0 else None
     peak = PEAK["f64" if widen else w.dtype]
     line = {
-        "metric": "logdet throughput, (n^3/3)/time-to-logdet",
+        "metric": ("logdet throughput, (2n^3/3)/time-to-logdet" if args.general
+                   else "logdet throughput, (n^3/3)/time-to-logdet"),
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f64" if widen else w.dtype, "data": "synthetic",
@@ -376,7 +390,9 @@ def main():
                    **({"storage": "f32, widened exactly; arithmetic f64"} if widen else {}),
                    **({"form": "positive definite (Cholesky), MDET_FLAG_ASSUME_SPD"} if args.assume_spd else {}),
                    **({"workspace": "MDET_FLAG_SCALED_COPY"} if args.scaled_copy else {}),
-                   **({"pivoting": "inside groups of 64, MDET_FLAG_PIVOT"} if args.pivot else {})},
+                   **({"pivoting": "inside groups of 64, MDET_FLAG_PIVOT"} if args.pivot else {}),
+                   **({"form": "general matrix (rows shuffled inside groups of 64), P A = L D U, "
+                               "MDET_FLAG_GENERAL; value counts 2n^3/3"} if args.general else {})},
         "time_to_logdet_s": sec, "frac_of_matrix_peak": value / peak,
         "logabsdet": final.logabsdet, "sign": final.sign, "negative_pivots": final.negative_pivots,
         "kernel_launches_per_step": final.kernel_launches,

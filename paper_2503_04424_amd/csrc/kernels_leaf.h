@@ -594,90 +594,105 @@ __global__ __launch_bounds__(FACTOR_THREADS) void leaf_factor_pivoted_kernel(
 // one <= 64 x 64 diagonal leaf, given as its two halves: P A = L D U by Gaussian
 // elimination with the pivot of column j taken among the leaf's rows not taken before
 // (largest magnitude; the lowest row of the input on ties).  Rows stay where they are
-// while the elimination runs, each lane of a wavefront one row and each wavefront 16 of
-// the columns, and are put into the order of their choice at the end.  On return Pl holds
-// L below the diagonal and D on it, Qu holds U^T (strictly lower, unit diagonal implied),
-// dvec / dinv the pivots and their reciprocals, linvL / linvU the inverses of the 16 x 16
-// diagonal sub-blocks of L and of U^T (for leaf_solve_kernel: rows below in Pl are solved
-// against U^T, rows below in Qu against L with the leaf's row order as their column
-// gather), perm[j] = pivot0 + (row of the leaf taken at step j); flags->odd_leaves is
-// raised by one if that order is an odd permutation.
+// while the elimination runs: lane r of every wavefront holds row r, wavefront q its
+// columns 16q .. 16q+15, in registers.  At step j the wavefront that owns column j picks
+// the pivot row and hands the multipliers and the row's number to the others through LDS
+// (one barrier per step); each wavefront then reads the pivot row's entries of its own
+// columns from the pivot lane's registers.  The rows are put into the order of their
+// choice at the end.  On return Pl holds L below the diagonal and D on it, Qu holds U^T
+// (strictly lower, unit diagonal implied), dvec / dinv the pivots and their reciprocals,
+// linvL / linvU the inverses of the 16 x 16 diagonal sub-blocks of L and of U^T (for
+// leaf_solve_kernel: rows below in Pl are solved against U^T, rows below in Qu against L
+// with the leaf's row order as their column gather), perm[j] = pivot0 + (row of the leaf
+// taken at step j); flags->odd_leaves is raised by one if that order is an odd permutation.
 template <typename T>
 __global__ __launch_bounds__(FACTOR_THREADS) void leaf_lu_kernel(
     T* __restrict__ Pl, T* __restrict__ Qu, int64_t ld, int w, T* __restrict__ dvec,
     T* __restrict__ dinv, T* __restrict__ linvL, T* __restrict__ linvU, int* __restrict__ perm,
     long long pivot0, DevFlags* flags) {
-  __shared__ T S[FACTOR_LDS_ELEMS];      // the leaf, rows in input order while it is eliminated
+  __shared__ T S[FACTOR_LDS_ELEMS];      // the rows in their final order: L below, D U on and above
   __shared__ T Lm[FACTOR_LDS_ELEMS];     // multipliers by input row; afterwards U^T
+  __shared__ T lbuf[2][LEAF];            // a step's multipliers, for the other wavefronts
+  __shared__ int pbuf[2];                // and its pivot row
   __shared__ int ord[LEAF];
   __builtin_amdgcn_s_setprio(3);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l16 = lane & 15;
+  const int c0 = wave * SUB;
   constexpr int PER = LEAF * LEAF / FACTOR_THREADS;
-  {
-    T v[PER];
+  T a[SUB];
 #pragma unroll
-    for (int q = 0; q < PER; ++q) {
-      const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
-      // (r, c) of the lower half and (c, r) of the upper half come from the same place of
-      // the two arrays: row max(r, c), column min(r, c)
-      const bool in = r < w && c < w;
-      const int hi = r > c ? r : c, lo = r > c ? c : r;
-      v[q] = in ? (c <= r ? Pl[(int64_t)hi * ld + lo] : Qu[(int64_t)hi * ld + lo]) : (r == c ? T(1) : T(0));
-    }
-#pragma unroll
-    for (int q = 0; q < PER; ++q) {
-      const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
-      S[r * LEAF_PAD + c] = v[q];
-      Lm[r * LEAF_PAD + c] = T(0);
-    }
+  for (int k = 0; k < SUB; ++k) {
+    // (r, c) of the lower half and (c, r) of the upper half come from the same place of
+    // the two arrays: row max(r, c), column min(r, c)
+    const int r = lane, c = c0 + k;
+    const int hi = r > c ? r : c, lo = r > c ? c : r;
+    a[k] = (r < w && c < w) ? (c <= r ? Pl[(int64_t)hi * ld + lo] : Qu[(int64_t)hi * ld + lo])
+                            : (r == c ? T(1) : T(0));
   }
+#pragma unroll
+  for (int q = 0; q < PER; ++q) Lm[((q * FACTOR_THREADS + tid) >> 6) * LEAF_PAD + (tid & 63)] = T(0);
   if (tid < LEAF) ord[tid] = tid;
-  __syncthreads();
+  __syncthreads();                            // Lm is clear before the first multiplier lands in it
   unsigned long long taken = 0ull;            // the same in every lane and wavefront
-  const int c0 = wave * SUB;                  // this wavefront's columns
+  int mypos = lane;                           // where this lane's row ends
 #pragma unroll 1
-  for (int j = 0; j < w; ++j) {
-    // every wavefront reads column j and finds the pivot row by itself
-    const T cj = S[lane * LEAF_PAD + j];
-    const int p = pick_pivot(cj, lane < w && !((taken >> lane) & 1ull));
-    taken |= 1ull << p;
-    const bool live = lane < w && !((taken >> lane) & 1ull);
-    const T rd = fast_rcp(S[p * LEAF_PAD + j]);
-    const T l = live ? cj * rd : T(0);
-    if (wave == 0) {
-      if (live) Lm[lane * LEAF_PAD + j] = l;
-      if (lane == 0) ord[j] = p;
-    }
-    // column j itself is not written in this step, nor the pivot row
+  for (int jb = 0; jb < LEAF / SUB; ++jb) {
 #pragma unroll
-    for (int q = 0; q < SUB; ++q) {
-      const int c = c0 + q;
-      if (live && c > j && c < w) S[lane * LEAF_PAD + c] = fma(-l, S[p * LEAF_PAD + c], S[lane * LEAF_PAD + c]);
+    for (int jj = 0; jj < SUB; ++jj) {
+      const int j = jb * SUB + jj;
+      if (j < w) {
+        if (wave == jb) {
+          const T cj = a[jj];
+          const bool cand = lane < w && !((taken >> lane) & 1ull);
+          const int pp = pick_pivot(cj, cand);
+          const T rd = fast_rcp(lane_value(cj, pp));
+          const T lj = (cand && lane != pp) ? cj * rd : T(0);
+          lbuf[j & 1][lane] = lj;
+          Lm[lane * LEAF_PAD + j] = lj;
+          if (lane == 0) {
+            pbuf[j & 1] = pp;
+            ord[j] = pp;
+          }
+        }
+        __syncthreads();
+        const T l = lbuf[j & 1][lane];
+        const int p = __builtin_amdgcn_readfirstlane(pbuf[j & 1]);
+        taken |= 1ull << p;
+        if (lane == p) mypos = j;
+        const bool live = lane < w && !((taken >> lane) & 1ull);
+        if (wave >= jb) {
+#pragma unroll
+          for (int k = 0; k < SUB; ++k) {
+            if (wave > jb || k > jj) {
+              const T pv = lane_value(a[k], p);
+              a[k] = live ? fma(-l, pv, a[k]) : a[k];
+            }
+          }
+        }
+      }
     }
-    __syncthreads();
   }
-  // rows into the order in which they were taken: L below the diagonal, D U on and above
+  // every row to the place of its turn; its entries left of the diagonal are replaced below
+#pragma unroll
+  for (int k = 0; k < SUB; ++k) S[mypos * LEAF_PAD + c0 + k] = a[k];
+  __syncthreads();
   {
     T v[PER];
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
       const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
       const int from = r < w ? ord[r] : r;
-      v[q] = c < r ? Lm[from * LEAF_PAD + c] : S[from * LEAF_PAD + c];
+      v[q] = c < r ? Lm[from * LEAF_PAD + c] : S[r * LEAF_PAD + c];
     }
     __syncthreads();
+    // L into place; U = D U~: rows of the upper part divided by their pivot, and its
+    // transpose with a unit diagonal
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
       const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
-      S[r * LEAF_PAD + c] = v[q];
-    }
-    __syncthreads();
-    // U = D U~: rows of the upper part divided by their pivot; its transpose, unit diagonal
-#pragma unroll
-    for (int q = 0; q < PER; ++q) {
-      const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
+      if (c < r) S[r * LEAF_PAD + c] = v[q];
       T u = r == c ? T(1) : T(0);
       if (c > r && c < w) u = v[q] * fast_rcp(S[r * LEAF_PAD + r]);
       if (c >= r) Lm[c * LEAF_PAD + r] = u;
