@@ -785,7 +785,7 @@ __global__ __launch_bounds__(256) void transpose_strict_kernel(const T* __restri
 constexpr int SOLVE_ROWS = 64;   // rows per workgroup
 
 template <typename T>
-__global__ __launch_bounds__(256) void leaf_solve_kernel(
+__device__ __forceinline__ void leaf_solve_body(
     T* __restrict__ Xg, int64_t ld, int m, int w, const T* __restrict__ Lleaf, int64_t ldl,
     const T* __restrict__ dinv, const T* __restrict__ linv, T* __restrict__ Wg, int64_t ldw,
     const T* __restrict__ dvec, int wfrom, const int* __restrict__ perm, int perm0,
@@ -909,6 +909,32 @@ __global__ __launch_bounds__(256) void leaf_solve_kernel(
       }
     }
   }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void leaf_solve_kernel(
+    T* __restrict__ Xg, int64_t ld, int m, int w, const T* __restrict__ Lleaf, int64_t ldl,
+    const T* __restrict__ dinv, const T* __restrict__ linv, T* __restrict__ Wg, int64_t ldw,
+    const T* __restrict__ dvec, int wfrom, const int* __restrict__ perm, int perm0,
+    const T* __restrict__ fix_src, T* __restrict__ fix_dst, int64_t fix_ld) {
+  leaf_solve_body<T>(Xg, ld, m, w, Lleaf, ldl, dinv, linv, Wg, ldw, dvec, wfrom, perm, perm0, fix_src, fix_dst,
+                     fix_ld);
+}
+
+// The rows below a leaf of a general matrix, both halves in one launch with two rows of
+// workgroups: blockIdx.y = 0 solves the rows of the lower half (Xg) against U^T (the leaf's
+// place in the second array, qoff elements on) with linvU; blockIdx.y = 1 the rows of the
+// transposed upper half (Xg + qoff) against L (Lleaf) with linvL, their columns gathered
+// in the leaf's row order (perm, perm0 as in leaf_solve_kernel).
+template <typename T>
+__global__ __launch_bounds__(256) void leaf_solve_general_kernel(
+    T* Xg, int64_t ld, int m, int w, const T* Lleaf, const T* __restrict__ dinv,
+    const T* __restrict__ linvL, const T* __restrict__ linvU, const T* __restrict__ dvec,
+    const int* __restrict__ perm, int perm0, int64_t qoff) {
+  const bool upper = blockIdx.y != 0;
+  leaf_solve_body<T>(upper ? Xg + qoff : Xg, ld, m, w, upper ? Lleaf : Lleaf + qoff, ld, dinv,
+                     upper ? linvL : linvU, (T*)nullptr, (int64_t)0, dvec, 0,
+                     upper ? perm : (const int*)nullptr, perm0, (const T*)nullptr, (T*)nullptr, (int64_t)0);
 }
 
 }  // namespace mdet

@@ -471,11 +471,11 @@ __global__ __launch_bounds__(UPD_THREADS) void panel_update64_kernel(
 // operands, the pivots and the C block are requested in one go and the whole
 // product runs from LDS, so the launch costs one memory round trip instead of one
 // per slab.  64 x 64 block of C per workgroup, 2 x 2 MFMA tiles per wavefront.
-template <typename T, bool SCALED = false>
-__global__ __launch_bounds__(UPD_THREADS) void leaf_update_kernel(
+template <typename T, bool SCALED>
+__device__ __forceinline__ void leaf_update_body(
     T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
     const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int nsn, int swl,
-    int lower_, int per, FusedLeaf<T> fl) {
+    int lower_, int per, const FusedLeaf<T>& fl) {
   __builtin_amdgcn_s_setprio(2);
   const bool lower = lower_ != 0;
   using X = Mfma<T>;
@@ -602,6 +602,55 @@ __global__ __launch_bounds__(UPD_THREADS) void leaf_update_kernel(
                               fl.spd);
   }
 }
+
+template <typename T, bool SCALED = false>
+__global__ __launch_bounds__(UPD_THREADS) void leaf_update_kernel(
+    T* __restrict__ C, int64_t ldc, const T* __restrict__ A, int64_t lda,
+    const T* __restrict__ B, int64_t ldb, const T* __restrict__ d, int M, int N, int nsn, int swl,
+    int lower_, int per, FusedLeaf<T> fl) {
+  leaf_update_body<T, SCALED>(C, ldc, A, lda, B, ldb, d, M, N, nsn, swl, lower_, per, fl);
+}
+
+// General matrices (Sec. 2.2, Eq. 1: M = P L U): the matrix is two lower-triangular arrays
+// qoff elements apart, the entries on and below the diagonal and the transposed entries
+// above it.  The same update runs on both in one launch with two rows of workgroups
+// (blockIdx.y): the first array takes A's rows there and B's rows in the second array,
+// the second array the other way round.  C, A and B all point into the first array.
+template <typename T>
+struct GeneralOperands {
+  T* C;
+  const T* A;
+  const T* B;
+};
+template <typename T>
+__device__ __forceinline__ GeneralOperands<T> general_operands(T* C, const T* A, const T* B, int64_t qoff) {
+  if (blockIdx.y != 0) return {C + qoff, A + qoff, B};
+  return {C, A, B + qoff};
+}
+template <typename T>
+__global__ __launch_bounds__(UPD_THREADS) void leaf_update_general_kernel(
+    T* C, int64_t ldc, const T* A, int64_t lda, const T* B, int64_t ldb, const T* __restrict__ d,
+    int M, int N, int nsn, int swl, int lower_, int per, int64_t qoff) {
+  const GeneralOperands<T> o = general_operands<T>(C, A, B, qoff);
+  const FusedLeaf<T> none{0, nullptr, nullptr, nullptr, 0, nullptr, 0};
+  leaf_update_body<T, false>(o.C, ldc, o.A, lda, o.B, ldb, d, M, N, nsn, swl, lower_, per, none);
+}
+#define MDET_GENERAL_UPDATE_KERNEL(NAME, TM, OCC, PRIO)                                              \
+  template <typename T>                                                                             \
+  __global__ __launch_bounds__(UPD_THREADS, OCC) void NAME(                                         \
+      T* C, int64_t ldc, const T* A, int64_t lda, const T* B, int64_t ldb, const T* __restrict__ d, \
+      int M, int N, int K, int nsn, int swl, int lower, int per, int k0, int64_t qoff) {            \
+    if (PRIO) __builtin_amdgcn_s_setprio(2);                                                        \
+    const GeneralOperands<T> o = general_operands<T>(C, A, B, qoff);                                \
+    const FusedLeaf<T> none{0, nullptr, nullptr, nullptr, 0, nullptr, 0};                           \
+    schur_update_body<T, TM, false>(o.C, ldc, o.A, lda, o.B, ldb, d, M, N, K, nsn, swl, lower != 0, \
+                                    per, k0, none);                                                 \
+  }
+MDET_GENERAL_UPDATE_KERNEL(trailing_update_general_kernel, 4, 2, 0)
+MDET_GENERAL_UPDATE_KERNEL(trailing_update64_general_kernel, 2, 1, 0)
+MDET_GENERAL_UPDATE_KERNEL(panel_update_general_kernel, 4, 2, 1)
+MDET_GENERAL_UPDATE_KERNEL(panel_update64_general_kernel, 2, 1, 1)
+#undef MDET_GENERAL_UPDATE_KERNEL
 
 // Two leaves side by side (a 128-column strip of a block column), the first one
 // factored: one launch solves the rows below the first leaf against it, updates the

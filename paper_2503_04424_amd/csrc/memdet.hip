@@ -177,13 +177,9 @@ struct Launcher {
   int update(hipStream_t st, T* C, int64_t ldc, const T* A, int64_t lda, const T* B, int64_t ldb,
              const T* d, int64_t M, int64_t N, int64_t K, bool lower, bool trailing = false,
              const FusedLeaf<T>* fuse = nullptr, int leave_free = -1, bool a_scaled = false) {
-    if (qoff == 0) return update_one(st, C, ldc, A, lda, B, ldb, d, M, N, K, lower, trailing, fuse, leave_free, a_scaled);
-    // general matrix: the entries on and below the diagonal take rows of L and of U^T,
-    // the transposed entries above it the same two the other way round
-    int rc = update_one(st, C, ldc, A, lda, B + qoff, ldb, d, M, N, K, lower, trailing, nullptr, leave_free, false);
-    if (rc != MDET_OK) return rc;
-    return update_one(st, C + qoff, ldc, A + qoff, lda, B, ldb, d, M, N, K, lower, trailing, nullptr, leave_free,
-                      false);
+    // general matrix: one launch updates both arrays (see update_one)
+    return update_one(st, C, ldc, A, lda, B, ldb, d, M, N, K, lower, trailing, qoff ? nullptr : fuse, leave_free,
+                      qoff ? false : a_scaled);
   }
 
   int update_one(hipStream_t st, T* C, int64_t ldc, const T* A, int64_t lda, const T* B, int64_t ldb,
@@ -205,7 +201,10 @@ struct Launcher {
     // block column a K = 64 update runs single-shot from LDS and short launches
     // use 64 x 64 blocks so that they reach more compute units
     const bool leaf_k = !trailing && K == 64;
-    const int64_t wg128 = 8 * update_grid(M, N, lower, 128).per;
+    // general matrix: the launch has two rows of workgroups, one per array
+    const int64_t dual = qoff != 0 ? 2 : 1;
+    if (dual == 2 && (spd || a_scaled || fuse || (qoff * (int64_t)sizeof(T)) % 16 != 0)) return MDET_EINVAL;
+    const int64_t wg128 = dual * 8 * update_grid(M, N, lower, 128).per;
     const bool small = !trailing && !leaf_k && wg128 < 1024;
     // A trailing update whose 128 x 128 blocks would not fill the device's slots (the
     // next block column of a small matrix, the bulk of the last few block columns)
@@ -225,8 +224,9 @@ struct Launcher {
     // workgroups per launch and XCD: everything at once, or rounds that fill all but
     // leave_free of the device's slots
     int64_t per_launch = ug.per;
-    if (trailing && !small_trailing && leave_free >= 0 && slots - leave_free >= 8 && 8 * ug.per > slots - leave_free)
-      per_launch = (slots - leave_free) / 8;
+    if (trailing && !small_trailing && leave_free >= 0 && slots - leave_free >= 8 * dual &&
+        dual * 8 * ug.per > slots - leave_free)
+      per_launch = (slots - leave_free) / (8 * dual);
     dim3 block(UPD_THREADS);
     const bool timed = profile && trailing && !small_trailing;   // trailing_update_kernel proper
     for (int64_t k0 = 0; k0 < ug.per; k0 += per_launch) {
@@ -246,7 +246,20 @@ struct Launcher {
     if (scaled) MDET_LAUNCH_UPD_AS(KERNEL, true);                                                 \
     else MDET_LAUNCH_UPD_AS(KERNEL, false);                                                       \
   } while (0)
-      if (small_trailing) MDET_LAUNCH_UPD(trailing_update64_kernel);
+      if (dual == 2) {
+        const dim3 grid2((unsigned)(8 * kn), 2);
+#define MDET_LAUNCH_GENERAL(KERNEL)                                                                 \
+  hipLaunchKernelGGL((KERNEL<T>), grid2, block, 0, st, C, ldc, A, lda, B, ldb, d, (int)M, (int)N,   \
+                     (int)K, ug.nsn, ug.swl, (int)lower, (int)ug.per, (int)k0, qoff)
+        if (small_trailing) MDET_LAUNCH_GENERAL(trailing_update64_general_kernel);
+        else if (trailing) MDET_LAUNCH_GENERAL(trailing_update_general_kernel);
+        else if (leaf_k)
+          hipLaunchKernelGGL((leaf_update_general_kernel<T>), grid2, block, 0, st, C, ldc, A, lda, B, ldb, d,
+                             (int)M, (int)N, ug.nsn, ug.swl, (int)lower, (int)ug.per, qoff);
+        else if (small) MDET_LAUNCH_GENERAL(panel_update64_general_kernel);
+        else MDET_LAUNCH_GENERAL(panel_update_general_kernel);
+#undef MDET_LAUNCH_GENERAL
+      } else if (small_trailing) MDET_LAUNCH_UPD(trailing_update64_kernel);
       else if (trailing) MDET_LAUNCH_UPD(trailing_update_kernel);
       else if (leaf_k) {
         if (scaled)
@@ -274,6 +287,7 @@ struct Launcher {
     } else {
       f = (double)M * (double)N * (double)K;
     }
+    f *= (double)dual;
     fma += f;
     if (timed) prof_fma += f;
     return MDET_OK;
@@ -324,16 +338,11 @@ struct Launcher {
       if (below > 0) {
         if (below > INT32_MAX) return MDET_EINVAL;
         const int64_t nblk = (below + SOLVE_ROWS - 1) / SOLVE_ROWS;
-        hipLaunchKernelGGL((leaf_solve_kernel<T>), dim3((unsigned)nblk), dim3(256), 0, st, P + w * ld, ld,
-                           (int)below, (int)w, (const T*)(P + qoff), ld, (const T*)(dinv + d0),
-                           (const T*)linvU, (T*)nullptr, (int64_t)0, (const T*)(dvec + d0), 0,
-                           (const int*)nullptr, 0, (const T*)nullptr, (T*)nullptr, (int64_t)0);
-        hipLaunchKernelGGL((leaf_solve_kernel<T>), dim3((unsigned)nblk), dim3(256), 0, st, P + qoff + w * ld, ld,
-                           (int)below, (int)w, (const T*)P, ld, (const T*)(dinv + d0), (const T*)linvL,
-                           (T*)nullptr, (int64_t)0, (const T*)(dvec + d0), 0, (const int*)(perm + d0), (int)d0,
-                           (const T*)nullptr, (T*)nullptr, (int64_t)0);
+        hipLaunchKernelGGL((leaf_solve_general_kernel<T>), dim3((unsigned)nblk, 2), dim3(256), 0, st, P + w * ld,
+                           ld, (int)below, (int)w, (const T*)P, (const T*)(dinv + d0), (const T*)linvL,
+                           (const T*)linvU, (const T*)(dvec + d0), (const int*)(perm + d0), (int)d0, qoff);
         fail->check(hipGetLastError());
-        launches += 2;
+        ++launches;
         fma += 2.0 * (double)below * ((double)w * (w - 1) / 2.0);
       }
       return MDET_OK;
