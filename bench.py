@@ -398,10 +398,12 @@ def main():
         "kernel_launches_per_step": final.kernel_launches,
         "roofline": {
             "kernel": ("trailing_update_kernel (Schur update A_ij -= L_ik L_jk^T on MFMA)" if args.assume_spd
+                       else "trailing_update_general_kernel (Schur update A_ij -= L_ik D_k U_kj of both triangles "
+                            "in one launch, on MFMA)" if args.general
                        else "trailing_update_kernel (Schur update A_ij -= L_ik D_k L_jk^T on MFMA)"),
             "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
             "frac": (achieved / peak) if achieved else None,
-            "traffic": measured_traffic(w.name) if not (args.n or args.block_size) else None,
+            "traffic": measured_traffic(w.name) if not (args.n or args.block_size or args.general) else None,
             "launches_timed": upd_n,
             "avg_launch_ms": (upd_t / upd_n * 1e3) if upd_n else None,
             "flop_per_launch_avg": (upd_f / upd_n) if upd_n else None,

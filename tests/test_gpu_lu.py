@@ -14,6 +14,7 @@ and on matrices whose candidates are well separated the permutations and the fac
 themselves must be equal.
 """
 import math
+import os
 
 import numpy as np
 import pytest
@@ -276,11 +277,12 @@ def test_bad_arguments_and_workspace(M):
     assert e.value.status == M.Status.EBUDGET
 
 
-def test_benchmark_size_against_a_product_of_known_factors(M):
-    # n = 8192: A = (rows shuffled inside groups of 64) of L0 U0 with a unit lower L0 of small
-    # entries and an upper U0 with a known diagonal: log|det A| = sum log|diag U0| up to the
-    # conditioning of the product
-    n = 8192
+@pytest.mark.parametrize("n", [8192, pytest.param(32768, marks=pytest.mark.skipif(
+    os.environ.get("MEMDET_FULL") != "1", reason="set MEMDET_FULL=1"))])
+def test_benchmark_size_against_a_product_of_known_factors(M, n):
+    # the sizes bench.py --general times: A = (rows shuffled inside groups of 64) of L0 U0 with
+    # a unit lower L0 of small entries and an upper U0 with a known diagonal:
+    # log|det A| = sum log|diag U0| up to the conditioning of the product
     g = torch.Generator(device="cuda").manual_seed(5)
     L0 = torch.tril(torch.randn((n, n), generator=g, device="cuda", dtype=torch.float64), -1) / (2.0 * math.sqrt(n))
     L0 += torch.eye(n, device="cuda", dtype=torch.float64)
