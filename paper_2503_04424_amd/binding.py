@@ -284,7 +284,8 @@ def mdet_logdet_device(a, block_size=0, mem_budget=0, overwrite=False, flags=0, 
                        stream=None, workspace=None, raise_on_error=True, perm=None) -> LogdetResult:
     """log|det| and sign of the symmetric matrix whose lower triangle is in the
     2-D CUDA tensor ``a`` (float64 / float32, row-major, unit column stride).
-    ``perm`` (int32 CUDA tensor, with FLAG_PIVOT or FLAG_GENERAL) receives the permutation."""
+    ``perm`` (int32 CUDA tensor, with FLAG_PIVOT or FLAG_GENERAL) receives the permutation.
+    With FLAG_GENERAL ``a`` is a general matrix and all of it is read."""
     if a.dim() != 2 or a.shape[0] != a.shape[1] or not a.is_cuda or (a.numel() and a.stride(1) != 1):
         raise ValueError("square row-major CUDA tensor expected")
     n = a.shape[0]

@@ -141,6 +141,31 @@ def test_plan_takes_the_scaled_copy_unasked_only_for_large_uncapped_calls(M):
     assert h.dev_bytes_needed == M.mdet_plan(32768, "f64", 2048, flags=M.FLAG_SCALED_COPY).dev_bytes_needed
 
 
+def test_plan_for_a_general_matrix(M):
+    # MDET_FLAG_GENERAL (Sec. 2.2, Eq. 1: M = P L U): one more array of the matrix's shape for
+    # the transposed upper triangle, the permutation, no scaled copy; resident device input only
+    def need(n, bs, **kw):
+        return M.mdet_plan(n, "f64", bs, for_device_input=True, **kw).dev_bytes_needed
+    for n, bs in ((4096, 512), (32768, 2048)):
+        sym = need(n, bs, overwrite=True, mem_budget=1 << 50)
+        gen = need(n, bs, overwrite=True, flags=M.FLAG_GENERAL)
+        assert gen == sym + n * n * 8 + n * 4
+        assert need(n, bs, overwrite=False, flags=M.FLAG_GENERAL) == gen + n * n * 8
+    assert M.mdet_plan(1000, "f32", 128, overwrite=True, flags=M.FLAG_GENERAL,
+                       for_device_input=True).dev_bytes_needed >= 1000 * 1000 * 4
+    for kw in (dict(for_device_input=False), dict(for_device_input=True, flags_extra=M.FLAG_PIVOT),
+               dict(for_device_input=True, flags_extra=M.FLAG_ASSUME_SPD)):
+        with pytest.raises(M.MemdetError) as e:
+            M.mdet_plan(4096, "f64", 512, flags=M.FLAG_GENERAL | kw.pop("flags_extra", 0), **kw)
+        assert e.value.status == M.Status.EINVAL
+    with pytest.raises(M.MemdetError) as e:
+        M.mdet_plan(4096, "f32", 512, flags=M.FLAG_GENERAL | M.FLAG_COMPUTE_F64, for_device_input=True)
+    assert e.value.status == M.Status.EINVAL
+    with pytest.raises(M.MemdetError) as e:
+        M.mdet_plan(4096, "f64", 512, 64 << 20, overwrite=True, flags=M.FLAG_GENERAL, for_device_input=True)
+    assert e.value.status == M.Status.EBUDGET
+
+
 def test_plan_fp32_storage_with_fp64_arithmetic(M):
     n = 3000
     plain = M.mdet_plan(n, "f32", 256, overwrite=True, for_device_input=True)
