@@ -84,10 +84,10 @@ typedef struct mdet_params {
                                 host_bytes that receives the updated blocks; NULL =
                                 the library allocates pinned memory itself.        */
   uint64_t host_scratch_bytes;
-  void* perm;                /* MDET_FLAG_PIVOT: n int32 that receive the permutation
-                                (a DEVICE pointer for mdet_logdet_device, a HOST pointer
-                                for the host and provider entry points); NULL = not
-                                wanted.  Ignored without the flag.                  */
+  void* perm;                /* MDET_FLAG_PIVOT, MDET_FLAG_GENERAL: n int32 that receive
+                                the permutation (a DEVICE pointer for mdet_logdet_device,
+                                a HOST pointer for the host and provider entry points);
+                                NULL = not wanted.  Ignored without those flags.     */
 } mdet_params;
 
 #define MDET_FLAG_NO_LOOKAHEAD 1u /* run every step on one stream, strictly in order
