@@ -312,3 +312,38 @@ def test_benchmark_size_against_a_product_of_known_factors(M, n):
     o = oracle.lu_logdet(a[:GROUP, :GROUP].cpu().numpy())
     assert np.max(np.abs(diag[:GROUP].cpu().numpy() - o.diag) / np.abs(o.diag)) <= 1e-10
     assert np.array_equal(p[:GROUP], o.perm)
+
+
+def test_empty_matrix_unaligned_views_and_two_callers(M):
+    import threading
+    r = M.mdet_logdet_device(torch.empty((0, 0), dtype=torch.float64, device="cuda"), flags=M.FLAG_GENERAL)
+    assert r.status == 0 and r.logabsdet == 0.0 and r.sign == 1
+    # views whose rows are not 16-byte aligned are factored in a copy even with overwrite = 1;
+    # block sizes are rounded up to multiples of 64
+    for n, bs, dt in [(130, 100, np.float64), (500, 0, np.float32), (257, 64, np.float32)]:
+        a = gaussian(n + bs, n, dt)
+        big = torch.zeros((n, n + 6), dtype=dev(a).dtype, device="cuda")
+        v = big[:, :n]
+        v.copy_(dev(a))
+        r0 = M.mdet_logdet_device(v, block_size=bs, flags=M.FLAG_GENERAL)
+        assert np.array_equal(v.cpu().numpy(), a)
+        r1 = M.mdet_logdet_device(v, block_size=bs, flags=M.FLAG_GENERAL, overwrite=True)
+        o = oracle.lu_logdet(a.astype(np.float64))
+        assert r0.status == r1.status == 0 and r0.logabsdet == r1.logabsdet and r0.sign == r1.sign == o.sign
+        assert rel(r0.logabsdet, o.logabsdet) <= TOL["f64" if dt is np.float64 else "f32"]
+    # two host threads on one device: calls are serialised inside the library
+    a = gaussian(15, 1500)
+    ad = dev(a)
+    o = oracle.lu_logdet(a)
+    out = [None, None]
+
+    def work(i):
+        for _ in range(4):
+            out[i] = M.mdet_logdet_device(ad, block_size=256, flags=M.FLAG_GENERAL)
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert out[0].logabsdet == out[1].logabsdet and out[0].sign == out[1].sign == o.sign
+    assert rel(out[0].logabsdet, o.logabsdet) <= TOL["f64"]
