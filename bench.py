@@ -159,6 +159,29 @@ def kernel_report(reps=5):
                     "shape": f"m={m} w={w}", "ms": ms,
                     "note": "both launches timed together; each kernel's own duration is in the "
                             "rocprofv3 summary of this command (64 dependent pivot steps, latency-bound)"})
+    # a leaf of a general matrix: P A = L D U of the 64 x 64 block, then the rows below it in
+    # both triangles (one solve launch)
+    for m in (32768,):
+        w = 64
+        g = torch.Generator(device="cuda").manual_seed(13)
+        src = torch.randn(2, m, w, dtype=torch.float64, device="cuda", generator=g) * 0.01
+        src[0, :w] += torch.diag(torch.linspace(1.0, 3.0, w, dtype=torch.float64, device="cuda"))[torch.randperm(
+            w, generator=torch.Generator().manual_seed(13)).cuda()]
+        panel = torch.empty_like(src)
+        dv = torch.zeros(w, dtype=torch.float64, device="cuda")
+        di = torch.zeros_like(dv)
+        pm = torch.zeros(w, dtype=torch.int32, device="cuda")
+        flags = torch.zeros(32 + 16384, dtype=torch.uint8, device="cuda")
+
+        def prep():
+            panel.copy_(src)
+            flags.zero_()
+            flags[:16] = 255
+        ms = timed(lambda: M.mdet_step_panel_factor_general(panel[0], panel[1], w, dv, di, pm, flags), prep=prep)
+        out.append({"kernel": "leaf_lu_kernel + leaf_solve_general_kernel", "dtype": "f64",
+                    "shape": f"m={m} w={w} (both triangles)", "ms": ms,
+                    "note": "both launches timed together; each kernel's own duration is in the "
+                            "rocprofv3 summary of this command (64 dependent pivot steps, latency-bound)"})
     for n in (196608,):          # one workgroup per block column; here a single column
         dvec = torch.rand(n, dtype=torch.float64, device="cuda") + 0.5
         res = torch.zeros(8, dtype=torch.float64, device="cuda")

@@ -357,6 +357,24 @@ int mdet_step_panel_factor_pivoted(int32_t dtype, void* P, int64_t ld, int64_t m
                                    void* d, void* dinv, int32_t* perm, int64_t pivot_index0,
                                    void* flags, void* stream);
 
+/* One block column of a general matrix (MDET_FLAG_GENERAL; Sec. 2.2, Eq. 1 and Alg. 1:
+ * M = P L U, pivoting inside a block).  The block column is given as two panels of m rows
+ * and w <= m columns with the same leading dimension, both DEVICE pointers: P points at
+ * the diagonal entry of the entries on and below the diagonal, Q at the same place of the
+ * transposed entries above it (Q[i][j] = M[j][i] for i > j; its diagonal and everything
+ * above the diagonal of either panel is not referenced).  Q - P must be a non-zero multiple
+ * of 16 bytes.  On return P holds L (unit lower, strictly below the diagonal) and D on the
+ * diagonal, Q holds U^T (unit upper U, M[perm] = L D U on these columns), the rows of every
+ * 64-row group left in input order for the columns left of the group; d[w], dinv[w] the
+ * pivots and their reciprocals; perm[w] the row order as for
+ * mdet_step_panel_factor_pivoted.  flags: DEVICE pointer to 32 + 2 * 8192 bytes; uint64
+ * [0] and [1] preset to all-ones receive the first bad pivot and its kind as above, [2]
+ * preset to zero receives the number of 64-row leaves whose row order is an odd
+ * permutation (the sign of P is -1 if that number is odd); the rest is scratch. */
+int mdet_step_panel_factor_general(int32_t dtype, void* P, void* Q, int64_t ld, int64_t m,
+                                   int64_t w, void* d, void* dinv, int32_t* perm,
+                                   int64_t pivot_index0, void* flags, void* stream);
+
 /* sum log|d_j|, sign and negative count of d[0..n) -> out[0] = logabsdet (double),
  * out[1] = sign (as double), out[2] = negative count (as double).  out: DEVICE
  * pointer to at least 8 doubles (the tail is scratch). */

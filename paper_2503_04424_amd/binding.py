@@ -73,6 +73,7 @@ EXPORTS = [
     "mdet_logdet_provider", "mdet_logdet_file", "mdet_host_layout_offset", "mdet_paper_block_rule",
     "mdet_paper_fma_count", "mdet_step_schur_update", "mdet_step_panel_factor",
     "mdet_step_panel_factor_pivoted",
+    "mdet_step_panel_factor_general",
     "mdet_step_logdet_reduce", "mdet_strerror", "mdet_version",
     "mdet_sequence_workspace_query", "mdet_principal_logdets", "mdet_flodance_fit",
     "mdet_flodance_eval",
@@ -109,6 +110,7 @@ def load():
     L.mdet_step_schur_update.argtypes = [i32, vp, i64, vp, i64, vp, i64, vp, i64, i64, i64, i32, vp]
     L.mdet_step_panel_factor.argtypes = [i32, vp, i64, i64, i64, vp, vp, i64, vp, vp]
     L.mdet_step_panel_factor_pivoted.argtypes = [i32, vp, i64, i64, i64, vp, vp, vp, i64, vp, vp]
+    L.mdet_step_panel_factor_general.argtypes = [i32, vp, vp, i64, i64, i64, vp, vp, vp, i64, vp, vp]
     L.mdet_step_logdet_reduce.argtypes = [i32, vp, i64, vp, vp]
     L.mdet_sequence_workspace_query.argtypes = [i64, i64, i32, C.POINTER(u64)]
     L.mdet_principal_logdets.argtypes = [i32, vp, i64, vp, vp, u64, vp]
@@ -413,6 +415,21 @@ def mdet_step_panel_factor_pivoted(panel, w, d, dinv, perm, flags_buf, pivot_ind
     m = panel.shape[0]
     st = load().mdet_step_panel_factor_pivoted(_dtype_code(panel.dtype), panel.data_ptr(), panel.stride(0),
                                                m, int(w), d.data_ptr(), dinv.data_ptr(),
+                                               _perm_ptr(perm, int(w), True), int(pivot_index0),
+                                               flags_buf.data_ptr(), _stream_handle(stream))
+    if st != Status.OK:
+        raise MemdetError(st)
+
+
+def mdet_step_panel_factor_general(lower, upper_t, w, d, dinv, perm, flags_buf, pivot_index0=0, stream=None) -> None:
+    """One block column of a general matrix: ``lower`` (m x >= w, entries on and below the
+    diagonal) and ``upper_t`` (same shape and row stride, the transposed entries above it);
+    flags_buf: 32 + 16384 bytes, uint64 [0], [1] all-ones and [2] zero on entry."""
+    m = lower.shape[0]
+    if upper_t.shape[0] != m or upper_t.stride(0) != lower.stride(0) or upper_t.dtype != lower.dtype:
+        raise ValueError("the two panels must have the same shape, row stride and dtype")
+    st = load().mdet_step_panel_factor_general(_dtype_code(lower.dtype), lower.data_ptr(), upper_t.data_ptr(),
+                                               lower.stride(0), m, int(w), d.data_ptr(), dinv.data_ptr(),
                                                _perm_ptr(perm, int(w), True), int(pivot_index0),
                                                flags_buf.data_ptr(), _stream_handle(stream))
     if st != Status.OK:

@@ -151,6 +151,7 @@ struct Launcher {
   // entry (j, i) of the matrix, in a second array of the same shape.  Every pointer the
   // driver passes refers to the first array; 0 = symmetric matrix, no second array.
   int64_t qoff = 0;
+  T* linv_u = nullptr;        // with qoff: the inverses of the sub-blocks of a leaf's U^T (linv: of its L)
   // Two arrays of n x wld elements (or none): while a block column is factored its rows
   // are also stored scaled by the pivots, W = L D, so that the updates that use the
   // column read their left operand ready-made (MDET_FLAG_SCALED_COPY).  Column k uses
@@ -326,9 +327,9 @@ struct Launcher {
     if (w <= LEAF && qoff != 0) {
       // P A = L D U of the leaf, then the rows below it in both halves: the lower half
       // against U^T, the transposed upper half against L with the leaf's row order
-      if (spd || !perm || !l10) return MDET_EINVAL;
+      if (spd || !perm || !linv_u) return MDET_EINVAL;
       T* linvL = linv;
-      T* linvU = linv + LEAF * SUB;
+      T* linvU = linv_u;
       hipLaunchKernelGGL((leaf_lu_kernel<T>), dim3(1), dim3(FACTOR_THREADS), 0, st, P, P + qoff, ld, (int)w,
                          dvec + d0, dinv + d0, linvL, linvU, perm + d0, (long long)d0, flags);
       fail->check(hipGetLastError());
@@ -668,6 +669,7 @@ static void bind_small(Launcher<T>& L, char* base, const SmallArea& sa) {
   L.dinv = (T*)(base + sa.dinv);
   L.linv = (T*)(base + sa.linv);
   L.l10 = (T*)(base + sa.l10);
+  L.linv_u = L.linv + LEAF * SUB;      // linv is two arrays here
   L.flags = (DevFlags*)(base + sa.flags);
   L.perm = sa.total > sa.perm ? (int*)(base + sa.perm) : nullptr;
   // two workgroups of the trailing update fit one compute unit (registers and LDS)
@@ -1598,6 +1600,43 @@ int mdet_step_panel_factor_pivoted(int32_t dtype, void* P, int64_t ld, int64_t m
                                    void* stream) {
   if (!perm) return MDET_EINVAL;
   return step_panel_factor(dtype, P, ld, m, w, d, dinv, perm, pivot_index0, flags, stream);
+}
+
+extern "C++" {
+template <typename T>
+static int step_panel_factor_general(T* P, T* Q, int64_t ld, int64_t m, int64_t w, T* d, T* dinv, int32_t* perm,
+                                     int64_t pivot_index0, void* flags, hipStream_t st) {
+  constexpr int vec = 16 / (int)sizeof(T);
+  const ptrdiff_t bytes = (const char*)Q - (const char*)P;
+  if (ld % vec || ((uintptr_t)P & 15u) || bytes % 16 != 0 || bytes == 0) return MDET_EINVAL;
+  HipFail fail;
+  Launcher<T> L;
+  L.fail = &fail;
+  L.dvec = d - pivot_index0;
+  L.dinv = dinv - pivot_index0;
+  L.perm = perm - pivot_index0;
+  L.flags = (DevFlags*)flags;
+  L.linv = (T*)((char*)flags + 32);
+  L.linv_u = L.linv + LEAF * SUB;
+  L.qoff = bytes / (ptrdiff_t)sizeof(T);
+  const int rc = L.factor_cols(st, P, ld, m, w, pivot_index0);
+  if (!fail.ok()) return MDET_EHIP;
+  return rc;
+}
+}  // extern "C++"
+
+int mdet_step_panel_factor_general(int32_t dtype, void* P, void* Q, int64_t ld, int64_t m, int64_t w, void* d,
+                                   void* dinv, int32_t* perm, int64_t pivot_index0, void* flags,
+                                   void* stream) {
+  if (!P || !Q || !d || !dinv || !perm || !flags || m < 0 || w < 0 || w > m || ld < w) return MDET_EINVAL;
+  if (pivot_index0 < 0 || pivot_index0 + w > INT32_MAX) return MDET_EINVAL;
+  if (dtype == MDET_F64)
+    return step_panel_factor_general<double>((double*)P, (double*)Q, ld, m, w, (double*)d, (double*)dinv, perm,
+                                             pivot_index0, flags, (hipStream_t)stream);
+  if (dtype == MDET_F32)
+    return step_panel_factor_general<float>((float*)P, (float*)Q, ld, m, w, (float*)d, (float*)dinv, perm,
+                                            pivot_index0, flags, (hipStream_t)stream);
+  return MDET_EINVAL;
 }
 
 int mdet_step_logdet_reduce(int32_t dtype, const void* d, int64_t n, double* out, void* stream) {

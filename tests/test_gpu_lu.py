@@ -108,6 +108,51 @@ def stored_factors(s, perm):
     return L, U
 
 
+# ---------------------------------------------------------------------------
+# one block column through the single-step entry point
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("m,w", [(64, 64), (40, 40), (1, 1), (200, 64), (333, 128), (1000, 256), (100, 100)])
+def test_block_column_factor_of_a_general_matrix(M, dtype, m, w):
+    npdt = np.float64 if dtype == "f64" else np.float32
+    a = shuffled_dominant(m * 7 + w, m, npdt)
+    ld = (m + 3) // 4 * 4
+    both = torch.zeros((2, m, ld), dtype=dev(a).dtype, device="cuda")
+    lower, upper_t = both[0, :, :m], both[1, :, :m]
+    lower.copy_(dev(a))
+    upper_t.copy_(dev(np.ascontiguousarray(a.T)))
+    d = torch.zeros(w, dtype=lower.dtype, device="cuda")
+    dinv = torch.zeros_like(d)
+    perm = torch.full((w,), -1, dtype=torch.int32, device="cuda")
+    flags = torch.zeros(4 + 2048, dtype=torch.int64, device="cuda")
+    flags[:2] = -1
+    M.mdet_step_panel_factor_general(lower, upper_t, w, d, dinv, perm, flags)
+    torch.cuda.synchronize()
+    assert int(flags[0].item()) == -1
+    pw = perm.cpu().numpy().astype(np.int64)
+    o = oracle.lu_logdet(a.astype(np.float64), want_LU=True)
+    assert o.status == 0 and np.array_equal(pw, o.perm[:w])
+    # sign of the row order of these w rows
+    assert (-1) ** int(flags[2].item()) == round(np.linalg.det(np.eye(w)[pw]))
+    tol = 1e-11 if dtype == "f64" else 2e-4
+    dd = d.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(dd - o.diag[:w]) / np.abs(o.diag[:w])) < tol
+    assert np.max(np.abs(dinv.cpu().numpy().astype(np.float64) * o.diag[:w] - 1)) < tol
+    # L: the stored rows of a group are in input order for the columns left of the group
+    got = lower.cpu().numpy().astype(np.float64)
+    for g0 in range(GROUP, m, GROUP):
+        g1 = min(m, g0 + GROUP)
+        left = min(g0, w)
+        got[g0:g1, :left] = got[o.perm[g0:g1], :left]
+    i, j = np.indices((m, w))
+    assert np.max(np.abs(got[:, :w] - o.LU[:, :w])[i > j], initial=0.0) < tol
+    assert np.max(np.abs(np.diag(got)[:w] - o.diag[:w]) / np.abs(o.diag[:w])) < tol
+    # U^T: columns of the matrix are not exchanged; U = D U~
+    gq = upper_t.cpu().numpy().astype(np.float64)
+    want_ut = (o.LU[:w, :] / o.diag[:w, None]).T                     # (m, w): U~[j][i] at [i][j]
+    assert np.max(np.abs(gq[:, :w] - want_ut)[i > j], initial=0.0) < tol
+
+
 @pytest.mark.parametrize("n,bs", [(1, 64), (2, 64), (63, 64), (64, 64), (65, 64), (130, 64), (512, 128),
                                   (1000, 256), (777, 64), (1536, 512), (2048, 1024), (1300, 192)])
 def test_shuffled_rows_are_found_again(M, n, bs):
