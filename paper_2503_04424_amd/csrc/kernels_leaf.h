@@ -605,11 +605,18 @@ __global__ __launch_bounds__(FACTOR_THREADS) void leaf_factor_pivoted_kernel(
 // leaf_solve_kernel: rows below in Pl are solved against U^T, rows below in Qu against L
 // with the leaf's row order as their column gather), perm[j] = pivot0 + (row of the leaf
 // taken at step j); flags->odd_leaves is raised by one if that order is an odd permutation.
-template <typename T>
-__global__ __launch_bounds__(FACTOR_THREADS) void leaf_lu_kernel(
+// NW wavefronts (4, 8 or 16): wavefront q holds columns q CW .. q CW + CW - 1, CW = 64 / NW.
+// A step costs its wavefront about 60 clocks per column held (two v_readlane of about 20
+// clocks each, the multiply-add and the live-row select), which is most of the step with
+// 16 columns; 16 wavefronts of 4 columns each spread that over the compute unit's SIMDs.
+constexpr int LU_WAVES = 16;   // n = 8192 as a general matrix: 15.02 ms with 4, 13.97 with 8, 13.56 with 16
+template <typename T, int NW>
+__global__ __launch_bounds__(64 * NW) void leaf_lu_kernel(
     T* __restrict__ Pl, T* __restrict__ Qu, int64_t ld, int w, T* __restrict__ dvec,
     T* __restrict__ dinv, T* __restrict__ linvL, T* __restrict__ linvU, int* __restrict__ perm,
     long long pivot0, DevFlags* flags) {
+  constexpr int CW = LEAF / NW;          // columns per wavefront
+  constexpr int NT = 64 * NW;            // threads
   __shared__ T S[FACTOR_LDS_ELEMS];      // the rows in their final order: L below, D U on and above
   __shared__ T Lm[FACTOR_LDS_ELEMS];     // multipliers by input row; afterwards U^T
   __shared__ T lbuf[2][LEAF];            // a step's multipliers, for the other wavefronts
@@ -619,11 +626,11 @@ __global__ __launch_bounds__(FACTOR_THREADS) void leaf_lu_kernel(
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l16 = lane & 15;
-  const int c0 = wave * SUB;
-  constexpr int PER = LEAF * LEAF / FACTOR_THREADS;
-  T a[SUB];
+  const int c0 = wave * CW;
+  constexpr int PER = LEAF * LEAF / NT;
+  T a[CW];
 #pragma unroll
-  for (int k = 0; k < SUB; ++k) {
+  for (int k = 0; k < CW; ++k) {
     // (r, c) of the lower half and (c, r) of the upper half come from the same place of
     // the two arrays: row max(r, c), column min(r, c)
     const int r = lane, c = c0 + k;
@@ -632,16 +639,16 @@ __global__ __launch_bounds__(FACTOR_THREADS) void leaf_lu_kernel(
                             : (r == c ? T(1) : T(0));
   }
 #pragma unroll
-  for (int q = 0; q < PER; ++q) Lm[((q * FACTOR_THREADS + tid) >> 6) * LEAF_PAD + (tid & 63)] = T(0);
+  for (int q = 0; q < PER; ++q) Lm[((q * NT + tid) >> 6) * LEAF_PAD + (tid & 63)] = T(0);
   if (tid < LEAF) ord[tid] = tid;
   __syncthreads();                            // Lm is clear before the first multiplier lands in it
   unsigned long long taken = 0ull;            // the same in every lane and wavefront
   int mypos = lane;                           // where this lane's row ends
 #pragma unroll 1
-  for (int jb = 0; jb < LEAF / SUB; ++jb) {
+  for (int jb = 0; jb < NW; ++jb) {
 #pragma unroll
-    for (int jj = 0; jj < SUB; ++jj) {
-      const int j = jb * SUB + jj;
+    for (int jj = 0; jj < CW; ++jj) {
+      const int j = jb * CW + jj;
       if (j < w) {
         if (wave == jb) {
           const T cj = a[jj];
@@ -664,7 +671,7 @@ __global__ __launch_bounds__(FACTOR_THREADS) void leaf_lu_kernel(
         const bool live = lane < w && !((taken >> lane) & 1ull);
         if (wave >= jb) {
 #pragma unroll
-          for (int k = 0; k < SUB; ++k) {
+          for (int k = 0; k < CW; ++k) {
             if (wave > jb || k > jj) {
               const T pv = lane_value(a[k], p);
               a[k] = live ? fma(-l, pv, a[k]) : a[k];
@@ -676,13 +683,13 @@ __global__ __launch_bounds__(FACTOR_THREADS) void leaf_lu_kernel(
   }
   // every row to the place of its turn; its entries left of the diagonal are replaced below
 #pragma unroll
-  for (int k = 0; k < SUB; ++k) S[mypos * LEAF_PAD + c0 + k] = a[k];
+  for (int k = 0; k < CW; ++k) S[mypos * LEAF_PAD + c0 + k] = a[k];
   __syncthreads();
   {
     T v[PER];
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
-      const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
+      const int e = q * NT + tid, r = e >> 6, c = e & 63;
       const int from = r < w ? ord[r] : r;
       v[q] = c < r ? Lm[from * LEAF_PAD + c] : S[r * LEAF_PAD + c];
     }
@@ -691,7 +698,7 @@ __global__ __launch_bounds__(FACTOR_THREADS) void leaf_lu_kernel(
     // transpose with a unit diagonal
 #pragma unroll
     for (int q = 0; q < PER; ++q) {
-      const int e = q * FACTOR_THREADS + tid, r = e >> 6, c = e & 63;
+      const int e = q * NT + tid, r = e >> 6, c = e & 63;
       if (c < r) S[r * LEAF_PAD + c] = v[q];
       T u = r == c ? T(1) : T(0);
       if (c > r && c < w) u = v[q] * fast_rcp(S[r * LEAF_PAD + r]);
@@ -699,13 +706,15 @@ __global__ __launch_bounds__(FACTOR_THREADS) void leaf_lu_kernel(
     }
   }
   __syncthreads();
-  for (int e = tid; e < LEAF * LEAF; e += FACTOR_THREADS) {
+  for (int e = tid; e < LEAF * LEAF; e += NT) {
     const int r = e >> 6, c = e & 63;
     if (r < w && c <= r) Pl[(int64_t)r * ld + c] = S[r * LEAF_PAD + c];
     if (r < w && c < r) Qu[(int64_t)r * ld + c] = Lm[r * LEAF_PAD + c];
   }
-  leaf_invert_sub<T>(S, linvL, wave, l16);
-  leaf_invert_sub<T>(Lm, linvU, wave, l16);
+  if (wave < NSUB) {
+    leaf_invert_sub<T>(S, linvL, wave, l16);
+    leaf_invert_sub<T>(Lm, linvU, wave, l16);
+  }
   if (wave == 0) {
     const T myd = S[lane * LEAF_PAD + lane];
     const bool zero = myd == T(0);

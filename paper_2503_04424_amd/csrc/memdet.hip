@@ -330,8 +330,8 @@ struct Launcher {
       if (spd || !perm || !linv_u) return MDET_EINVAL;
       T* linvL = linv;
       T* linvU = linv_u;
-      hipLaunchKernelGGL((leaf_lu_kernel<T>), dim3(1), dim3(FACTOR_THREADS), 0, st, P, P + qoff, ld, (int)w,
-                         dvec + d0, dinv + d0, linvL, linvU, perm + d0, (long long)d0, flags);
+      hipLaunchKernelGGL((leaf_lu_kernel<T, LU_WAVES>), dim3(1), dim3(64 * LU_WAVES), 0, st, P, P + qoff, ld,
+                         (int)w, dvec + d0, dinv + d0, linvL, linvU, perm + d0, (long long)d0, flags);
       fail->check(hipGetLastError());
       ++launches;
       fma += ((double)w * w * w - (double)w) / 3.0;
