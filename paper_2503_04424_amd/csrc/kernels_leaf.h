@@ -17,8 +17,13 @@
 //                      W = X D into a second array, for the rows from `wfrom` on:
 //                      the operand of the Schur updates with the scaling applied,
 //                      rounded as the update kernels round l * d.
+// leaf_solve_general_kernel : the same for both triangles of a general matrix in one
+//                      launch (rows of the lower one against U^T, rows of the transposed
+//                      upper one against L with the leaf's row order as column gather).
+// transpose_strict_kernel : the entries above the diagonal of a general matrix into their
+//                      transposed store, and back.
 //
-// Both work on 16-column sub-blocks: the sequential part (elimination inside a
+// leaf_factor_kernel and leaf_solve_kernel work on 16-column sub-blocks: the sequential part (elimination inside a
 // 16 x 16 diagonal sub-block) runs on the vector ALUs with one matrix row per lane,
 // everything else (updates inside the leaf, the substitution against already
 // solved sub-blocks) is 16 x 16 x 16 products on the matrix cores.  The loops over

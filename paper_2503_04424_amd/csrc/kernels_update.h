@@ -21,6 +21,9 @@
 // Also here, because they end with the same hand-over of the next leaf:
 // leaf_update_kernel (K = 64, one shot from LDS) and leaf_pair_kernel (a leaf's solve,
 // the K = 64 update by it and the next leaf's factorisation in one launch).
+//
+// The *_general_kernel names run the same bodies for a general matrix (Sec. 2.2, Eq. 1:
+// M = P L U) kept as two lower-triangular arrays, one row of workgroups per array.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
