@@ -6,10 +6,15 @@
  * budget: the symmetric case ("case II") of the paper's memory-constrained
  * algorithm (Sec. 2.2: block Schur-complement recursion of Eq. 1, stored-triangle
  * processing and diagonal scaling for LDL^T; App. D: inputs "matrix, maximum
- * memory c", outputs "l = log|det|, sigma = sign").  No pivoting is done: D is
+ * memory c", outputs "l = log|det|, sigma = sign").  By default no pivoting is done: D is
  * diagonal, L unit lower triangular, and
  *
  *      logabsdet = sum_j log|d_j| ,   sign = prod_j sgn(d_j) .
+ *
+ * Flags select the other forms of the method: pivoting on the diagonal inside a block
+ * (MDET_FLAG_PIVOT), the Cholesky form for positive-definite matrices
+ * (MDET_FLAG_ASSUME_SPD), the LU form for general matrices (MDET_FLAG_GENERAL), and
+ * storage narrower than the arithmetic (MDET_FLAG_COMPUTE_F64).
  *
  * Conventions common to every entry point
  *  - Only the LOWER triangle of the matrix is read.  Element (i, j), i >= j.
@@ -35,8 +40,8 @@
 extern "C" {
 #endif
 
-/* MDET_F16 (IEEE binary16) and MDET_BF16 are storage formats only: accepted by
- * mdet_logdet_device together with MDET_FLAG_COMPUTE_F64, nowhere else. */
+/* MDET_F16 (IEEE binary16) and MDET_BF16 are storage formats only: accepted together with
+ * MDET_FLAG_COMPUTE_F64, not without it. */
 typedef enum { MDET_F32 = 0, MDET_F64 = 1, MDET_F16 = 2, MDET_BF16 = 3 } mdet_dtype;
 
 typedef enum {
@@ -94,22 +99,30 @@ typedef struct mdet_params {
                                      (results are bit-identical either way)        */
 #define MDET_FLAG_FORCE_OUT_OF_CORE 2u /* host entry points: stream blocks even if the
                                      whole triangle would fit in the budget         */
-#define MDET_FLAG_COMPUTE_F64 8u  /* dtype = MDET_F32, MDET_F16 or MDET_BF16,
-                                     mdet_logdet_device only: the matrix is STORED in
-                                     that format and every arithmetic step
+#define MDET_FLAG_COMPUTE_F64 8u  /* dtype = MDET_F32, MDET_F16 or MDET_BF16: the matrix is
+                                     STORED in that format and every arithmetic step
                                      runs in fp64 on the exactly widened values (App. C,
                                      data-precision pipeline, stage 3: whatever precision
                                      the matrix was stored in, the log-determinant is
-                                     computed in 64 bit).  The library works on an fp64
-                                     copy in its workspace (n * ld_padded * 8 bytes,
-                                     counted against the budget; the input is never
-                                     modified) and diag receives n DOUBLES.  The host
-                                     and provider entry points return MDET_EINVAL.     */
-#define MDET_FLAG_PROFILE 4u      /* bracket every launch of the trailing-update kernel
-                                     (the 128 x 128-block one that does the bulk of the
-                                     work; small updates run a 64 x 64-block variant
-                                     that is not counted) with HIP events on its own
-                                     stream and report the sums in
+                                     computed in 64 bit).  diag receives n DOUBLES.
+                                     mdet_logdet_device works on an fp64 copy in its
+                                     workspace (n * ld_padded * 8 bytes, counted against
+                                     the budget; the input is never modified).  The host,
+                                     provider and file entry points move the original
+                                     blocks over the host link in the stored width and
+                                     widen them on the device (a staging buffer of at most
+                                     64 MiB, counted against the budget); the factored
+                                     block columns of a streamed run are fp64 and never go
+                                     back into the matrix: they go to host_scratch (or the
+                                     scratch file), whatever `overwrite` says, and
+                                     mdet_workspace_query reports the fp64 layout's size
+                                     as host_bytes.                                    */
+#define MDET_FLAG_PROFILE 4u      /* bracket every launch of the two trailing-update
+                                     kernels (128 x 128 blocks for the bulk of the work,
+                                     64 x 64 blocks for updates too small to fill the
+                                     device) with HIP events on its own stream and
+                                     report, per kernel, launches, summed durations and
+                                     flops, and the union of all the intervals, in
                                      result->t_trailing_update etc.                 */
 #define MDET_FLAG_SCALED_COPY 32u /* speed for memory: 2 n block_size further elements of
                                      device workspace hold, for the block column being
@@ -200,7 +213,9 @@ typedef struct mdet_result {
   double t_total;              /* seconds, wall clock of the call                    */
   uint64_t bytes_h2d;          /* host -> device bytes moved                         */
   uint64_t bytes_d2h;          /* device -> host bytes moved                         */
-  uint64_t dev_bytes_high_water; /* device bytes in use at the peak (<= budget)      */
+  uint64_t dev_bytes_high_water; /* highest workspace offset the call used, in bytes
+                                    (the arena is carved group by group; <= budget and
+                                    <= mdet_plan's dev_bytes_needed)                  */
   uint64_t kernel_launches;
   /* filled when MDET_FLAG_PROFILE is set: the Schur updates of the trailing matrix */
   uint64_t trailing_update_launches;
@@ -210,6 +225,15 @@ typedef struct mdet_result {
      was busy in each direction (sum of the copies' event-timed durations, seconds) */
   double t_h2d;
   double t_d2h;
+  /* MDET_FLAG_PROFILE, continued: the same three figures for the 64 x 64-block variant of
+     the trailing-update kernel (updates too small to fill the device with 128 x 128
+     blocks), and the time during which at least one trailing-update launch of either
+     kernel was running (the union of the launches' intervals: launches on the library's
+     two compute streams overlap, so the sums above count some time twice) */
+  uint64_t trailing_update64_launches;
+  double t_trailing_update64;
+  double trailing_update64_flops;
+  double t_trailing_update_busy;
 } mdet_result;
 
 /*
@@ -220,7 +244,8 @@ typedef struct mdet_result {
  * write the block row-major with leading dimension `ld` elements into the HOST
  * buffer `dst` (pinned memory owned by the library) and return 0; any other
  * return value aborts the call with MDET_EPROVIDER.  For diagonal blocks only the
- * lower triangle need be filled.
+ * lower triangle need be filled.  Every block is asked for exactly once, block columns in
+ * ascending order within a resident group, elements of params->dtype.
  */
 typedef int (*mdet_block_provider)(void* user, int64_t bi, int64_t bj, int64_t rows,
                                    int64_t cols, void* dst, int64_t ld);
@@ -285,9 +310,12 @@ int mdet_logdet_device(const mdet_params* params, void* dA, int64_t ld,
 int mdet_logdet_host(const mdet_params* params, void* hA, mdet_result* result,
                      void* diag);
 
-/* As mdet_logdet_host, but blocks are fetched through `provider` (e.g. from disk)
- * into library-owned host memory laid out as above (pinned if that much can be pinned).
- * overwrite is ignored. */
+/* As mdet_logdet_host, but the original blocks are fetched through `provider` (e.g. from
+ * disk), each when the schedule first needs it, into one of two pinned buffers of one block
+ * and from there to the device: host memory holds no copy of the matrix.  Only a run that
+ * streams keeps its factored block columns in host memory (params->host_scratch, or memory the
+ * library allocates: mdet_workspace_query's host_bytes with overwrite = 0).  overwrite is
+ * ignored. */
 int mdet_logdet_provider(const mdet_params* params, mdet_block_provider provider,
                          void* user, mdet_result* result, void* diag);
 
@@ -419,6 +447,26 @@ int mdet_flodance_fit(const double* ell, int64_t len, int64_t d, int64_t n0, int
  * doubles that mdet_flodance_fit wrote.  n_values, out: `count` doubles each. */
 int mdet_flodance_eval(const double* coef, int32_t q, const double* n_values, int64_t count,
                        double* out, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Measuring sticks for the benchmark (asynchronous, enqueue only; DEVICE pointers).
+ * ---------------------------------------------------------------------- */
+
+/* A plain copy of `bytes` bytes (a multiple of 16, both pointers 16-byte aligned) by one
+ * kernel: reads `bytes`, writes `bytes`.  The ratio between what a profiler's memory
+ * counters report for it and these known figures calibrates the same counters for the
+ * kernels of the path (the traffic figures beside the roofline of the trailing update of
+ * Sec. 2.2). */
+int mdet_step_copy(void* dst, const void* src, uint64_t bytes, void* stream);
+
+/* Matrix-core instructions on registers only (16 x 16 x 4 products of `dtype`, MDET_F64 or
+ * MDET_F32, four accumulators in turn): `workgroups` workgroups of four wavefronts, `iters`
+ * rounds of 16 products per wavefront.  *flop receives the flops of the launch (2048 per
+ * product); `out` needs 65536 elements of dtype (receives values that keep the compiler
+ * from dropping the work).  Time it with events: the rate is the matrix pipe's measured
+ * ceiling for the Schur update S <- S - C B of Sec. 2.2. */
+int mdet_step_mfma_peak(int32_t dtype, int32_t workgroups, int32_t iters, void* out, double* flop,
+                        void* stream);
 
 const char* mdet_strerror(int status);
 const char* mdet_version(void);

@@ -51,6 +51,8 @@ class _Result(C.Structure):
         ("kernel_launches", C.c_uint64), ("trailing_update_launches", C.c_uint64),
         ("t_trailing_update", C.c_double), ("trailing_update_flops", C.c_double),
         ("t_h2d", C.c_double), ("t_d2h", C.c_double),
+        ("trailing_update64_launches", C.c_uint64), ("t_trailing_update64", C.c_double),
+        ("trailing_update64_flops", C.c_double), ("t_trailing_update_busy", C.c_double),
     ]
 
 
@@ -76,7 +78,7 @@ EXPORTS = [
     "mdet_step_panel_factor_general",
     "mdet_step_logdet_reduce", "mdet_strerror", "mdet_version",
     "mdet_sequence_workspace_query", "mdet_principal_logdets", "mdet_flodance_fit",
-    "mdet_flodance_eval",
+    "mdet_flodance_eval", "mdet_step_copy", "mdet_step_mfma_peak",
 ]
 
 _lib = None
@@ -116,6 +118,8 @@ def load():
     L.mdet_principal_logdets.argtypes = [i32, vp, i64, vp, vp, u64, vp]
     L.mdet_flodance_fit.argtypes = [vp, i64, i64, i64, i64, i32, vp, vp, u64, vp]
     L.mdet_flodance_eval.argtypes = [vp, i32, vp, i64, vp, vp]
+    L.mdet_step_copy.argtypes = [vp, vp, u64, vp]
+    L.mdet_step_mfma_peak.argtypes = [i32, i32, i32, vp, C.POINTER(C.c_double), vp]
     L.mdet_strerror.argtypes = [C.c_int]
     L.mdet_strerror.restype = C.c_char_p
     L.mdet_version.restype = C.c_char_p
@@ -164,6 +168,10 @@ class LogdetResult:
     trailing_update_flops: float = 0.0
     t_h2d: float = 0.0
     t_d2h: float = 0.0
+    trailing_update64_launches: int = 0
+    t_trailing_update64: float = 0.0
+    trailing_update64_flops: float = 0.0
+    t_trailing_update_busy: float = 0.0
 
 
 @dataclass
@@ -225,7 +233,9 @@ def _result(status: int, r: _Result) -> LogdetResult:
                         r.block_size_used, r.num_blocks, bool(r.out_of_core), r.num_superpanels,
                         r.flops, r.t_total, r.bytes_h2d, r.bytes_d2h, r.dev_bytes_high_water,
                         r.kernel_launches, r.hip_error, r.trailing_update_launches,
-                        r.t_trailing_update, r.trailing_update_flops, r.t_h2d, r.t_d2h)
+                        r.t_trailing_update, r.trailing_update_flops, r.t_h2d, r.t_d2h,
+                        r.trailing_update64_launches, r.t_trailing_update64, r.trailing_update64_flops,
+                        r.t_trailing_update_busy)
 
 
 _SOFT = (Status.OK, Status.ESINGULAR, Status.ENONFINITE, Status.ENOTPOSDEF)
@@ -320,12 +330,21 @@ def mdet_logdet_host(packed, n, block_size, mem_budget=0, overwrite=True, flags=
                 host_scratch.data_ptr() if host_scratch is not None else None,
                 host_scratch.numel() * host_scratch.element_size() if host_scratch is not None else 0,
                 perm=_perm_ptr(perm, n, False))
-    b = (int(block_size) + 63) // 64 * 64
+    # the block size the library will use (0 = its own choice), for the size check only
+    info = _PlanInfo()
+    st = load().mdet_plan(C.byref(p), 0, C.byref(info))
+    if st != Status.OK:
+        if raise_on_error:
+            raise MemdetError(st)
+        return _result(st, _Result())
+    b = info.block_size_used
     need = mdet_host_layout_offset(n, b, (n + b - 1) // b) if n > 0 else 0
     if packed.numel() < need:
         raise ValueError(f"packed layout needs {need} elements")
-    if diag is not None and (diag.dtype != packed.dtype or diag.numel() < n or diag.is_cuda):
-        raise ValueError("diag must be a host tensor of n elements of the matrix dtype")
+    import torch
+    diag_dtype = torch.float64 if (flags & FLAG_COMPUTE_F64) else packed.dtype
+    if diag is not None and (diag.dtype != diag_dtype or diag.numel() < n or diag.is_cuda):
+        raise ValueError("diag must be a host tensor of n elements of the arithmetic's dtype")
     r = _Result()
     st = load().mdet_logdet_host(C.byref(p), C.c_void_p(packed.data_ptr()), C.byref(r),
                                  C.c_void_p(diag.data_ptr()) if diag is not None else None)
@@ -501,6 +520,26 @@ def mdet_flodance_eval(coef, q, n_values, out=None, stream=None):
     if st != Status.OK:
         raise MemdetError(st)
     return out
+
+
+def mdet_step_copy(dst, src, stream=None) -> None:
+    """dst <- src by the library's plain copy kernel (asynchronous); same byte size, a multiple of 16."""
+    nb = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nb:
+        raise ValueError("dst and src must have the same size in bytes")
+    st = load().mdet_step_copy(dst.data_ptr(), src.data_ptr(), nb, _stream_handle(stream))
+    if st != Status.OK:
+        raise MemdetError(st)
+
+
+def mdet_step_mfma_peak(dtype, workgroups, iters, out, stream=None) -> float:
+    """Queues the register-only matrix-core loop; returns the flops of the launch."""
+    f = C.c_double(0.0)
+    st = load().mdet_step_mfma_peak(_dtype_code(dtype), int(workgroups), int(iters), out.data_ptr(),
+                                    C.byref(f), _stream_handle(stream))
+    if st != Status.OK:
+        raise MemdetError(st)
+    return f.value
 
 
 def pack_lower_block_columns(a, block_size: int, out=None, pin: bool = False):

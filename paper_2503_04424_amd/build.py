@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmemdet.so")
-SOURCES = [os.path.join(CSRC, "memdet.hip"), os.path.join(CSRC, "sequence.hip")]
+SOURCES = [os.path.join(CSRC, f) for f in ("memdet.hip", "sequence.hip", "calibrate.hip")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [

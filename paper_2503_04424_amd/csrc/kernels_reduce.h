@@ -92,6 +92,19 @@ __global__ __launch_bounds__(256) void widen_lower_kernel(const S* __restrict__ 
   for (int64_t j = threadIdx.x; j < end; j += 256) dst[i * ldd + j] = widen_exact(src[i * lds + j]);
 }
 
+// The same for a rows x cols rectangle (a piece of a block column on its way from host
+// memory): src with leading dimension lds, dst with ldd.
+template <typename S>
+__global__ __launch_bounds__(256) void widen_rows_kernel(const S* __restrict__ src, int64_t lds,
+                                                         double* __restrict__ dst, int64_t ldd,
+                                                         int64_t rows, int64_t cols) {
+  const int64_t total = rows * cols;
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+    const int64_t i = e / cols, j = e - i * cols;
+    dst[i * ldd + j] = widen_exact(src[i * lds + j]);
+  }
+}
+
 // X[r][c] *= d[c] in place, rows x cols with leading dimension ld (cols and ld multiples
 // of the 16-byte vector): rows of L of a finished block column become rows of W = L D,
 // each product rounded once, as the update kernels round it when they scale on the fly.

@@ -21,6 +21,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <algorithm>
 #include <atomic>
 #include <condition_variable>
 #include <functional>
@@ -28,6 +29,7 @@
 #include <mutex>
 #include <new>
 #include <thread>
+#include <type_traits>
 #include <vector>
 
 #include "../../include/memdet.h"
@@ -161,10 +163,15 @@ struct Launcher {
   int slots = 0;              // trailing-update workgroups the device holds at one time
   double fma = 0.0;
   uint64_t launches = 0;
-  // optional timing of the trailing-update launches (MDET_FLAG_PROFILE)
+  // optional timing of the trailing-update launches (MDET_FLAG_PROFILE): every launch of
+  // the two trailing-update kernels (kind 0: 128 x 128 blocks, kind 1: 64 x 64 blocks)
+  // bracketed by events on its own stream; prof_ref, recorded once at the start of the
+  // call, places the launches on one time axis
   bool profile = false;
-  std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
-  double prof_fma = 0.0;
+  struct ProfLaunch { hipEvent_t e0, e1; int kind; };
+  std::vector<ProfLaunch> prof_events;
+  hipEvent_t prof_ref = nullptr;
+  double prof_fma[2] = {0.0, 0.0};
 
   static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
@@ -229,7 +236,7 @@ struct Launcher {
         dual * 8 * ug.per > slots - leave_free)
       per_launch = (slots - leave_free) / (8 * dual);
     dim3 block(UPD_THREADS);
-    const bool timed = profile && trailing && !small_trailing;   // trailing_update_kernel proper
+    const bool timed = profile && trailing;
     for (int64_t k0 = 0; k0 < ug.per; k0 += per_launch) {
       const int64_t kn = ug.per - k0 < per_launch ? ug.per - k0 : per_launch;
       dim3 grid((unsigned)(8 * kn));
@@ -276,7 +283,7 @@ struct Launcher {
       ++launches;
       if (timed) {
         fail->check(hipEventRecord(e1, st));
-        prof_events.emplace_back(e0, e1);
+        prof_events.push_back(ProfLaunch{e0, e1, small_trailing ? 1 : 0});
       }
     }
     fail->check(hipGetLastError());
@@ -290,7 +297,7 @@ struct Launcher {
     }
     f *= (double)dual;
     fma += f;
-    if (timed) prof_fma += f;
+    if (timed) prof_fma[small_trailing ? 1 : 0] += f;
     return MDET_OK;
   }
 
@@ -429,19 +436,55 @@ struct Launcher {
                        wskip > w1 ? wskip - w1 : 0);
   }
 
-  // After all streams are idle: sum of the timed launches' durations (seconds).
+  // Start of the profiled region (MDET_FLAG_PROFILE): the origin of the launches' time axis.
+  void profile_begin(hipStream_t st) {
+    if (!profile) return;
+    prof_ref = timing_event_get(fail);
+    fail->check(hipEventRecord(prof_ref, st));
+  }
+
+  // After all streams are idle: per kernel the number of timed launches, the sum of their
+  // durations and their flops; and the length of the union of all their intervals, i.e. the
+  // time during which at least one trailing-update launch was running (launches on the two
+  // compute streams overlap, so the sum of the durations counts some time twice).
   void collect_profile(mdet_result* res) {
-    double ms_total = 0.0;
+    double ms_sum[2] = {0.0, 0.0};
+    uint64_t count[2] = {0, 0};
+    std::vector<std::pair<double, double>> iv;
+    iv.reserve(prof_events.size());
     for (auto& pr : prof_events) {
-      float ms = 0.f;
-      if (hipEventElapsedTime(&ms, pr.first, pr.second) == hipSuccess) ms_total += ms;
-      timing_event_put(pr.first);
-      timing_event_put(pr.second);
+      float ms = 0.f, at = 0.f;
+      if (hipEventElapsedTime(&ms, pr.e0, pr.e1) == hipSuccess) {
+        ms_sum[pr.kind] += ms;
+        ++count[pr.kind];
+        if (prof_ref && hipEventElapsedTime(&at, prof_ref, pr.e0) == hipSuccess)
+          iv.emplace_back((double)at, (double)at + (double)ms);
+      }
+      timing_event_put(pr.e0);
+      timing_event_put(pr.e1);
     }
-    res->trailing_update_launches = prof_events.size();
-    res->t_trailing_update = ms_total * 1e-3;
-    res->trailing_update_flops = 2.0 * prof_fma;
+    std::sort(iv.begin(), iv.end());
+    double busy = 0.0, lo = 0.0, hi = -1.0;
+    for (auto& x : iv) {
+      if (hi < lo || x.first > hi) {
+        if (hi > lo) busy += hi - lo;
+        lo = x.first;
+        hi = x.second;
+      } else if (x.second > hi) {
+        hi = x.second;
+      }
+    }
+    if (hi > lo) busy += hi - lo;
+    res->trailing_update_launches = count[0];
+    res->t_trailing_update = ms_sum[0] * 1e-3;
+    res->trailing_update_flops = 2.0 * prof_fma[0];
+    res->trailing_update64_launches = count[1];
+    res->t_trailing_update64 = ms_sum[1] * 1e-3;
+    res->trailing_update64_flops = 2.0 * prof_fma[1];
+    res->t_trailing_update_busy = busy * 1e-3;
     prof_events.clear();
+    timing_event_put(prof_ref);
+    prof_ref = nullptr;
   }
 
   void reduce(hipStream_t st, int64_t n, int64_t bs, int64_t T_, double* partial, double* out,
@@ -679,11 +722,20 @@ static void bind_small(Launcher<T>& L, char* base, const SmallArea& sa) {
     L.slots = 2 * cus;
 }
 
+// first_bad = ~0 (none), no odd leaves.  A kernel, not a memset: a caller may record the
+// launches of the allocation-free entry point into a graph.
+__global__ void reset_flags_kernel(DevFlags* f) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    f->first_bad = ~0ull;
+    f->bad_kind = ~0ull;
+    f->odd_leaves = 0ull;
+  }
+}
+
 template <typename T>
 static void reset_flags(Launcher<T>& L, hipStream_t st) {
-  // 0xFF bytes: first_bad = ~0 (none)
-  L.fail->check(hipMemsetAsync(L.flags, 0xFF, 2 * sizeof(unsigned long long), st));
-  L.fail->check(hipMemsetAsync(&L.flags->odd_leaves, 0, sizeof(unsigned long long), st));
+  hipLaunchKernelGGL(reset_flags_kernel, dim3(1), dim3(64), 0, st, L.flags);
+  L.fail->check(hipGetLastError());
 }
 
 // ---------------------------------------------------------------------------
@@ -747,6 +799,7 @@ static int logdet_device_t(const mdet_params& p, const Plan& plan, T* dA, int64_
     }
   }
   reset_flags(L, s0);
+  L.profile_begin(s0);
   T* Q = nullptr;
   const int nb64 = (int)((pl.n + LEAF - 1) / LEAF);
   if (pl.general && pl.n > 0) {
@@ -1103,11 +1156,34 @@ static void copy_col_rows(HipFail& fail, const Plan& pl, int64_t j, int64_t r0, 
   *bytes += nbytes;
 }
 
+// Pinned host buffer owned by the library.
+struct PinnedBuf {
+  void* p = nullptr;
+  int alloc(size_t bytes) {
+    hipError_t e = hipHostMalloc(&p, bytes ? bytes : 1, hipHostMallocDefault);
+    if (e != hipSuccess) { (void)hipGetLastError(); p = nullptr; return MDET_ENOMEM_HOST; }
+    return MDET_OK;
+  }
+  ~PinnedBuf() { if (p) (void)hipHostFree(p); }
+};
+
+// Where the original blocks come from when it is not host memory or a file in the
+// arithmetic's own type laid out like the factors.
+struct HostSource {
+  // the matrix as stored, narrower than the arithmetic (MDET_FLAG_COMPUTE_F64): base address
+  // (or byte offset in the file) of the packed layout in elements of `dtype`
+  const char* narrow = nullptr;
+  int32_t dtype = MDET_F64;
+  // blocks fetched through the caller's function instead (mdet_logdet_provider)
+  mdet_block_provider provider = nullptr;
+  void* user = nullptr;
+};
+
 // fd_in / fd_out >= 0: the store is a file and hA / hOut the byte offset of the layout in it
 // (as a pointer), see mdet_logdet_file.
 template <typename T>
 static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut, mdet_result* res,
-                         T* diag_host, int fd_in = -1, int fd_out = -1) {
+                         T* diag_host, int fd_in = -1, int fd_out = -1, const HostSource* source = nullptr) {
   HipFail fail;
   int dev = 0;
   MDET_HIP(fail, hipGetDevice(&dev));
@@ -1130,7 +1206,9 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
   double* partial = (double*)(ws.base + sa.partial);
   double* out = (double*)(ws.base + sa.out);
   double* running = (double*)(ws.base + sa.running);
-  char* arena = ws.base + sa.total;
+  char* const stage = ws.base + sa.total;            // pl.stage_bytes of staging for narrow uploads
+  char* arena = ws.base + sa.total + pl.stage_bytes;
+  uint64_t arena_used = 0;                           // highest arena offset any group reached
 
   EventPool events(&fail);
   hipStream_t s0 = ss->main, s1 = ss->side, sh = ss->h2d, sd = ss->d2h;
@@ -1139,6 +1217,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
   MDET_HIP(fail, hipStreamWaitEvent(s0, ev_in, 0));
   MDET_HIP(fail, hipStreamWaitEvent(sh, ev_in, 0));
   reset_flags(L, s0);
+  L.profile_begin(s0);
 
   const bool lookahead = !(p.flags & MDET_FLAG_NO_LOOKAHEAD);
   const int64_t bs = pl.bs, n = pl.n, T_ = pl.T;
@@ -1150,8 +1229,94 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
   auto host_col = [&](T* base, int64_t j) { return base + pl.col_offset(j); };
   // pageable host memory goes through pinned chunks (see HostStager)
   HostStager stager_in(&fail, fd_in), stager_out(&fail, fd_out);
-  HostStager* stage_in = (fd_in >= 0 || (n > 0 && HostStager::pageable(hA))) ? &stager_in : nullptr;
-  HostStager* stage_out = (fd_out >= 0 || (n > 0 && HostStager::pageable(hOut))) ? &stager_out : nullptr;
+  const bool from_provider = source && source->provider;
+  const bool narrow = source && !from_provider && pl.widen;
+  const void* const in_base = narrow ? (const void*)source->narrow : (const void*)hA;
+  HostStager* stage_in = (!from_provider && (fd_in >= 0 || (n > 0 && HostStager::pageable(in_base)))) ? &stager_in : nullptr;
+  HostStager* stage_out = (fd_out >= 0 || (n > 0 && hOut && HostStager::pageable(hOut))) ? &stager_out : nullptr;
+  // two pinned buffers of one block each for the provider's blocks, used in turn
+  PinnedBuf prov_buf[2];
+  hipEvent_t prov_ev[2] = {nullptr, nullptr};
+  int prov_next = 0;
+  int prov_rc = MDET_OK;
+  if (from_provider && n > 0) {
+    for (int q = 0; q < 2; ++q) {
+      if (prov_buf[q].alloc((size_t)bs * bs * pl.src_beta) != MDET_OK) return MDET_ENOMEM_HOST;
+      prov_ev[q] = events.get();
+    }
+  }
+  // narrow elements of rows x cols at `src` (leading dimension lds, device memory) widened into dst
+  auto widen_piece = [&](const void* src, int64_t lds, T* dst, int64_t ldd, int64_t rows, int64_t cols) {
+    if constexpr (std::is_same<T, double>::value) {
+      const int64_t total = rows * cols;
+      const unsigned grid = (unsigned)std::min<int64_t>((total + 255) / 256, 8192);
+      const int32_t sdt = source ? source->dtype : MDET_F64;
+      if (sdt == MDET_F16)
+        hipLaunchKernelGGL((widen_rows_kernel<StoredF16>), dim3(grid), dim3(256), 0, sh, (const StoredF16*)src, lds,
+                           (double*)dst, ldd, rows, cols);
+      else if (sdt == MDET_BF16)
+        hipLaunchKernelGGL((widen_rows_kernel<StoredBF16>), dim3(grid), dim3(256), 0, sh, (const StoredBF16*)src,
+                           lds, (double*)dst, ldd, rows, cols);
+      else
+        hipLaunchKernelGGL((widen_rows_kernel<float>), dim3(grid), dim3(256), 0, sh, (const float*)src, lds,
+                           (double*)dst, ldd, rows, cols);
+      MDET_HIP(fail, hipGetLastError());
+      ++L.launches;
+    }
+  };
+  // Rows [r0, r1) of the ORIGINAL block column j into its device image, on the upload stream.
+  auto upload_orig = [&](int64_t j, int64_t r0, int64_t r1) {
+    if (r1 <= r0) return;
+    const int64_t w = pl.col_width(j), ldd = pl.col_ld(j);
+    T* dcol = cols[j].base;
+    if (from_provider) {
+      // block by block through the caller's function, each into a pinned buffer and on from there
+      for (int64_t i = r0 / bs; i * bs < r1 && prov_rc == MDET_OK; ++i) {
+        const int64_t b0 = i * bs, b1 = std::min<int64_t>(n, b0 + bs);
+        const int q = prov_next;
+        prov_next ^= 1;
+        MDET_HIP(fail, hipEventSynchronize(prov_ev[q]));     // its last transfer has left the buffer
+        if (source->provider(source->user, i, j, b1 - b0, w, prov_buf[q].p, w) != 0) { prov_rc = MDET_EPROVIDER; break; }
+        CopyProfile::Scope timed(&cprof, 0, sh);
+        T* dst = dcol + (b0 - j * bs) * ldd;
+        const size_t row_bytes = (size_t)w * pl.src_beta;
+        if (pl.widen) {
+          // pieces of at most the staging buffer, widened from there (one stream: in order)
+          const int64_t per = std::max<int64_t>(1, (int64_t)(pl.stage_bytes / row_bytes));
+          for (int64_t r = b0; r < b1; r += per) {
+            const int64_t rn = std::min<int64_t>(per, b1 - r);
+            MDET_HIP(fail, hipMemcpyAsync(stage, (const char*)prov_buf[q].p + (size_t)(r - b0) * row_bytes,
+                                          (size_t)rn * row_bytes, hipMemcpyHostToDevice, sh));
+            widen_piece(stage, w, dcol + (r - j * bs) * ldd, ldd, rn, w);
+          }
+        } else if (ldd == w) {
+          MDET_HIP(fail, hipMemcpyAsync(dst, prov_buf[q].p, (size_t)(b1 - b0) * row_bytes, hipMemcpyHostToDevice, sh));
+        } else {
+          MDET_HIP(fail, hipMemcpy2DAsync(dst, ldd * sizeof(T), prov_buf[q].p, row_bytes, row_bytes,
+                                          (size_t)(b1 - b0), hipMemcpyHostToDevice, sh));
+        }
+        MDET_HIP(fail, hipEventRecord(prov_ev[q], sh));
+        h2d_bytes += (uint64_t)(b1 - b0) * row_bytes;
+      }
+      return;
+    }
+    if (!narrow) {
+      copy_col_rows(fail, pl, j, r0, r1, dcol, host_col(hA, j), true, sh, &h2d_bytes, &cprof, stage_in);
+      return;
+    }
+    CopyProfile::Scope timed(&cprof, 0, sh);
+    const size_t row_bytes = (size_t)w * pl.src_beta;
+    const char* scol = source->narrow + (uint64_t)pl.col_offset(j) * pl.src_beta;
+    const int64_t per = std::max<int64_t>(1, (int64_t)(pl.stage_bytes / row_bytes));
+    for (int64_t r = r0; r < r1; r += per) {
+      const int64_t rn = std::min<int64_t>(per, r1 - r);
+      const char* src = scol + (size_t)(r - j * bs) * row_bytes;
+      if (stage_in) stage_in->to_device(stage, (size_t)rn * row_bytes, src, (size_t)rn * row_bytes, 1, sh);
+      else MDET_HIP(fail, hipMemcpyAsync(stage, src, (size_t)rn * row_bytes, hipMemcpyHostToDevice, sh));
+      widen_piece(stage, w, dcol + (r - j * bs) * ldd, ldd, rn, w);
+    }
+    h2d_bytes += (uint64_t)(r1 - r0) * row_bytes;
+  };
 
   if (!pl.out_of_core) {
     // ---- everything resident: upload column by column, factor as columns arrive
@@ -1174,13 +1339,14 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
     ResidentHooks hooks;
     hooks.before_touch = [&](hipStream_t st, int64_t j) {
       if (!ready[j]) {
-        copy_col_rows(fail, pl, j, j * bs, n, cols[j].base, host_col(hA, j), true, sh, &h2d_bytes, &cprof, stage_in);
+        upload_orig(j, j * bs, n);
         ready[j] = events.get();
         fail.check(hipEventRecord(ready[j], sh));
       }
       std::vector<char>& seen = (st == s0) ? seen0 : seen1;
       if (!seen[j]) { seen[j] = 1; fail.check(hipStreamWaitEvent(st, ready[j], 0)); }
     };
+    arena_used = off + pl.wcopy_bytes;
     rc = factor_resident(L, pl, cols, 0, T_, false, lookahead, s0, s1, events, &hooks);
   } else {
     // ---- out-of-core: resident groups of block columns, factored columns stream past
@@ -1216,6 +1382,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
         for (int q = 0; q < 2; ++q) { bpool[q] = (T*)(arena + off); off += (uint64_t)wc * tile_al; }
         for (uint64_t q = 0; q < pl.ring_tiles; ++q) { ring.push_back((T*)(arena + off)); off += tile_al; }
       }
+      if (off > arena_used) arena_used = off;
       // -- the arena may be reused once the previous group is saved and idle
       if (ev_arena_free) MDET_HIP(fail, hipStreamWaitEvent(sh, ev_arena_free, 0));
       for (hipEvent_t e : saved) MDET_HIP(fail, hipStreamWaitEvent(sh, e, 0));
@@ -1229,7 +1396,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
         ResidentHooks hooks;
         hooks.before_touch = [&](hipStream_t st, int64_t j) {
           if (!ready[j]) {   // uploaded when first needed, as in the in-core case
-            copy_col_rows(fail, pl, j, j * bs, n, cols[j].base, host_col(hA, j), true, sh, &h2d_bytes, &cprof, stage_in);
+            upload_orig(j, j * bs, n);
             ready[j] = events.get();
             fail.check(hipEventRecord(ready[j], sh));
           }
@@ -1247,8 +1414,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
         std::vector<hipEvent_t> row_ready((size_t)T_, nullptr);
         auto upload_row = [&](int64_t i) {
           const int64_t r0 = i * bs, r1 = (i + 1) * bs < n ? (i + 1) * bs : n;
-          for (int64_t j = j0; j < j1 && j <= i; ++j)
-            copy_col_rows(fail, pl, j, r0, r1, cols[j].base, host_col(hA, j), true, sh, &h2d_bytes, &cprof, stage_in);
+          for (int64_t j = j0; j < j1 && j <= i; ++j) upload_orig(j, r0, r1);
           row_ready[i] = events.get();
           MDET_HIP(fail, hipEventRecord(row_ready[i], sh));
         };
@@ -1357,32 +1523,29 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
   res->bytes_d2h = d2h_bytes;
   res->t_h2d = cprof.collect(0);
   res->t_d2h = cprof.collect(1);
+  res->dev_bytes_high_water = sa.total + pl.stage_bytes + arena_used;
+  if (prov_rc != MDET_OK) return prov_rc;
   if (stager_in.io_failed() || stager_out.io_failed()) return MDET_EIO;
   if (!fail.ok()) { res->hip_error = fail.code; return MDET_EHIP; }
   if (rc != MDET_OK) return rc;
   return finish_result(o, res);
 }
 
-// Pinned host buffer owned by the library.
-struct PinnedBuf {
-  void* p = nullptr;
-  int alloc(size_t bytes) {
-    hipError_t e = hipHostMalloc(&p, bytes ? bytes : 1, hipHostMallocDefault);
-    if (e != hipSuccess) { (void)hipGetLastError(); p = nullptr; return MDET_ENOMEM_HOST; }
-    return MDET_OK;
-  }
-  ~PinnedBuf() { if (p) (void)hipHostFree(p); }
-};
-
-static int logdet_host_any(const mdet_params* p, void* hA, mdet_result* res, void* diag) {
+// Runs the host path in the arithmetic's type.  hA: the matrix as stored (host memory; ignored
+// when `provider` is given).  The factored block columns of a streamed run go to hA itself
+// (overwrite = 1 and the matrix stored in the arithmetic's type), else to the caller's
+// host_scratch, else to memory the library allocates (pinned if that much can be pinned).
+static int logdet_host_any(const mdet_params* p, void* hA, mdet_result* res, void* diag,
+                           mdet_block_provider provider = nullptr, void* user = nullptr) {
   Plan pl;
   int rc = make_plan(*p, false, 0, pl);
   init_result(res, pl);
   if (rc != MDET_OK) return rc;
   PinnedBuf scratch;
   std::unique_ptr<char[]> plain_scratch;
-  void* hOut = hA;
-  if (pl.out_of_core && !p->overwrite) {
+  const bool own_store = pl.widen || provider != nullptr;   // the factors cannot go where the matrix is
+  void* hOut = own_store ? nullptr : hA;
+  if (pl.out_of_core && (!p->overwrite || own_store)) {
     if (p->host_scratch) {
       if (p->host_scratch_bytes < pl.layout_bytes) return MDET_ENOMEM_HOST;
       hOut = p->host_scratch;
@@ -1395,9 +1558,17 @@ static int logdet_host_any(const mdet_params* p, void* hA, mdet_result* res, voi
       hOut = plain_scratch.get();
     }
   }
+  HostSource src;
+  src.narrow = pl.widen ? (const char*)hA : nullptr;
+  src.dtype = p->dtype;
+  src.provider = provider;
+  src.user = user;
+  const HostSource* sp = (pl.widen || provider) ? &src : nullptr;
   auto t0 = std::chrono::steady_clock::now();
-  if (p->dtype == MDET_F64) rc = logdet_host_t<double>(*p, pl, (double*)hA, (double*)hOut, res, (double*)diag);
-  else rc = logdet_host_t<float>(*p, pl, (float*)hA, (float*)hOut, res, (float*)diag);
+  if (p->dtype == MDET_F64 || pl.widen)
+    rc = logdet_host_t<double>(*p, pl, own_store ? nullptr : (double*)hA, (double*)hOut, res, (double*)diag, -1, -1, sp);
+  else
+    rc = logdet_host_t<float>(*p, pl, own_store ? nullptr : (float*)hA, (float*)hOut, res, (float*)diag, -1, -1, sp);
   res->t_total = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
   return rc;
 }
@@ -1415,24 +1586,28 @@ static int logdet_file_any(const mdet_params* p, const char* matrix_path, const 
     ~Fd() { if (fd >= 0) ::close(fd); }
   } in, out;
   const bool writes = pl.out_of_core;              // factored columns are stored only when they stream
-  const bool in_place = writes && p->overwrite;
+  const bool in_place = writes && p->overwrite && !pl.widen;
   in.fd = ::open(matrix_path, in_place ? O_RDWR : O_RDONLY);
   if (in.fd < 0) return MDET_EIO;
   struct stat sb;
-  if (::fstat(in.fd, &sb) != 0 || (uint64_t)sb.st_size < pl.layout_bytes) return MDET_EIO;
+  if (::fstat(in.fd, &sb) != 0 || (uint64_t)sb.st_size < pl.layout_bytes / pl.beta * pl.src_beta) return MDET_EIO;
   int fd_out = in.fd;
-  if (writes && !p->overwrite) {
+  if (writes && !in_place) {
     if (!scratch_path) return MDET_EINVAL;
     out.fd = ::open(scratch_path, O_RDWR | O_CREAT, 0600);
     if (out.fd < 0) return MDET_EIO;
     if (::ftruncate(out.fd, (off_t)pl.layout_bytes) != 0) return MDET_EIO;
     fd_out = out.fd;
   }
+  HostSource src;
+  src.narrow = nullptr;          // byte offset 0 of the matrix file
+  src.dtype = p->dtype;
+  const HostSource* sp = pl.widen ? &src : nullptr;
   auto t0 = std::chrono::steady_clock::now();
-  if (p->dtype == MDET_F64)
-    rc = logdet_host_t<double>(*p, pl, (double*)nullptr, (double*)nullptr, res, (double*)diag, in.fd, fd_out);
+  if (p->dtype == MDET_F64 || pl.widen)
+    rc = logdet_host_t<double>(*p, pl, (double*)nullptr, (double*)nullptr, res, (double*)diag, in.fd, fd_out, sp);
   else
-    rc = logdet_host_t<float>(*p, pl, (float*)nullptr, (float*)nullptr, res, (float*)diag, in.fd, fd_out);
+    rc = logdet_host_t<float>(*p, pl, (float*)nullptr, (float*)nullptr, res, (float*)diag, in.fd, fd_out, sp);
   res->t_total = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
   return rc;
 }
@@ -1671,31 +1846,9 @@ extern "C" int mdet_logdet_file(const mdet_params* p, const char* matrix_path, c
 extern "C" int mdet_logdet_provider(const mdet_params* p, mdet_block_provider provider, void* user,
                                     mdet_result* res, void* diag) {
   if (!params_ok(p) || !res || !provider) return MDET_EINVAL;
-  Plan pl;
-  int rc = make_plan(*p, false, 0, pl);
-  init_result(res, pl);
-  if (rc != MDET_OK) return rc;
-  // pinned memory if it can be had (there are limits well below the size of host memory),
-  // ordinary memory otherwise: the host path moves that through pinned chunks
-  PinnedBuf buf;
-  std::unique_ptr<char[]> plain;
-  if (buf.alloc(pl.layout_bytes) != MDET_OK) {
-    plain.reset(new (std::nothrow) char[pl.layout_bytes ? pl.layout_bytes : 1]);
-    if (!plain) return MDET_ENOMEM_HOST;
-    buf.p = nullptr;
-  }
-  void* const store = buf.p ? buf.p : (void*)plain.get();
-  const int64_t bs = pl.bs;
-  for (int64_t j = 0; j < pl.T; ++j) {
-    const int64_t wj = pl.col_width(j);
-    char* col = (char*)store + (uint64_t)pl.col_offset(j) * pl.beta;
-    for (int64_t i = j; i < pl.T; ++i) {
-      const int64_t wi = pl.col_width(i);
-      void* dst = col + (uint64_t)(i - j) * bs * wj * pl.beta;
-      if (provider(user, i, j, wi, wj, dst, wj) != 0) return MDET_EPROVIDER;
-    }
-  }
-  mdet_params q = *p;
-  q.overwrite = 1;        // the staging buffer is ours
-  return logdet_host_any(&q, store, res, diag);
+  // The blocks are fetched when the schedule first needs them, each into a pinned buffer and
+  // from there to the device: host memory holds no copy of the matrix.  Only a run that
+  // streams keeps its factored block columns in host memory (the caller's host_scratch or the
+  // library's own).
+  return logdet_host_any(p, nullptr, res, diag, provider, user);
 }

@@ -25,7 +25,10 @@ struct SuperPanel {
 
 struct Plan {
   int64_t n = 0, bs = 0, T = 0;
-  int beta = 8;
+  int beta = 8;                    // bytes per element on the device (the arithmetic's type)
+  int src_beta = 8;                // bytes per element of the caller's matrix (differs with MDET_FLAG_COMPUTE_F64)
+  bool widen = false;              // MDET_FLAG_COMPUTE_F64: stored narrow, widened exactly on the device
+  uint64_t stage_bytes = 0;        // host entry points with widen: device staging for the narrow uploads
   bool device_input = false;
   bool out_of_core = false;
   bool need_copy = false;          // device input: work on a copy (overwrite = 0)
@@ -102,9 +105,10 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
   // fp32 or 16-bit storage with fp64 arithmetic: everything on the device is fp64
   const bool widen = p.dtype != MDET_F64 && (p.flags & MDET_FLAG_COMPUTE_F64) != 0;
   if (narrow16 && !widen) return MDET_EINVAL;      // 16-bit types are storage formats only
-  if (widen && !device_input) return MDET_EINVAL;
   pl.n = p.n;
   pl.beta = (p.dtype == MDET_F64 || widen) ? 8 : 4;
+  pl.widen = widen;
+  pl.src_beta = p.dtype == MDET_F64 ? 8 : (p.dtype == MDET_F32 ? 4 : 2);
   pl.bs = round_up(p.block_size > 0 ? p.block_size : default_block_size(p.n), 64);
   pl.T = p.n > 0 ? (p.n + pl.bs - 1) / pl.bs : 0;
   pl.device_input = device_input;
@@ -163,6 +167,18 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
   const bool force_ooc = (p.flags & MDET_FLAG_FORCE_OUT_OF_CORE) != 0;
   uint64_t dev_layout = 0;
   for (int64_t j = 0; j < pl.T; ++j) dev_layout += align256(pl.dev_col_bytes(j));
+  // narrow storage: the originals arrive in the stored width in a staging buffer of at most
+  // 64 MiB (one block row of a block column at a time, cut further if need be) and are
+  // widened from there into their block column
+  pl.stage_bytes = 0;
+  if (widen && pl.T > 0) {
+    const uint64_t piece = (uint64_t)pl.bs * pl.bs * pl.src_beta;
+    const uint64_t one_row = (uint64_t)pl.bs * pl.src_beta;
+    uint64_t st = piece < (64ull << 20) ? piece : (64ull << 20);
+    if (st < one_row) st = one_row;
+    pl.stage_bytes = align256(st);
+  }
+  pl.small_bytes += pl.stage_bytes;      // counted with the fixed part of the workspace
   const uint64_t incore = pl.small_bytes + dev_layout;
   if (!force_ooc && (budget == 0 || incore <= budget)) {
     pl.out_of_core = false;
@@ -171,7 +187,7 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
       pl.wcopy_bytes = wcopy;
       pl.dev_bytes += wcopy;
     }
-    pl.h2d = pl.layout_bytes;
+    pl.h2d = pl.layout_bytes / pl.beta * pl.src_beta;
     pl.panels.push_back({0, pl.T, pl.layout_bytes});
     return MDET_OK;
   }
@@ -202,13 +218,17 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
     if (use > peak) peak = use;
     pl.panels.push_back({j0, j1, resident});
     // traffic: originals in, factors out, and every earlier column's rows from j0 down
-    for (int64_t j = j0; j < j1; ++j) { pl.h2d += pl.col_bytes(j); pl.d2h += pl.col_bytes(j); }
+    for (int64_t j = j0; j < j1; ++j) {
+      pl.h2d += pl.col_bytes(j) / pl.beta * pl.src_beta;
+      pl.d2h += pl.col_bytes(j);
+    }
     for (int64_t k = 0; k < j0; ++k)
       pl.h2d += (uint64_t)pl.col_rows(j0) * pl.col_width(k) * pl.beta;
     j0 = j1;
   }
   pl.dev_bytes = peak;
-  pl.host_bytes = p.overwrite ? 0 : pl.layout_bytes;
+  // the factors are always in the arithmetic's type: a matrix stored narrower cannot take them
+  pl.host_bytes = (p.overwrite && !widen) ? 0 : pl.layout_bytes;
   return MDET_OK;
 }
 

@@ -10,7 +10,7 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
-    config.addinivalue_line("markers", "full: full-size out-of-core configurations (set MEMDET_FULL=1)")
+    config.addinivalue_line("markers", "full: full-size benchmark configurations (minutes of GPU time)")
 
 
 def read_golden(name):

@@ -115,11 +115,12 @@ def test_plan_rounds_block_size_and_handles_edges(M):
         M.mdet_plan(-1, "f64", 64)
     with pytest.raises(ValueError):
         M.mdet_plan(10, "int8", 64)
-    # the 16-bit types are storage formats: only with fp64 arithmetic, device input only
+    # the 16-bit types are storage formats: only with fp64 arithmetic
     with pytest.raises(M.MemdetError):
         M.mdet_plan(10, "f16", 64)
     with pytest.raises(M.MemdetError):
-        M.mdet_plan(10, "bf16", 64, flags=M.FLAG_COMPUTE_F64)
+        M.mdet_plan(10, "bf16", 64, for_device_input=True)
+    assert M.mdet_plan(10, "bf16", 64, flags=M.FLAG_COMPUTE_F64).num_blocks == 1
     assert M.mdet_plan(4096, "f16", 256, flags=M.FLAG_COMPUTE_F64,
                        for_device_input=True).dev_bytes_needed >= 4096 * 4096 * 8
     # device input: only a small scratch unless a copy is needed
@@ -174,8 +175,25 @@ def test_plan_fp32_storage_with_fp64_arithmetic(M):
     assert wide.dev_bytes_needed >= n * n * 8               # an fp64 copy of the matrix
     with pytest.raises(M.MemdetError):                      # budget counts the copy
         M.mdet_plan(n, "f32", 256, mem_budget=n * n * 4, flags=M.FLAG_COMPUTE_F64, for_device_input=True)
-    with pytest.raises(M.MemdetError):                      # device entry point only
-        M.mdet_plan(n, "f32", 256, flags=M.FLAG_COMPUTE_F64, for_device_input=False)
+    # host entry points (App. C: stored narrow, computed in 64 bits): the originals cross the
+    # link in the stored width, everything on the device and every factor is fp64
+    n, b = 32768, 2048
+    full64 = M.mdet_plan(n, "f64", b, 3 << 30)
+    for dt, beta in (("f32", 4), ("f16", 2), ("bf16", 2)):
+        w = M.mdet_plan(n, dt, b, 3 << 30, flags=M.FLAG_COMPUTE_F64)
+        assert w.out_of_core and w.dev_bytes_needed <= 3 << 30
+        assert w.host_matrix_bytes == full64.host_matrix_bytes          # the fp64 layout of the factors
+        assert w.host_bytes_needed == full64.host_matrix_bytes          # which never go into the matrix
+        assert M.mdet_plan(n, dt, b, 3 << 30, overwrite=False, flags=M.FLAG_COMPUTE_F64).host_bytes_needed == \
+            w.host_bytes_needed
+        assert w.stream_bytes_d2h == full64.stream_bytes_d2h
+        # the same groups would save (8 - beta)/8 of the originals' upload; the staging buffer may
+        # cost a block column of residency, so compare against the plan's own group structure
+        assert w.stream_bytes_h2d < full64.stream_bytes_h2d
+        assert w.num_superpanels >= full64.num_superpanels
+    inc = M.mdet_plan(4096, "f32", 512, flags=M.FLAG_COMPUTE_F64)
+    assert not inc.out_of_core and inc.stream_bytes_h2d == inc.host_matrix_bytes // 2 and inc.host_bytes_needed == 0
+    assert inc.dev_bytes_needed >= inc.host_matrix_bytes + 512 * 512 * 4
 
 
 def test_kms_golden_values_are_the_closed_form():

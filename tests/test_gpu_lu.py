@@ -322,8 +322,7 @@ def test_bad_arguments_and_workspace(M):
     assert e.value.status == M.Status.EBUDGET
 
 
-@pytest.mark.parametrize("n", [8192, pytest.param(32768, marks=pytest.mark.skipif(
-    os.environ.get("MEMDET_FULL") != "1", reason="set MEMDET_FULL=1"))])
+@pytest.mark.parametrize("n", [8192, 32768])
 def test_benchmark_size_against_a_product_of_known_factors(M, n):
     # the sizes bench.py --general times: A = (rows shuffled inside groups of 64) of L0 U0 with
     # a unit lower L0 of small entries and an upper U0 with a known diagonal:
