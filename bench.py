@@ -241,9 +241,11 @@ def kernel_report(reps=5):
                       "data": "synthetic", "kernels": out}))
 
 
-def mfma_peak_report(reps=5):
+def mfma_peak_report(reps=3):
     """The matrix pipe's measured ceiling: register-only loops of 16 x 16 x 4 products
-    (mdet_step_mfma_peak), one and two workgroups per compute unit.  One JSON line."""
+    (mdet_step_mfma_peak), one and two workgroups per compute unit, in launches of about
+    2, 20 and 200 ms (the clock the chip sustains depends on how long the pipe stays full).
+    One JSON line."""
     import torch
     import paper_2503_04424_amd as M
     M.load()
@@ -252,25 +254,28 @@ def mfma_peak_report(reps=5):
     rows = []
     for dt, name in ((torch.float64, "f64"), (torch.float32, "f32")):
         out = torch.empty(65536, dtype=dt, device="cuda")
-        for per_cu in (1, 2):
+        for nacc, per_cu, scale in ((4, 1, 1), (4, 1, 10), (4, 2, 10), (16, 1, 1), (16, 1, 10), (16, 2, 10),
+                                    (16, 1, 100)):
             wgs = cus * per_cu
-            iters = 40000 // per_cu
-            M.mdet_step_mfma_peak(name, wgs, 200, out)
+            # one f64 product occupies a SIMD's matrix pipe for 64 clocks, one f32 product for 32
+            iters = (4000 if name == "f64" else 8000) * scale // per_cu
+            M.mdet_step_mfma_peak(name, wgs, 200, out, accumulators=nacc)
             best = None
             for _ in range(reps):
                 torch.cuda.synchronize()
                 e0 = torch.cuda.Event(enable_timing=True)
                 e1 = torch.cuda.Event(enable_timing=True)
                 e0.record()
-                flop = M.mdet_step_mfma_peak(name, wgs, iters, out)
+                flop = M.mdet_step_mfma_peak(name, wgs, iters, out, accumulators=nacc)
                 e1.record()
                 torch.cuda.synchronize()
                 ms = e0.elapsed_time(e1)
                 best = ms if best is None else min(best, ms)
             tf = flop / best / 1e9
-            rows.append({"kernel": f"mfma_peak_{name}_kernel", "dtype": name, "workgroups": wgs,
-                         "wavefronts_per_simd": per_cu, "ms": best, "achieved": tf, "unit": "TFLOP/s",
-                         "published_peak": PEAK[name], "frac_of_published": tf / PEAK[name]})
+            rows.append({"kernel": f"mfma_peak_{name}_kernel<{nacc}>", "dtype": name, "accumulators": nacc,
+                         "workgroups": wgs, "wavefronts_per_simd": per_cu, "ms": round(best, 3),
+                         "achieved": round(tf, 2), "unit": "TFLOP/s", "published_peak": PEAK[name],
+                         "frac_of_published": round(tf / PEAK[name], 4)})
     print(json.dumps({"metric": "matrix-core ceiling, register-only 16x16x4 products", "n_gpus": 1,
                       "compute_units": cus, "rows": rows}))
 
@@ -331,8 +336,9 @@ def pmc_summary(directory):
 
 
 def stats_summary(directory):
-    """The library's kernels from rocprofv3's kernel_stats CSV, and the copies from its
-    memory_copy_stats CSV if there is one, under `directory`.  Plain text, for profiles/."""
+    """The library's kernels (and the runtime's copy kernels) from rocprofv3's kernel_stats CSV,
+    and the copies from its memory-copy CSVs if there are any, under `directory`.  Plain text,
+    for profiles/.  This rocprofv3 records no sizes for copies: bytes are in bench.py's own line."""
     import csv
     import glob
     for path in sorted(glob.glob(os.path.join(directory, "**", "*kernel_stats.csv"), recursive=True)):
@@ -341,33 +347,23 @@ def stats_summary(directory):
         other = 0.0
         for r in csv.DictReader(open(path)):
             name = r["Name"]
-            if "mdet::" not in name:
+            if "mdet::" in name:
+                short = name.split("mdet::")[1].split("(")[0]
+            elif name.startswith("__amd_rocclr_"):
+                short = name + " (runtime copy kernel)"
+            else:
                 other += float(r["TotalDurationNs"])
                 continue
-            short = name.split("mdet::")[1].split("(")[0]
             print(f"{short[:58]:58s} {int(r['Calls']):7d} {float(r['TotalDurationNs']) / 1e6:11.3f} "
                   f"{float(r['AverageNs']) / 1e3:11.2f} {float(r['MinNs']) / 1e3:10.2f} "
                   f"{float(r['MaxNs']) / 1e3:10.2f} {float(r['Percentage']):6.2f}")
-        print(f"{'(other kernels: input generation, torch)':58s} {'':7s} {other / 1e6:11.3f}")
+        print(f"{'(other kernels: input generation by torch)':58s} {'':7s} {other / 1e6:11.3f}")
     for path in sorted(glob.glob(os.path.join(directory, "**", "*memory_copy_stats.csv"), recursive=True)):
         print(f"# {os.path.relpath(path, directory)}")
+        print(f"{'direction':30s} {'copies':>8s} {'busy_s':>9s} {'avg_us':>10s} {'min_us':>9s} {'max_us':>9s}")
         for r in csv.DictReader(open(path)):
-            print("  ".join(f"{k}={v}" for k, v in r.items()))
-    for path in sorted(glob.glob(os.path.join(directory, "**", "*memory_copy_trace.csv"), recursive=True)):
-        # bytes and busy time per direction, from the trace itself
-        tot = {}
-        for r in csv.DictReader(open(path)):
-            d = r.get("Direction", "?")
-            b = float(r.get("Bytes", r.get("Size", 0)) or 0)
-            t = float(r["End_Timestamp"]) - float(r["Start_Timestamp"])
-            c = tot.setdefault(d, [0, 0.0, 0.0])
-            c[0] += 1
-            c[1] += b
-            c[2] += t
-        print(f"# {os.path.relpath(path, directory)}")
-        for d, (cnt, b, t) in sorted(tot.items()):
-            print(f"{d:28s} copies {cnt:8d}  bytes {b:.4e}  busy_s {t / 1e9:9.3f}  GB/s while copying "
-                  f"{(b / t) if t else 0.0:7.2f}")
+            print(f"{r['Name']:30s} {int(r['Calls']):8d} {float(r['TotalDurationNs']) / 1e9:9.3f} "
+                  f"{float(r['AverageNs']) / 1e3:10.2f} {float(r['MinNs']) / 1e3:9.2f} {float(r['MaxNs']) / 1e3:9.2f}")
 
 
 def main():

@@ -168,21 +168,20 @@ typedef struct mdet_params {
 
 #define MDET_FLAG_GENERAL 128u    /* the matrix is not symmetric (Sec. 2.2, Eq. 1 and Alg. 1:
                                      M = P L U for generic matrices, with pivoting inside a
-                                     block and none between blocks).  mdet_logdet_device
-                                     only, fp32 or fp64 in their own arithmetic; every other
-                                     entry point, MDET_FLAG_ASSUME_SPD, MDET_FLAG_PIVOT and
-                                     MDET_FLAG_COMPUTE_F64 with it give MDET_EINVAL.  All
-                                     n x n entries of the input are read.  Gaussian
-                                     elimination in the order of the symmetric path (block
-                                     columns, leaves of 64); in column j the pivot is the
-                                     entry of largest magnitude among the rows j .. end of
-                                     j's group of 64 consecutive rows (the first on ties),
+                                     block and none between blocks), fp32 or fp64 in their
+                                     own arithmetic; MDET_FLAG_ASSUME_SPD, MDET_FLAG_PIVOT and
+                                     MDET_FLAG_COMPUTE_F64 with it, and mdet_logdet_provider,
+                                     give MDET_EINVAL.  All n x n entries of the input are
+                                     read.  Gaussian elimination in the order of the symmetric
+                                     path (block columns, leaves of 64); in column j the pivot
+                                     is the entry of largest magnitude among the rows j .. end
+                                     of j's group of 64 consecutive rows (the first on ties),
                                      and the two rows change places.  The factors are kept
                                      as P A = L D U, L unit lower and U unit upper
                                      triangular; log|det| = sum log|d_j|, sign = the
                                      permutation's sign times the pivots' signs.
                                      `diag` receives d; perm (as for MDET_FLAG_PIVOT, n
-                                     int32 on the device) the row order: perm[j] = row of
+                                     int32) the row order: perm[j] = row of
                                      the input that stands at position j inside its group.
                                      As in the symmetric pivoted form the exchanges are not
                                      applied to the columns left of a group, so with
@@ -191,11 +190,22 @@ typedef struct mdet_params {
                                      left of the group, d on the diagonal and U above it:
                                      A[perm] = L' D U with L' = S's lower part, rows of each
                                      diagonal 64-block's columns already in pivot order.
-                                     Device memory: one more array of the matrix's shape
-                                     (the entries above the diagonal are kept transposed,
-                                     so that both triangles are read along rows), counted by
-                                     mdet_plan and mdet_workspace_query.  A column whose
-                                     candidates are all zero ends the call with
+                                     mdet_logdet_device: one more array of the matrix's shape
+                                     in the workspace (the entries above the diagonal are
+                                     kept transposed, so that both triangles are read along
+                                     rows), counted by mdet_plan and mdet_workspace_query.
+                                     mdet_logdet_host and mdet_logdet_file (the
+                                     memory-constrained generic case of Alg. 1): the caller
+                                     supplies both triangles in that form, the packed lower
+                                     block-column layout of M followed by the packed lower
+                                     block-column layout of M^T (diagonal blocks complete in
+                                     the first, only their strictly lower part read in the
+                                     second); block columns of both are resident, streamed
+                                     and written back together, so every figure of the plan
+                                     (device bytes, traffic, host scratch) is twice the
+                                     symmetric one; with overwrite = 1 a streamed run leaves
+                                     L and D in the first layout and U^T (unit) in the second.
+                                     A column whose candidates are all zero ends the call with
                                      MDET_ESINGULAR.                                     */
 
 typedef struct mdet_result {
@@ -460,13 +470,14 @@ int mdet_flodance_eval(const double* coef, int32_t q, const double* n_values, in
 int mdet_step_copy(void* dst, const void* src, uint64_t bytes, void* stream);
 
 /* Matrix-core instructions on registers only (16 x 16 x 4 products of `dtype`, MDET_F64 or
- * MDET_F32, four accumulators in turn): `workgroups` workgroups of four wavefronts, `iters`
+ * MDET_F32; `accumulators` = 4 or 16 accumulator tiles used in turn, 16 / accumulators
+ * dependent products in a row on each): `workgroups` workgroups of four wavefronts, `iters`
  * rounds of 16 products per wavefront.  *flop receives the flops of the launch (2048 per
  * product); `out` needs 65536 elements of dtype (receives values that keep the compiler
  * from dropping the work).  Time it with events: the rate is the matrix pipe's measured
  * ceiling for the Schur update S <- S - C B of Sec. 2.2. */
-int mdet_step_mfma_peak(int32_t dtype, int32_t workgroups, int32_t iters, void* out, double* flop,
-                        void* stream);
+int mdet_step_mfma_peak(int32_t dtype, int32_t accumulators, int32_t workgroups, int32_t iters,
+                        void* out, double* flop, void* stream);
 
 const char* mdet_strerror(int status);
 const char* mdet_version(void);

@@ -14,5 +14,5 @@ from .binding import (  # noqa: F401
     mdet_step_logdet_reduce, mdet_strerror, mdet_version,
     mdet_sequence_workspace_query, mdet_principal_logdets, mdet_flodance_fit, mdet_flodance_eval,
     mdet_step_copy, mdet_step_mfma_peak,
-    pack_lower_block_columns,
+    pack_lower_block_columns, pack_general_block_columns,
 )

@@ -119,7 +119,7 @@ def load():
     L.mdet_flodance_fit.argtypes = [vp, i64, i64, i64, i64, i32, vp, vp, u64, vp]
     L.mdet_flodance_eval.argtypes = [vp, i32, vp, i64, vp, vp]
     L.mdet_step_copy.argtypes = [vp, vp, u64, vp]
-    L.mdet_step_mfma_peak.argtypes = [i32, i32, i32, vp, C.POINTER(C.c_double), vp]
+    L.mdet_step_mfma_peak.argtypes = [i32, i32, i32, i32, vp, C.POINTER(C.c_double), vp]
     L.mdet_strerror.argtypes = [C.c_int]
     L.mdet_strerror.restype = C.c_char_p
     L.mdet_version.restype = C.c_char_p
@@ -339,6 +339,8 @@ def mdet_logdet_host(packed, n, block_size, mem_budget=0, overwrite=True, flags=
         return _result(st, _Result())
     b = info.block_size_used
     need = mdet_host_layout_offset(n, b, (n + b - 1) // b) if n > 0 else 0
+    if flags & FLAG_GENERAL:
+        need *= 2          # the layout of the matrix, then the layout of its transpose
     if packed.numel() < need:
         raise ValueError(f"packed layout needs {need} elements")
     import torch
@@ -532,14 +534,28 @@ def mdet_step_copy(dst, src, stream=None) -> None:
         raise MemdetError(st)
 
 
-def mdet_step_mfma_peak(dtype, workgroups, iters, out, stream=None) -> float:
+def mdet_step_mfma_peak(dtype, workgroups, iters, out, accumulators=4, stream=None) -> float:
     """Queues the register-only matrix-core loop; returns the flops of the launch."""
     f = C.c_double(0.0)
-    st = load().mdet_step_mfma_peak(_dtype_code(dtype), int(workgroups), int(iters), out.data_ptr(),
-                                    C.byref(f), _stream_handle(stream))
+    st = load().mdet_step_mfma_peak(_dtype_code(dtype), int(accumulators), int(workgroups), int(iters),
+                                    out.data_ptr(), C.byref(f), _stream_handle(stream))
     if st != Status.OK:
         raise MemdetError(st)
     return f.value
+
+
+def pack_general_block_columns(a, block_size: int, pin: bool = False):
+    """Host layout of a general matrix for ``mdet_logdet_host`` with FLAG_GENERAL: the packed
+    lower block-column layout of ``a`` followed by that of its transpose.  Layout marshalling only."""
+    import torch
+    n = a.shape[0]
+    b = (int(block_size) + 63) // 64 * 64
+    T = (n + b - 1) // b if n > 0 else 0
+    total = mdet_host_layout_offset(n, b, T) if n > 0 else 0
+    out = torch.empty(max(2 * total, 1), dtype=a.dtype, pin_memory=pin)
+    pack_lower_block_columns(a, block_size, out=out[:max(total, 1)])
+    pack_lower_block_columns(a.t(), block_size, out=out[total:] if total else out)
+    return out
 
 
 def pack_lower_block_columns(a, block_size: int, out=None, pin: bool = False):

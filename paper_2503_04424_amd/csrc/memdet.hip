@@ -1209,6 +1209,18 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
   char* const stage = ws.base + sa.total;            // pl.stage_bytes of staging for narrow uploads
   char* arena = ws.base + sa.total + pl.stage_bytes;
   uint64_t arena_used = 0;                           // highest arena offset any group reached
+  // A general matrix (Sec. 2.2, Eq. 1: M = P L U) is two lower-triangular arrays, the entries
+  // on and below the diagonal and the transposed entries above it: on the host two packed
+  // layouts one after the other, on the device two arenas arena_half bytes apart with
+  // everything (block columns, streamed blocks) at the same offsets in both.  Every copy below
+  // is made once per array; every kernel works on both at once (see Launcher::qoff).
+  const int arrays = pl.general ? 2 : 1;
+  const int64_t host_half = (int64_t)(pl.layout_bytes / sizeof(T));     // elements between the two host layouts
+  const int64_t dev_half = (int64_t)(pl.arena_half / sizeof(T));
+  if (pl.general) {
+    L.qoff = dev_half;
+    if (L.qoff == 0 && pl.n > 0) return MDET_EINVAL;
+  }
 
   EventPool events(&fail);
   hipStream_t s0 = ss->main, s1 = ss->side, sh = ss->h2d, sd = ss->d2h;
@@ -1301,7 +1313,9 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
       return;
     }
     if (!narrow) {
-      copy_col_rows(fail, pl, j, r0, r1, dcol, host_col(hA, j), true, sh, &h2d_bytes, &cprof, stage_in);
+      for (int h = 0; h < arrays; ++h)
+        copy_col_rows(fail, pl, j, r0, r1, dcol + h * dev_half, host_col(hA, j) + h * host_half, true, sh,
+                      &h2d_bytes, &cprof, stage_in);
       return;
     }
     CopyProfile::Scope timed(&cprof, 0, sh);
@@ -1362,7 +1376,9 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
     };
     auto write_back = [&](int64_t k) {
       fail.check(hipStreamWaitEvent(sd, final_ev[k], 0));
-      copy_col_rows(fail, pl, k, k * bs, n, cols[k].base, host_col(hOut, k), false, sd, &d2h_bytes, &cprof, stage_out);
+      for (int h = 0; h < arrays; ++h)
+        copy_col_rows(fail, pl, k, k * bs, n, cols[k].base + h * dev_half, host_col(hOut, k) + h * host_half, false,
+                      sd, &d2h_bytes, &cprof, stage_out);
       hipEvent_t sv = events.get();
       fail.check(hipEventRecord(sv, sd));
       saved.push_back(sv);
@@ -1429,11 +1445,13 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
           if (b_free[q]) MDET_HIP(fail, hipStreamWaitEvent(sh, b_free[q], 0));
           if (k == 0)
             for (int64_t i = j0; i < j1; ++i) upload_row(i);
-          {
+          for (int h = 0; h < arrays; ++h) {
             const size_t nbytes = (size_t)(rows_end_J - j0 * bs) * bs * sizeof(T);
             CopyProfile::Scope timed(&cprof, 0, sh);
-            if (stage_out) stage_out->to_device(bpool[q], nbytes, hk + (j0 - k) * bs * bs, nbytes, 1, sh);
-            else MDET_HIP(fail, hipMemcpyAsync(bpool[q], hk + (j0 - k) * bs * bs, nbytes, hipMemcpyHostToDevice, sh));
+            T* dst = bpool[q] + h * dev_half;
+            const T* src = hk + h * host_half + (j0 - k) * bs * bs;
+            if (stage_out) stage_out->to_device(dst, nbytes, src, nbytes, 1, sh);
+            else MDET_HIP(fail, hipMemcpyAsync(dst, src, nbytes, hipMemcpyHostToDevice, sh));
             h2d_bytes += nbytes;
           }
           if (!b_ready[q]) b_ready[q] = events.get();
@@ -1454,12 +1472,14 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
             if (k == 0) upload_row(i);
             if (slot_free[sl]) MDET_HIP(fail, hipStreamWaitEvent(sh, slot_free[sl], 0));
             const size_t nbytes = (size_t)wi * bs * sizeof(T);
-            {
+            for (int h = 0; h < arrays; ++h) {
               CopyProfile::Scope timed(&cprof, 0, sh);
-              if (stage_out) stage_out->to_device(ring[sl], nbytes, hk + (i - k) * bs * bs, nbytes, 1, sh);
-              else MDET_HIP(fail, hipMemcpyAsync(ring[sl], hk + (i - k) * bs * bs, nbytes, hipMemcpyHostToDevice, sh));
+              T* dst = ring[sl] + h * dev_half;
+              const T* src = hk + h * host_half + (i - k) * bs * bs;
+              if (stage_out) stage_out->to_device(dst, nbytes, src, nbytes, 1, sh);
+              else MDET_HIP(fail, hipMemcpyAsync(dst, src, nbytes, hipMemcpyHostToDevice, sh));
+              h2d_bytes += nbytes;
             }
-            h2d_bytes += nbytes;
             if (!slot_ready[sl]) slot_ready[sl] = events.get();
             MDET_HIP(fail, hipEventRecord(slot_ready[sl], sh));
             MDET_HIP(fail, hipStreamWaitEvent(s0, slot_ready[sl], 0));
@@ -1467,7 +1487,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
             // The streamed rows are the left operand of one update per column of the
             // group: scaled by the pivots once, in place (W = L D), they serve all of
             // them through the kernel that scales nothing.
-            const bool prescaled = !L.spd && wc > 1;
+            const bool prescaled = !L.spd && wc > 1 && !pl.general;
             if (prescaled) {
               const int64_t vecs = wi * (bs / (16 / (int64_t)sizeof(T)));
               const unsigned grid = (unsigned)std::min<int64_t>((vecs + 255) / 256, 4096);
@@ -1523,12 +1543,15 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
   res->bytes_d2h = d2h_bytes;
   res->t_h2d = cprof.collect(0);
   res->t_d2h = cprof.collect(1);
-  res->dev_bytes_high_water = sa.total + pl.stage_bytes + arena_used;
+  res->dev_bytes_high_water = sa.total + pl.stage_bytes + (pl.general ? pl.arena_half : 0) + arena_used;
   if (prov_rc != MDET_OK) return prov_rc;
   if (stager_in.io_failed() || stager_out.io_failed()) return MDET_EIO;
   if (!fail.ok()) { res->hip_error = fail.code; return MDET_EHIP; }
   if (rc != MDET_OK) return rc;
-  return finish_result(o, res);
+  rc = finish_result(o, res);
+  // the permutation's sign: one factor of -1 for every leaf with an odd row order
+  if (pl.general && (o.flags.odd_leaves & 1ull)) res->sign = -res->sign;
+  return rc;
 }
 
 // Runs the host path in the arithmetic's type.  hA: the matrix as stored (host memory; ignored
@@ -1543,17 +1566,19 @@ static int logdet_host_any(const mdet_params* p, void* hA, mdet_result* res, voi
   if (rc != MDET_OK) return rc;
   PinnedBuf scratch;
   std::unique_ptr<char[]> plain_scratch;
+  if (pl.general && provider) return MDET_EINVAL;           // the callback's blocks are those of one triangle
   const bool own_store = pl.widen || provider != nullptr;   // the factors cannot go where the matrix is
   void* hOut = own_store ? nullptr : hA;
+  const uint64_t store_bytes = (pl.general ? 2 : 1) * pl.layout_bytes;
   if (pl.out_of_core && (!p->overwrite || own_store)) {
     if (p->host_scratch) {
-      if (p->host_scratch_bytes < pl.layout_bytes) return MDET_ENOMEM_HOST;
+      if (p->host_scratch_bytes < store_bytes) return MDET_ENOMEM_HOST;
       hOut = p->host_scratch;
-    } else if (scratch.alloc(pl.layout_bytes) == MDET_OK) {
+    } else if (scratch.alloc(store_bytes) == MDET_OK) {
       hOut = scratch.p;
     } else {
       // more than can be pinned: ordinary memory, which the host path stages itself
-      plain_scratch.reset(new (std::nothrow) char[pl.layout_bytes ? pl.layout_bytes : 1]);
+      plain_scratch.reset(new (std::nothrow) char[store_bytes ? store_bytes : 1]);
       if (!plain_scratch) return MDET_ENOMEM_HOST;
       hOut = plain_scratch.get();
     }
@@ -1590,13 +1615,15 @@ static int logdet_file_any(const mdet_params* p, const char* matrix_path, const 
   in.fd = ::open(matrix_path, in_place ? O_RDWR : O_RDONLY);
   if (in.fd < 0) return MDET_EIO;
   struct stat sb;
-  if (::fstat(in.fd, &sb) != 0 || (uint64_t)sb.st_size < pl.layout_bytes / pl.beta * pl.src_beta) return MDET_EIO;
+  const uint64_t arrays = pl.general ? 2 : 1;
+  if (::fstat(in.fd, &sb) != 0 || (uint64_t)sb.st_size < arrays * (pl.layout_bytes / pl.beta * pl.src_beta))
+    return MDET_EIO;
   int fd_out = in.fd;
   if (writes && !in_place) {
     if (!scratch_path) return MDET_EINVAL;
     out.fd = ::open(scratch_path, O_RDWR | O_CREAT, 0600);
     if (out.fd < 0) return MDET_EIO;
-    if (::ftruncate(out.fd, (off_t)pl.layout_bytes) != 0) return MDET_EIO;
+    if (::ftruncate(out.fd, (off_t)(arrays * pl.layout_bytes)) != 0) return MDET_EIO;
     fd_out = out.fd;
   }
   HostSource src;

@@ -34,7 +34,9 @@ struct Plan {
   bool need_copy = false;          // device input: work on a copy (overwrite = 0)
   bool pivot = false;              // MDET_FLAG_PIVOT
   bool general = false;            // MDET_FLAG_GENERAL: P A = L D U, two triangular arrays
-  uint64_t q_bytes = 0;            // the second of them
+  uint64_t q_bytes = 0;            // the second of them (device input)
+  uint64_t arena_half = 0;         // host input: bytes of block columns and streamed blocks of ONE array
+                                   // (a general matrix has two, the second arena_half bytes after the first)
   uint64_t small_bytes = 0;        // pivots, reciprocals, flags, reduction scratch
   uint64_t layout_bytes = 0;       // packed lower block-column layout
   uint64_t copy_bytes = 0;
@@ -114,10 +116,10 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
   pl.device_input = device_input;
   pl.tile_bytes = (uint64_t)pl.bs * pl.bs * pl.beta;
   pl.pivot = (p.flags & MDET_FLAG_PIVOT) != 0;
-  // general matrix: resident device input only, in the arithmetic of its own type; the
-  // row order inside each leaf is always recorded
+  // general matrix: in the arithmetic of its own type; the row order inside each leaf is
+  // always recorded.  From host memory both triangles travel: twice the arrays, twice the traffic
   pl.general = (p.flags & MDET_FLAG_GENERAL) != 0;
-  if (pl.general && (!device_input || widen || (p.flags & MDET_FLAG_PIVOT))) return MDET_EINVAL;
+  if (pl.general && (widen || (p.flags & MDET_FLAG_PIVOT))) return MDET_EINVAL;
   if (pl.general && (p.flags & MDET_FLAG_ASSUME_SPD)) return MDET_EINVAL;
   if (pl.general) pl.pivot = true;
   if (pl.pivot && (p.flags & MDET_FLAG_ASSUME_SPD)) return MDET_EINVAL;   // nothing to choose from
@@ -139,6 +141,7 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
                           !(p.flags & MDET_FLAG_ASSUME_SPD) && !pl.general && pl.T >= 2)
                              ? 2 * align256((uint64_t)pl.n * pl.bs * pl.beta) : 0;
   pl.wcopy_optional = wcopy_auto && wcopy != 0;
+  pl.arena_half = 0;
 
   if (device_input) {
     const int vec = 16 / pl.beta;
@@ -179,15 +182,17 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
     pl.stage_bytes = align256(st);
   }
   pl.small_bytes += pl.stage_bytes;      // counted with the fixed part of the workspace
-  const uint64_t incore = pl.small_bytes + dev_layout;
+  const uint64_t arrays = pl.general ? 2 : 1;
+  const uint64_t incore = pl.small_bytes + arrays * dev_layout;
   if (!force_ooc && (budget == 0 || incore <= budget)) {
     pl.out_of_core = false;
     pl.dev_bytes = incore;
+    pl.arena_half = dev_layout;
     if (wcopy && (!budget || incore + wcopy <= budget)) {
       pl.wcopy_bytes = wcopy;
       pl.dev_bytes += wcopy;
     }
-    pl.h2d = pl.layout_bytes / pl.beta * pl.src_beta;
+    pl.h2d = arrays * (pl.layout_bytes / pl.beta * pl.src_beta);
     pl.panels.push_back({0, pl.T, pl.layout_bytes});
     return MDET_OK;
   }
@@ -195,7 +200,7 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
   // ---- out-of-core: greedy groups of block columns ------------------------
   pl.out_of_core = true;
   // with no cap at all (forced streaming) behave as if a quarter of the layout were allowed
-  uint64_t cap = budget ? budget : (pl.small_bytes + pl.layout_bytes / 4 + 8 * pl.tile_bytes);
+  uint64_t cap = budget ? budget : (pl.small_bytes + arrays * (pl.layout_bytes / 4 + 8 * pl.tile_bytes));
   uint64_t peak = 0;
   int64_t j0 = 0;
   while (j0 < pl.T) {
@@ -207,28 +212,29 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
       // streamed factor blocks: two sets of wc row blocks of the group's own rows
       // (operands reused by every streamed block) plus the ring
       uint64_t stream = (j0 > 0) ? (2 * wc + pl.ring_tiles) * align256(pl.tile_bytes) : 0;
-      if (pl.small_bytes + cand + stream > cap) break;
+      if (pl.small_bytes + arrays * (cand + stream) > cap) break;
       resident = cand;
       ++j1;
     }
     if (j1 == j0) return MDET_EBUDGET;   // not even one block column fits
     uint64_t wc = (uint64_t)(j1 - j0);
     uint64_t stream = (j0 > 0) ? (2 * wc + pl.ring_tiles) * align256(pl.tile_bytes) : 0;
-    uint64_t use = pl.small_bytes + resident + stream;
+    uint64_t use = pl.small_bytes + arrays * (resident + stream);
     if (use > peak) peak = use;
+    if (resident + stream > pl.arena_half) pl.arena_half = resident + stream;
     pl.panels.push_back({j0, j1, resident});
     // traffic: originals in, factors out, and every earlier column's rows from j0 down
     for (int64_t j = j0; j < j1; ++j) {
-      pl.h2d += pl.col_bytes(j) / pl.beta * pl.src_beta;
-      pl.d2h += pl.col_bytes(j);
+      pl.h2d += arrays * (pl.col_bytes(j) / pl.beta * pl.src_beta);
+      pl.d2h += arrays * pl.col_bytes(j);
     }
     for (int64_t k = 0; k < j0; ++k)
-      pl.h2d += (uint64_t)pl.col_rows(j0) * pl.col_width(k) * pl.beta;
+      pl.h2d += arrays * ((uint64_t)pl.col_rows(j0) * pl.col_width(k) * pl.beta);
     j0 = j1;
   }
   pl.dev_bytes = peak;
   // the factors are always in the arithmetic's type: a matrix stored narrower cannot take them
-  pl.host_bytes = (p.overwrite && !widen) ? 0 : pl.layout_bytes;
+  pl.host_bytes = (p.overwrite && !widen) ? 0 : arrays * pl.layout_bytes;
   return MDET_OK;
 }
 

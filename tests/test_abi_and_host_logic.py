@@ -154,7 +154,7 @@ def test_plan_for_a_general_matrix(M):
         assert need(n, bs, overwrite=False, flags=M.FLAG_GENERAL) == gen + n * n * 8
     assert M.mdet_plan(1000, "f32", 128, overwrite=True, flags=M.FLAG_GENERAL,
                        for_device_input=True).dev_bytes_needed >= 1000 * 1000 * 4
-    for kw in (dict(for_device_input=False), dict(for_device_input=True, flags_extra=M.FLAG_PIVOT),
+    for kw in (dict(for_device_input=False, flags_extra=M.FLAG_PIVOT), dict(for_device_input=True, flags_extra=M.FLAG_PIVOT),
                dict(for_device_input=True, flags_extra=M.FLAG_ASSUME_SPD)):
         with pytest.raises(M.MemdetError) as e:
             M.mdet_plan(4096, "f64", 512, flags=M.FLAG_GENERAL | kw.pop("flags_extra", 0), **kw)
@@ -165,6 +165,18 @@ def test_plan_for_a_general_matrix(M):
     with pytest.raises(M.MemdetError) as e:
         M.mdet_plan(4096, "f64", 512, 64 << 20, overwrite=True, flags=M.FLAG_GENERAL, for_device_input=True)
     assert e.value.status == M.Status.EBUDGET
+    # from host memory under a cap (Alg. 1, the memory-constrained generic case): both triangles'
+    # block columns are resident, streamed and written back together - twice the symmetric figures
+    n, b = 32768, 2048
+    sym = M.mdet_plan(n, "f64", b, 3 << 30)
+    gen = M.mdet_plan(n, "f64", b, 6 << 30, flags=M.FLAG_GENERAL)
+    assert gen.out_of_core and gen.dev_bytes_needed <= 6 << 30
+    assert gen.num_superpanels == sym.num_superpanels
+    assert gen.stream_bytes_h2d == 2 * sym.stream_bytes_h2d and gen.stream_bytes_d2h == 2 * sym.stream_bytes_d2h
+    assert M.mdet_plan(n, "f64", b, 6 << 30, overwrite=False, flags=M.FLAG_GENERAL).host_bytes_needed == \
+        2 * sym.host_matrix_bytes
+    whole = M.mdet_plan(4096, "f64", 512, flags=M.FLAG_GENERAL)
+    assert not whole.out_of_core and whole.dev_bytes_needed >= 2 * whole.host_matrix_bytes
 
 
 def test_plan_fp32_storage_with_fp64_arithmetic(M):

@@ -308,9 +308,8 @@ def test_bad_arguments_and_workspace(M):
         M.mdet_logdet_device(dev(np.eye(128, dtype=np.float32)), block_size=64,
                              flags=M.FLAG_GENERAL | M.FLAG_COMPUTE_F64)
     assert e.value.status == M.Status.EINVAL
-    packed = torch.zeros(128 * 64 * 3, dtype=torch.float64)
-    with pytest.raises(M.MemdetError) as e:
-        M.mdet_logdet_host(packed, 128, 64, flags=M.FLAG_GENERAL)
+    with pytest.raises(M.MemdetError) as e:          # the callback supplies one triangle's blocks only
+        M.mdet_logdet_provider(lambda *args: 0, 128, "f64", 64, flags=M.FLAG_GENERAL)
     assert e.value.status == M.Status.EINVAL
     # the workspace grows by the transposed upper triangle and the permutation
     plain, _ = M.mdet_workspace_query(4096, "f64", 512, for_device_input=True)
@@ -391,3 +390,98 @@ def test_empty_matrix_unaligned_views_and_two_callers(M):
         t.join()
     assert out[0].logabsdet == out[1].logabsdet and out[0].sign == out[1].sign == o.sign
     assert rel(out[0].logabsdet, o.logabsdet) <= TOL["f64"]
+
+
+# ---------------------------------------------------------------------------
+# the memory-constrained generic case (Alg. 1): the matrix in host memory or a file, under a budget
+# ---------------------------------------------------------------------------
+def min_budget_general(M, n, dtype, bs):
+    lo, hi = 0, 1 << 40
+    while hi - lo > 4096:
+        mid = (lo + hi) // 2
+        try:
+            M.mdet_plan(n, dtype, bs, mid, flags=M.FLAG_GENERAL | M.FLAG_FORCE_OUT_OF_CORE)
+            hi = mid
+        except M.MemdetError:
+            lo = mid
+    return hi
+
+
+@pytest.mark.parametrize("kind,n,bs,dtype", [("dominant", 1024, 128, "f64"), ("dominant", 1100, 192, "f64"),
+                                             ("gaussian", 1280, 256, "f64"), ("dominant", 777, 64, "f64"),
+                                             ("dominant", 1500, 256, "f32")])
+def test_general_matrix_from_host_memory_in_core_and_streamed(M, kind, n, bs, dtype):
+    npdt = np.float64 if dtype == "f64" else np.float32
+    a = (shuffled_dominant(n + bs, n, npdt) if kind == "dominant" else gaussian(n + bs, n, npdt))
+    o = oracle.lu_logdet(a.astype(np.float64) if dtype == "f64" else a)
+    ref, pref, dref, _ = run_device(M, a, bs)
+    assert ref.sign == o.sign and rel(ref.logabsdet, o.logabsdet) <= TOL[dtype]
+    G = M.FLAG_GENERAL
+    h = M.pack_general_block_columns(torch.from_numpy(a), bs, pin=True)
+    keep = h.clone()
+    tdt = torch.float64 if dtype == "f64" else torch.float32
+    d = torch.empty(n, dtype=tdt)
+    perm = torch.full((n,), -1, dtype=torch.int32)
+    r0 = M.mdet_logdet_host(h.clone(), n, bs, flags=G, diag=d, perm=perm)
+    assert not r0.out_of_core and r0.status == 0
+    # the same arithmetic as the resident device run: same bits, same row order
+    assert r0.logabsdet == ref.logabsdet and r0.sign == ref.sign
+    assert np.array_equal(d.numpy().astype(np.float64), dref) and np.array_equal(perm.numpy().astype(np.int64), pref)
+    assert r0.bytes_h2d == M.mdet_plan(n, dtype, bs, flags=G).stream_bytes_h2d == h.numel() * h.element_size()
+    lo = min_budget_general(M, n, dtype, bs)
+    full = M.mdet_plan(n, dtype, bs, flags=G).dev_bytes_needed
+    groups = set()
+    for budget in (lo, (lo + full) // 2, int(lo * 1.3)):
+        plan = M.mdet_plan(n, dtype, bs, budget, overwrite=False, flags=G | M.FLAG_FORCE_OUT_OF_CORE)
+        assert plan.host_bytes_needed == h.numel() * h.element_size()
+        d2 = torch.empty(n, dtype=tdt)
+        p2 = torch.full((n,), -1, dtype=torch.int32)
+        res = M.mdet_logdet_host(h, n, bs, mem_budget=budget, overwrite=False, flags=G | M.FLAG_FORCE_OUT_OF_CORE,
+                                 diag=d2, perm=p2)
+        assert res.out_of_core and res.status == 0 and res.dev_bytes_high_water <= budget
+        assert res.logabsdet == r0.logabsdet and res.sign == r0.sign
+        assert torch.equal(d2, d) and torch.equal(p2, perm)
+        assert (res.bytes_h2d, res.num_superpanels) == (plan.stream_bytes_h2d, plan.num_superpanels)
+        assert res.flops == pytest.approx(2 * 2 * (n ** 3 - n) / 6, rel=1e-12)
+        assert torch.equal(h, keep)                       # overwrite = 0: the input stays as it is
+        groups.add(res.num_superpanels)
+    assert max(groups) >= 3
+    # in place: the layouts end up holding L, D and U^T of the streamed groups
+    hw = h.clone()
+    res = M.mdet_logdet_host(hw, n, bs, mem_budget=lo, flags=G | M.FLAG_FORCE_OUT_OF_CORE)
+    assert res.logabsdet == r0.logabsdet and not torch.equal(hw, keep)
+    first_diag = hw[:bs * bs].view(bs, bs).diagonal() if n >= bs else None
+    if first_diag is not None:
+        assert np.array_equal(first_diag.numpy(), d.numpy()[:bs])          # D on the diagonal of the first layout
+
+
+def test_general_matrix_in_a_file_and_error_paths(M, tmp_path):
+    n, bs = 1100, 192
+    a = shuffled_dominant(33, n)
+    o = oracle.lu_logdet(a)
+    G = M.FLAG_GENERAL | M.FLAG_FORCE_OUT_OF_CORE
+    h = M.pack_general_block_columns(torch.from_numpy(a), bs)
+    path, spath = str(tmp_path / "m.bin"), str(tmp_path / "s.bin")
+    h.numpy().tofile(path)
+    lo = min_budget_general(M, n, "f64", bs)
+    ref = M.mdet_logdet_host(h.clone(), n, bs, mem_budget=lo, flags=G)
+    perm = torch.full((n,), -1, dtype=torch.int32)
+    res = M.mdet_logdet_file(path, n, "f64", bs, mem_budget=lo, overwrite=False, scratch_path=spath, flags=G, perm=perm)
+    assert res.out_of_core and res.logabsdet == ref.logabsdet and res.sign == ref.sign == o.sign
+    assert rel(res.logabsdet, o.logabsdet) <= TOL["f64"] and np.array_equal(perm.numpy(), o.perm)
+    assert np.array_equal(np.fromfile(path, dtype=np.float64), h.numpy())
+    # a file that holds one triangle only is too short
+    short = str(tmp_path / "short.bin")
+    h.numpy()[: h.numel() // 2].tofile(short)
+    bad = M.mdet_logdet_file(short, n, "f64", bs, flags=M.FLAG_GENERAL, raise_on_error=False)
+    assert bad.status == M.Status.EIO
+    # a zero column: singular at the oracle's index, also when it is met in a streamed group
+    z = a.copy()
+    z[:, 900] = 0.0
+    oz = oracle.lu_logdet(z)
+    rz = M.mdet_logdet_host(M.pack_general_block_columns(torch.from_numpy(z), bs), n, bs, mem_budget=lo, flags=G)
+    assert rz.status == M.Status.ESINGULAR and rz.sign == 0 == oz.sign and rz.bad_pivot_index == 900
+    # budget below two block columns' worth
+    with pytest.raises(M.MemdetError) as e:
+        M.mdet_logdet_host(h, n, bs, mem_budget=lo - 8192, flags=M.FLAG_GENERAL)
+    assert e.value.status == M.Status.EBUDGET

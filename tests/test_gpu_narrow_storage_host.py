@@ -212,6 +212,7 @@ def test_profile_covers_both_trailing_update_kernels_and_calibration_kernels_run
     torch.cuda.synchronize()
     assert torch.equal(dst, src)
     out = torch.empty(65536, dtype=torch.float64, device="cuda")
-    flop = M.mdet_step_mfma_peak("f64", 256, 10, out)
-    torch.cuda.synchronize()
-    assert flop == 256 * 4 * 10 * 16 * 2048
+    for nacc in (4, 16):
+        flop = M.mdet_step_mfma_peak("f64", 256, 10, out, accumulators=nacc)
+        torch.cuda.synchronize()
+        assert flop == 256 * 4 * 10 * 16 * 2048
