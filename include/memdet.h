@@ -302,6 +302,38 @@ int mdet_logdet_device(const mdet_params* params, void* dA, int64_t ld,
                        mdet_result* result, void* diag);
 
 /*
+ * mdet_logdet_device_noalloc: mdet_logdet_device for callers that cannot allocate device
+ * memory or wait: code that records its work into a HIP graph, tight serving loops, harnesses
+ * that forbid hipMalloc.  The call allocates and frees nothing on the device or through the
+ * runtime (no stream, no event) and does not synchronise: it only queues kernels and two
+ * device-to-device copies on params->stream, all in order on that one stream (the schedule of
+ * MDET_FLAG_NO_LOOKAHEAD, whose results are bit-identical to the two-stream schedule).  The
+ * small workspace of the path (pivots, their reciprocals, leaf inverses, flags, partial sums,
+ * permutation) lives in a fixed array of MDET_NOALLOC_SCRATCH_BYTES in device memory that
+ * belongs to the library; each GPU the library runs on holds its own copy until the process
+ * ends.  Hence:
+ *   - n is limited by that array: about 16 n + 64 KiB bytes in fp64 (8 n in fp32, 4 n more
+ *     with MDET_FLAG_PIVOT), i.e. n <= ~250 000; beyond it MDET_ENOMEM_DEVICE.
+ *   - overwrite must be 1 (the matrix is factored in place; rows 16-byte aligned), and of the
+ *     flags only MDET_FLAG_ASSUME_SPD and MDET_FLAG_PIVOT are taken; mem_budget_bytes,
+ *     dev_workspace and host_scratch are ignored.  Anything else: MDET_EINVAL.
+ *   - all calls on one GPU share the array, which keeps the last call's contents (what must
+ *     start clean is cleared by the call itself): calls that overlap on one GPU, on whatever
+ *     streams, race.  Calls on different GPUs do not.
+ *   dA, ld, diag (DEVICE, n elements of dtype or NULL), params->perm (DEVICE): as for
+ *   mdet_logdet_device.
+ *   out   DEVICE pointer to 5 doubles, valid once the stream has run the work: [0] log|det A|,
+ *         [1] sign, [2] number of negative pivots, [3] index of the first zero or non-finite
+ *         pivot (-1: none), [4] the mdet_status the synchronous entry point would have
+ *         returned (MDET_OK, MDET_ESINGULAR, MDET_ENONFINITE, MDET_ENOTPOSDEF), with [0], [1]
+ *         set as that entry point sets logabsdet and sign.
+ * Returns MDET_OK when everything was queued.
+ */
+#define MDET_NOALLOC_SCRATCH_BYTES (4ull << 20)
+int mdet_logdet_device_noalloc(const mdet_params* params, void* dA, int64_t ld, double* out,
+                               void* diag);
+
+/*
  * mdet_logdet_host: matrix in HOST memory (pinned or not: memory that is not pinned
  * is moved through pinned chunks of the library's own, by a few threads that live for
  * the length of the call), in the packed lower block-column layout:

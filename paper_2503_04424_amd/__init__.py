@@ -13,6 +13,6 @@ from .binding import (  # noqa: F401
     mdet_paper_fma_count, mdet_step_schur_update, mdet_step_panel_factor, mdet_step_panel_factor_pivoted, mdet_step_panel_factor_general,
     mdet_step_logdet_reduce, mdet_strerror, mdet_version,
     mdet_sequence_workspace_query, mdet_principal_logdets, mdet_flodance_fit, mdet_flodance_eval,
-    mdet_step_copy, mdet_step_mfma_peak,
+    mdet_step_copy, mdet_step_mfma_peak, mdet_logdet_device_noalloc,
     pack_lower_block_columns, pack_general_block_columns,
 )

@@ -79,6 +79,7 @@ EXPORTS = [
     "mdet_step_logdet_reduce", "mdet_strerror", "mdet_version",
     "mdet_sequence_workspace_query", "mdet_principal_logdets", "mdet_flodance_fit",
     "mdet_flodance_eval", "mdet_step_copy", "mdet_step_mfma_peak",
+    "mdet_logdet_device_noalloc",
 ]
 
 _lib = None
@@ -118,6 +119,7 @@ def load():
     L.mdet_principal_logdets.argtypes = [i32, vp, i64, vp, vp, u64, vp]
     L.mdet_flodance_fit.argtypes = [vp, i64, i64, i64, i64, i32, vp, vp, u64, vp]
     L.mdet_flodance_eval.argtypes = [vp, i32, vp, i64, vp, vp]
+    L.mdet_logdet_device_noalloc.argtypes = [C.POINTER(_Params), vp, i64, vp, vp]
     L.mdet_step_copy.argtypes = [vp, vp, u64, vp]
     L.mdet_step_mfma_peak.argtypes = [i32, i32, i32, i32, vp, C.POINTER(C.c_double), vp]
     L.mdet_strerror.argtypes = [C.c_int]
@@ -316,6 +318,22 @@ def mdet_logdet_device(a, block_size=0, mem_budget=0, overwrite=False, flags=0, 
     if st not in _SOFT and raise_on_error:
         raise MemdetError(st, r)
     return _result(st, r)
+
+
+def mdet_logdet_device_noalloc(a, out, block_size=0, flags=0, diag=None, stream=None, perm=None) -> int:
+    """Queues the in-place factorisation of ``a`` on ``stream`` without allocating anything;
+    ``out``: 5 float64 on the GPU (log|det|, sign, negative pivots, first bad pivot, status).
+    Returns the status of the queueing itself."""
+    if a.dim() != 2 or a.shape[0] != a.shape[1] or not a.is_cuda or (a.numel() and a.stride(1) != 1):
+        raise ValueError("square row-major CUDA tensor expected")
+    import torch
+    if out.dtype != torch.float64 or out.numel() < 5 or not out.is_cuda:
+        raise ValueError("out must be a CUDA tensor of 5 float64")
+    n = a.shape[0]
+    ld = a.stride(0) if n > 1 else max(n, 1)
+    p = _params(n, a.dtype, block_size, 0, True, flags, _stream_handle(stream), perm=_perm_ptr(perm, n, True))
+    return load().mdet_logdet_device_noalloc(C.byref(p), C.c_void_p(a.data_ptr()), ld, C.c_void_p(out.data_ptr()),
+                                             C.c_void_p(diag.data_ptr()) if diag is not None else None)
 
 
 def mdet_logdet_host(packed, n, block_size, mem_budget=0, overwrite=True, flags=0, diag=None,

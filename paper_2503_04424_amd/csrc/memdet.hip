@@ -856,6 +856,86 @@ static int logdet_device_t(const mdet_params& p, const Plan& plan, T* dA, int64_
 
 
 // ---------------------------------------------------------------------------
+// mdet_logdet_device_noalloc: the same path for callers that cannot allocate
+// ---------------------------------------------------------------------------
+// The workspace of mdet_logdet_device (pivots, reciprocals, inverses of the leaves' diagonal
+// sub-blocks, flags, partial sums, permutation) lives in a fixed array in device memory that
+// belongs to the library; each GPU holds its own copy of it until the process ends.
+constexpr uint64_t NOALLOC_SCRATCH_BYTES = MDET_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+// In host code the array's name is only a handle: its address on a device is asked for once,
+// with that device current, and kept.
+static char* g_scratch_ptr[64];
+
+static hipError_t scratch_address(int dev, char** out) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[dev] = (char*)ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+// out[0] = log|det|, out[1] = sign, out[2] = negative pivots, out[3] = index of the first zero
+// or non-finite pivot (-1: none), out[4] = the status the synchronous entry point would return
+__global__ void noalloc_finish_kernel(const double* __restrict__ red, const DevFlags* __restrict__ flags,
+                                      double* __restrict__ out) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  double logabs = red[0], sign = red[1];
+  int status = MDET_OK;
+  double bad = -1.0;
+  if (flags->first_bad != ~0ull) {
+    bad = (double)flags->first_bad;
+    sign = 0.0;
+    if (flags->bad_kind == 1ull) { logabs = -HUGE_VAL; status = MDET_ESINGULAR; }
+    else if (flags->bad_kind == 4ull) { logabs = __builtin_nan(""); status = MDET_ENOTPOSDEF; }
+    else { logabs = __builtin_nan(""); status = MDET_ENONFINITE; }
+  } else if (!(logabs - logabs == 0.0)) {
+    status = MDET_ENONFINITE;
+  }
+  out[0] = logabs;
+  out[1] = sign;
+  out[2] = red[2];
+  out[3] = bad;
+  out[4] = (double)status;
+}
+
+template <typename T>
+static int logdet_device_noalloc_t(const mdet_params& p, const Plan& pl, char* base, T* dA, int64_t ld,
+                                   double* out_dev, T* diag) {
+  HipFail fail;
+  const SmallArea sa = small_area(pl.n, pl.T, pl.beta, pl.pivot);
+  Launcher<T> L;
+  L.fail = &fail;
+  L.spd = (p.flags & MDET_FLAG_ASSUME_SPD) != 0;
+  bind_small(L, base, sa);
+  double* partial = (double*)(base + sa.partial);
+  double* red = (double*)(base + sa.out);
+  double* running = (double*)(base + sa.running);
+  hipStream_t st = (hipStream_t)p.stream;
+  // everything on the caller's stream, in order: no second stream, no events
+  EventPool events(&fail);       // never asked for an event without look-ahead
+  reset_flags(L, st);
+  std::vector<ColRef<T>> cols((size_t)pl.T);
+  for (int64_t j = 0; j < pl.T; ++j) cols[j] = {dA + j * pl.bs * ld + j * pl.bs, ld};
+  int rc = factor_resident(L, pl, cols, 0, pl.T, true, false, st, st, events);
+  if (rc != MDET_OK) return rc;
+  L.reduce(st, pl.n, pl.bs, pl.T, partial, red, running);
+  hipLaunchKernelGGL(noalloc_finish_kernel, dim3(1), dim3(64), 0, st, (const double*)red,
+                     (const DevFlags*)L.flags, out_dev);
+  MDET_HIP(fail, hipGetLastError());
+  if (diag && pl.n > 0)
+    MDET_HIP(fail, hipMemcpyAsync(diag, L.dvec, pl.n * sizeof(T), hipMemcpyDeviceToDevice, st));
+  if (L.perm && p.perm && pl.n > 0)
+    MDET_HIP(fail, hipMemcpyAsync(p.perm, L.perm, pl.n * sizeof(int), hipMemcpyDeviceToDevice, st));
+  return fail.ok() ? MDET_OK : MDET_EHIP;
+}
+
+// ---------------------------------------------------------------------------
 // mdet_logdet_host: packed lower block-column layout in host memory
 // ---------------------------------------------------------------------------
 // Copy of rows [r0, r1) of block column j between the host layout (leading
@@ -1743,6 +1823,33 @@ int mdet_logdet_device(const mdet_params* p, void* dA, int64_t ld, mdet_result* 
   else rc = logdet_device_t<float>(*p, pl, (float*)dA, ld, res, (float*)diag);
   res->t_total = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
   return rc;
+}
+
+int mdet_logdet_device_noalloc(const mdet_params* p, void* dA, int64_t ld, double* out, void* diag) {
+  if (!params_ok(p) || !out) return MDET_EINVAL;
+  if (p->n > 0 && (!dA || ld < p->n || ((uintptr_t)dA & 15u))) return MDET_EINVAL;
+  if (p->dtype != MDET_F64 && p->dtype != MDET_F32) return MDET_EINVAL;
+  // in place only (a copy would be workspace of the matrix's size), plain symmetric forms only
+  if (!p->overwrite || (p->flags & ~(uint32_t)(MDET_FLAG_NO_LOOKAHEAD | MDET_FLAG_ASSUME_SPD | MDET_FLAG_PIVOT)))
+    return MDET_EINVAL;
+  mdet_params q = *p;
+  q.flags |= MDET_FLAG_NO_LOOKAHEAD;
+  q.mem_budget_bytes = 0;
+  q.dev_workspace = nullptr;
+  Plan pl;
+  int rc = make_plan(q, true, ld, pl);
+  if (rc != MDET_OK) return rc;
+  if (pl.need_copy) return MDET_EINVAL;            // rows not 16-byte aligned
+  // the fixed array must hold the whole small area; the optional pivot-scaled copies are not used
+  pl.wcopy_bytes = 0;
+  if (small_area(pl.n, pl.T, pl.beta, pl.pivot).total > NOALLOC_SCRATCH_BYTES) return MDET_ENOMEM_DEVICE;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return MDET_EHIP; }
+  char* base = nullptr;
+  if (scratch_address(dev, &base) != hipSuccess) { (void)hipGetLastError(); return MDET_EHIP; }
+  if (p->dtype == MDET_F64)
+    return logdet_device_noalloc_t<double>(q, pl, base, (double*)dA, ld, out, (double*)diag);
+  return logdet_device_noalloc_t<float>(q, pl, base, (float*)dA, ld, out, (float*)diag);
 }
 
 int mdet_step_schur_update(int32_t dtype, void* C, int64_t ldc, const void* A, int64_t lda,
