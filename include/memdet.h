@@ -164,7 +164,29 @@ typedef struct mdet_params {
                                      with M = S except that row perm[j] of each diagonal
                                      64 x 64 block of M is row j of that block of S.
                                      Costs one more launch per 64 columns; n < 2^31; not
-                                     with MDET_FLAG_ASSUME_SPD (MDET_EINVAL).            */
+                                     with MDET_FLAG_ASSUME_SPD (MDET_EINVAL).  The group of
+                                     64 is this library's unit of factorisation, smaller
+                                     than the paper's block: MDET_FLAG_PIVOT_BLOCK searches
+                                     the whole diagonal block instead, at a price.       */
+
+#define MDET_FLAG_PIVOT_BLOCK 256u /* symmetric pivoting over the whole diagonal block (Sec. 2.2:
+                                     pivoting within each block, none between blocks): as
+                                     MDET_FLAG_PIVOT, but at every step the candidates are ALL
+                                     entries left on the diagonal of the current Schur
+                                     complement inside the block column's own b x b diagonal
+                                     block (b = block_size_used), not only those of a group
+                                     of 64.  perm, diag, sign, log|det| as for MDET_FLAG_PIVOT;
+                                     the stored factor (overwrite = 1) holds, in each diagonal
+                                     b x b block, L and D of that block in pivot order, the
+                                     rows left of it in input order.  1 x 1 pivots only: a
+                                     block whose diagonal is exhausted by zeros ([[0, 1],
+                                     [1, 0]]) ends the call with MDET_ESINGULAR.  Costs one
+                                     small launch per elimination step (about 0.3 ms per 64
+                                     columns) and workspace for two b x b arrays and one
+                                     (n - b) x b array, counted by mdet_plan; every entry
+                                     point takes it; not with MDET_FLAG_PIVOT,
+                                     MDET_FLAG_ASSUME_SPD or MDET_FLAG_GENERAL (MDET_EINVAL),
+                                     b <= 16384.                                          */
 
 #define MDET_FLAG_GENERAL 128u    /* the matrix is not symmetric (Sec. 2.2, Eq. 1 and Alg. 1:
                                      M = P L U for generic matrices, with pivoting inside a

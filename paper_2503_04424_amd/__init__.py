@@ -5,7 +5,7 @@ gfx950); this package only marshals arguments.  PyTorch tensors are used as
 device / pinned-host memory and for the current stream handle.
 """
 from .binding import (  # noqa: F401
-    MDET_F32, MDET_F64, MDET_F16, MDET_BF16, FLAG_NO_LOOKAHEAD, FLAG_FORCE_OUT_OF_CORE, FLAG_PROFILE, FLAG_COMPUTE_F64, FLAG_ASSUME_SPD, FLAG_SCALED_COPY, FLAG_PIVOT, FLAG_GENERAL,
+    MDET_F32, MDET_F64, MDET_F16, MDET_BF16, FLAG_NO_LOOKAHEAD, FLAG_FORCE_OUT_OF_CORE, FLAG_PROFILE, FLAG_COMPUTE_F64, FLAG_ASSUME_SPD, FLAG_SCALED_COPY, FLAG_PIVOT, FLAG_GENERAL, FLAG_PIVOT_BLOCK,
     MemdetError, LogdetResult, PlanInfo, Status,
     lib, lib_path, load,
     mdet_plan, mdet_workspace_query, mdet_logdet_device, mdet_logdet_host,

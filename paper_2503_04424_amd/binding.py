@@ -23,6 +23,7 @@ FLAG_ASSUME_SPD = 16
 FLAG_SCALED_COPY = 32
 FLAG_PIVOT = 64
 FLAG_GENERAL = 128
+FLAG_PIVOT_BLOCK = 256
 
 
 class Status:

@@ -34,6 +34,7 @@
 
 #include "../../include/memdet.h"
 #include "kernels_leaf.h"
+#include "kernels_pivot_block.h"
 #include "kernels_reduce.h"
 #include "kernels_update.h"
 #include "plan.h"
@@ -148,6 +149,21 @@ struct Launcher {
   // diagonal, and perm[j] is the row/column of the input that ended at position j
   // (MDET_FLAG_PIVOT).  The leaf then has a launch of its own.
   int* perm = nullptr;
+  // MDET_FLAG_PIVOT_BLOCK: the pivot is looked for on the whole diagonal block of a block
+  // column (see kernels_pivot_block.h); the workspace it needs, or none
+  struct PivotBlock {
+    T* S = nullptr;
+    T* Lfull = nullptr;
+    T* Y = nullptr;
+    T* Bg = nullptr;
+    T* leaf = nullptr;
+    T* linv = nullptr;
+    T* dg = nullptr;
+    int* active = nullptr;
+    int* piv = nullptr;
+    PbCand* part = nullptr;       // two sets of 64, used in turn
+    int64_t ldl = 0, max_w = 0, max_below = 0;
+  } pb;
   // General matrices (MDET_FLAG_GENERAL; Sec. 2.2, Eq. 1: M = P L U): distance in elements
   // from an entry (i, j), i >= j, of the array the driver works on to the place that holds
   // entry (j, i) of the matrix, in a second array of the same shape.  Every pointer the
@@ -331,6 +347,7 @@ struct Launcher {
   int factor_cols(hipStream_t st, T* P, int64_t ld, int64_t m, int64_t w, int64_t d0,
                   bool first_done = false, T* Wp = nullptr, int64_t wskip = 0) {
     if (w <= 0) return MDET_OK;
+    if (pb.S != nullptr) return factor_cols_pivot_block(st, P, ld, m, w, d0);
     if (w <= LEAF && qoff != 0) {
       // P A = L D U of the leaf, then the rows below it in both halves: the lower half
       // against U^T, the transposed upper half against L with the leaf's row order
@@ -441,6 +458,68 @@ struct Launcher {
     if (!profile) return;
     prof_ref = timing_event_get(fail);
     fail->check(hipEventRecord(prof_ref, st));
+  }
+
+  // A whole block column with the pivots taken from anywhere on its w x w diagonal block
+  // (MDET_FLAG_PIVOT_BLOCK; the scheme is described in kernels_pivot_block.h).  Same
+  // arguments and same result layout as factor_cols: L and D in pivot order in place,
+  // dvec / dinv / perm filled for the columns d0 .. d0 + w.
+  int factor_cols_pivot_block(hipStream_t st, T* P, int64_t ld, int64_t m, int64_t w, int64_t d0) {
+    if (spd || qoff != 0 || !perm || w > pb.max_w || m - w > pb.max_below || m > INT32_MAX) return MDET_EINVAL;
+    const int64_t ldl = pb.ldl, below = m - w;
+    const int nparts = (int)((w + PB_THREADS - 1) / PB_THREADS);
+    if (nparts > 64) return MDET_EINVAL;
+    PbCand* part[2] = {pb.part, pb.part + 64};
+    hipLaunchKernelGGL((pb_init_kernel<T>), dim3((unsigned)nparts), dim3(PB_THREADS), 0, st, (const T*)P, ld, (int)w,
+                       pb.S, ldl, pb.Lfull, ldl, pb.dg, pb.active, part[0]);
+    fail->check(hipGetLastError());
+    ++launches;
+    int cur = 0;
+    int rc = MDET_OK;
+    for (int64_t c0 = 0; c0 < w && rc == MDET_OK; c0 += LEAF) {
+      const int lw = (int)(w - c0 < LEAF ? w - c0 : LEAF);
+      for (int jj = 0; jj < lw; ++jj) {
+        hipLaunchKernelGGL((pb_step_kernel<T>), dim3((unsigned)nparts), dim3(PB_THREADS), 0, st, (const T*)pb.S, ldl,
+                           pb.Lfull, ldl, pb.dg, pb.active, (const PbCand*)part[cur], part[cur ^ 1], nparts, pb.piv,
+                           dvec + d0, dinv + d0, perm + d0, (int)w, (int)c0, jj, (long long)d0, flags);
+        cur ^= 1;
+        ++launches;
+      }
+      fail->check(hipGetLastError());
+      fma += (double)w * lw * (lw - 1) / 2.0;
+      hipLaunchKernelGGL((pb_leaf_kernel<T>), dim3(1), dim3(256), 0, st, (const T*)pb.Lfull, ldl, (const int*)pb.piv,
+                         (int)c0, lw, pb.leaf, pb.linv);
+      fail->check(hipGetLastError());
+      ++launches;
+      // candidates remain: the diagonal block up to date with this group's 64 pivots
+      if (c0 + lw < w)
+        rc = update(st, pb.S, ldl, pb.Lfull + c0, ldl, pb.Lfull + c0, ldl, dvec + d0 + c0, w, w, LEAF, false);
+      if (below > 0 && rc == MDET_OK) {
+        const unsigned grid = (unsigned)std::min<int64_t>((below + 3) / 4, 2048);
+        hipLaunchKernelGGL((pb_gather_kernel<T>), dim3(grid), dim3(256), 0, st, (const T*)(P + w * ld), ld, below, pb.Y,
+                           ldl, (const T*)pb.Lfull, ldl, pb.Bg, ldl, (const int*)pb.piv, (int)c0, lw);
+        fail->check(hipGetLastError());
+        ++launches;
+        // the gathered columns receive everything solved before: Y_new -= Y_old D Bg^T
+        if (c0 > 0) rc = update(st, pb.Y + c0, ldl, pb.Y, ldl, pb.Bg, ldl, dvec + d0, below, lw, c0, false);
+        if (rc != MDET_OK) break;
+        const int64_t nblk = (below + SOLVE_ROWS - 1) / SOLVE_ROWS;
+        hipLaunchKernelGGL((leaf_solve_kernel<T>), dim3((unsigned)nblk), dim3(256), 0, st, pb.Y + c0, ldl, (int)below,
+                           lw, (const T*)pb.leaf, (int64_t)LEAF, (const T*)(dinv + d0 + c0), (const T*)pb.linv,
+                           (T*)nullptr, (int64_t)0, (const T*)(dvec + d0 + c0), 0, (const int*)nullptr, 0,
+                           (const T*)nullptr, (T*)nullptr, (int64_t)0);
+        fail->check(hipGetLastError());
+        ++launches;
+        fma += (double)below * ((double)lw * (lw - 1) / 2.0);
+      }
+    }
+    if (rc != MDET_OK) return rc;
+    const unsigned grid = (unsigned)std::min<int64_t>(m, 4096);
+    hipLaunchKernelGGL((pb_store_kernel<T>), dim3(grid), dim3(256), 0, st, P, ld, m, (int)w, (const T*)pb.Lfull, ldl,
+                       (const int*)pb.piv, (const T*)(dvec + d0), (const T*)pb.Y, ldl);
+    fail->check(hipGetLastError());
+    ++launches;
+    return MDET_OK;
   }
 
   // After all streams are idle: per kernel the number of timed launches, the sum of their
@@ -732,6 +811,26 @@ __global__ void reset_flags_kernel(DevFlags* f) {
   }
 }
 
+// The workspace of MDET_FLAG_PIVOT_BLOCK, which follows the small area.
+template <typename T>
+static void bind_pivot_block(Launcher<T>& L, char* base, const Plan& pl) {
+  if (!pl.pivot_block) return;
+  const PivotBlockArea a = pivot_block_area(pl.n, pl.bs, pl.beta);
+  L.pb.S = (T*)(base + a.S);
+  L.pb.Lfull = (T*)(base + a.Lfull);
+  L.pb.Y = (T*)(base + a.Y);
+  L.pb.Bg = (T*)(base + a.Bg);
+  L.pb.leaf = (T*)(base + a.leaf);
+  L.pb.linv = (T*)(base + a.linv);
+  L.pb.dg = (T*)(base + a.dg);
+  L.pb.active = (int*)(base + a.active);
+  L.pb.piv = (int*)(base + a.piv);
+  L.pb.part = (PbCand*)(base + a.part);
+  L.pb.ldl = a.ldl;
+  L.pb.max_w = pl.bs;
+  L.pb.max_below = pl.n > pl.bs ? pl.n - pl.bs : 0;
+}
+
 template <typename T>
 static void reset_flags(Launcher<T>& L, hipStream_t st) {
   hipLaunchKernelGGL(reset_flags_kernel, dim3(1), dim3(64), 0, st, L.flags);
@@ -763,6 +862,8 @@ static int logdet_device_t(const mdet_params& p, const Plan& plan, T* dA, int64_
   L.profile = (p.flags & MDET_FLAG_PROFILE) != 0;
   L.spd = (p.flags & MDET_FLAG_ASSUME_SPD) != 0;
   bind_small(L, ws.base, sa);
+  bind_pivot_block(L, ws.base + sa.total, pl);
+  const uint64_t fixed = sa.total + pl.pb_bytes;       // what follows starts here
   double* partial = (double*)(ws.base + sa.partial);
   double* out = (double*)(ws.base + sa.out);
   double* running = (double*)(ws.base + sa.running);
@@ -780,7 +881,7 @@ static int logdet_device_t(const mdet_params& p, const Plan& plan, T* dA, int64_
   if (pl.need_copy && pl.n > 0) {
     constexpr int vec = 16 / (int)sizeof(T);
     ldw = round_up(pl.n, vec);
-    W = (T*)(ws.base + sa.total);
+    W = (T*)(ws.base + fixed);
     if (widen_from) {
       const dim3 grid((unsigned)pl.n), block(256);
       if (p.dtype == MDET_F16)
@@ -804,7 +905,7 @@ static int logdet_device_t(const mdet_params& p, const Plan& plan, T* dA, int64_
   const int nb64 = (int)((pl.n + LEAF - 1) / LEAF);
   if (pl.general && pl.n > 0) {
     // the entries above the diagonal go, transposed, into an array of their own
-    Q = (T*)(ws.base + sa.total + pl.copy_bytes + pl.wcopy_bytes);
+    Q = (T*)(ws.base + fixed + pl.copy_bytes + pl.wcopy_bytes);
     L.qoff = Q - W;
     if (L.qoff == 0 || !L.perm) return MDET_EINVAL;
     hipLaunchKernelGGL((transpose_strict_kernel<T>), dim3((unsigned)((int64_t)nb64 * (nb64 + 1) / 2)),
@@ -812,7 +913,7 @@ static int logdet_device_t(const mdet_params& p, const Plan& plan, T* dA, int64_
     MDET_HIP(fail, hipGetLastError());
   }
   if (pl.wcopy_bytes) {
-    char* wb = ws.base + sa.total + pl.copy_bytes;
+    char* wb = ws.base + fixed + pl.copy_bytes;
     L.wbuf[0] = (T*)wb;
     L.wbuf[1] = (T*)(wb + pl.wcopy_bytes / 2);
     L.wld = pl.bs;
@@ -1286,8 +1387,9 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
   double* partial = (double*)(ws.base + sa.partial);
   double* out = (double*)(ws.base + sa.out);
   double* running = (double*)(ws.base + sa.running);
-  char* const stage = ws.base + sa.total;            // pl.stage_bytes of staging for narrow uploads
-  char* arena = ws.base + sa.total + pl.stage_bytes;
+  bind_pivot_block(L, ws.base + sa.total, pl);
+  char* const stage = ws.base + sa.total + pl.pb_bytes;   // pl.stage_bytes of staging for narrow uploads
+  char* arena = stage + pl.stage_bytes;
   uint64_t arena_used = 0;                           // highest arena offset any group reached
   // A general matrix (Sec. 2.2, Eq. 1: M = P L U) is two lower-triangular arrays, the entries
   // on and below the diagonal and the transposed entries above it: on the host two packed
@@ -1517,14 +1619,11 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
         std::vector<hipEvent_t> slot_ready(ring.size(), nullptr), slot_free(ring.size(), nullptr);
         hipEvent_t b_ready[2] = {nullptr, nullptr}, b_free[2] = {nullptr, nullptr};
         size_t slot_next = 0;
-        for (int64_t k = 0; k < j0 && rc == MDET_OK; ++k) {
+        // operands of column k for the group's own rows: rows [j0*bs, rows_end_J) of column k
+        auto upload_operands = [&](int64_t k) {
           const int q = (int)(k & 1);
           T* hk = host_col(hOut, k);          // factored column k (bs wide, ld = bs)
-          const T* dk = L.dvec + k * bs;
-          // operands for the group's own rows: rows [j0*bs, rows_end_J) of column k
           if (b_free[q]) MDET_HIP(fail, hipStreamWaitEvent(sh, b_free[q], 0));
-          if (k == 0)
-            for (int64_t i = j0; i < j1; ++i) upload_row(i);
           for (int h = 0; h < arrays; ++h) {
             const size_t nbytes = (size_t)(rows_end_J - j0 * bs) * bs * sizeof(T);
             CopyProfile::Scope timed(&cprof, 0, sh);
@@ -1537,55 +1636,80 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
           if (!b_ready[q]) b_ready[q] = events.get();
           MDET_HIP(fail, hipEventRecord(b_ready[q], sh));
           MDET_HIP(fail, hipStreamWaitEvent(s0, b_ready[q], 0));
-          // group rows: each target column j gets rows [j*bs, rows_end_J) in one launch
+        };
+        // the group's own rows: each target column j gets rows [j*bs, rows_end_J) in one launch
+        auto update_group_rows = [&](int64_t k) {
+          const int q = (int)(k & 1);
           for (int64_t j = j0; j < j1 && rc == MDET_OK; ++j) {
             if (k == 0)
               for (int64_t i = j; i < j1; ++i) MDET_HIP(fail, hipStreamWaitEvent(s0, row_ready[i], 0));
             const T* A = bpool[q] + (j - j0) * bs * bs;
-            rc = L.update(s0, cols[j].base, cols[j].ld, A, bs, A, bs, dk, rows_end_J - j * bs,
+            rc = L.update(s0, cols[j].base, cols[j].ld, A, bs, A, bs, L.dvec + k * bs, rows_end_J - j * bs,
                           pl.col_width(j), bs, true, true);
           }
-          // rows below the group: one streamed block per block row
-          for (int64_t i = j1; i < T_ && rc == MDET_OK; ++i) {
-            const size_t sl = slot_next++ % ring.size();
-            const int64_t wi = pl.col_width(i);
-            if (k == 0) upload_row(i);
-            if (slot_free[sl]) MDET_HIP(fail, hipStreamWaitEvent(sh, slot_free[sl], 0));
-            const size_t nbytes = (size_t)wi * bs * sizeof(T);
-            for (int h = 0; h < arrays; ++h) {
-              CopyProfile::Scope timed(&cprof, 0, sh);
-              T* dst = ring[sl] + h * dev_half;
-              const T* src = hk + h * host_half + (i - k) * bs * bs;
-              if (stage_out) stage_out->to_device(dst, nbytes, src, nbytes, 1, sh);
-              else MDET_HIP(fail, hipMemcpyAsync(dst, src, nbytes, hipMemcpyHostToDevice, sh));
-              h2d_bytes += nbytes;
-            }
-            if (!slot_ready[sl]) slot_ready[sl] = events.get();
-            MDET_HIP(fail, hipEventRecord(slot_ready[sl], sh));
-            MDET_HIP(fail, hipStreamWaitEvent(s0, slot_ready[sl], 0));
-            if (k == 0) MDET_HIP(fail, hipStreamWaitEvent(s0, row_ready[i], 0));
-            // The streamed rows are the left operand of one update per column of the
-            // group: scaled by the pivots once, in place (W = L D), they serve all of
-            // them through the kernel that scales nothing.
-            const bool prescaled = !L.spd && wc > 1 && !pl.general;
-            if (prescaled) {
-              const int64_t vecs = wi * (bs / (16 / (int64_t)sizeof(T)));
-              const unsigned grid = (unsigned)std::min<int64_t>((vecs + 255) / 256, 4096);
-              hipLaunchKernelGGL((scale_columns_kernel<T>), dim3(grid), dim3(256), 0, s0, ring[sl], bs, wi,
-                                 (int)bs, dk);
-              MDET_HIP(fail, hipGetLastError());
-              ++L.launches;
-            }
-            for (int64_t j = j0; j < j1 && rc == MDET_OK; ++j) {
-              T* C = cols[j].base + (i - j) * bs * cols[j].ld;
-              rc = L.update(s0, C, cols[j].ld, ring[sl], bs, bpool[q] + (j - j0) * bs * bs, bs, dk, wi,
-                            pl.col_width(j), bs, false, true, nullptr, -1, prescaled);
-            }
-            if (!slot_free[sl]) slot_free[sl] = events.get();
-            MDET_HIP(fail, hipEventRecord(slot_free[sl], s0));
+        };
+        // block row i below the group: the streamed block (i, k), used by every column of the group
+        auto stream_block = [&](int64_t k, int64_t i) {
+          const int q = (int)(k & 1);
+          T* hk = host_col(hOut, k);
+          const T* dk = L.dvec + k * bs;
+          const size_t sl = slot_next++ % ring.size();
+          const int64_t wi = pl.col_width(i);
+          if (slot_free[sl]) MDET_HIP(fail, hipStreamWaitEvent(sh, slot_free[sl], 0));
+          const size_t nbytes = (size_t)wi * bs * sizeof(T);
+          for (int h = 0; h < arrays; ++h) {
+            CopyProfile::Scope timed(&cprof, 0, sh);
+            T* dst = ring[sl] + h * dev_half;
+            const T* src = hk + h * host_half + (i - k) * bs * bs;
+            if (stage_out) stage_out->to_device(dst, nbytes, src, nbytes, 1, sh);
+            else MDET_HIP(fail, hipMemcpyAsync(dst, src, nbytes, hipMemcpyHostToDevice, sh));
+            h2d_bytes += nbytes;
           }
-          if (!b_free[q]) b_free[q] = events.get();
-          MDET_HIP(fail, hipEventRecord(b_free[q], s0));
+          if (!slot_ready[sl]) slot_ready[sl] = events.get();
+          MDET_HIP(fail, hipEventRecord(slot_ready[sl], sh));
+          MDET_HIP(fail, hipStreamWaitEvent(s0, slot_ready[sl], 0));
+          if (k == 0) MDET_HIP(fail, hipStreamWaitEvent(s0, row_ready[i], 0));
+          // The streamed rows are the left operand of one update per column of the
+          // group: scaled by the pivots once, in place (W = L D), they serve all of
+          // them through the kernel that scales nothing.
+          const bool prescaled = !L.spd && wc > 1 && !pl.general;
+          if (prescaled) {
+            const int64_t vecs = wi * (bs / (16 / (int64_t)sizeof(T)));
+            const unsigned grid = (unsigned)std::min<int64_t>((vecs + 255) / 256, 4096);
+            hipLaunchKernelGGL((scale_columns_kernel<T>), dim3(grid), dim3(256), 0, s0, ring[sl], bs, wi,
+                               (int)bs, dk);
+            MDET_HIP(fail, hipGetLastError());
+            ++L.launches;
+          }
+          for (int64_t j = j0; j < j1 && rc == MDET_OK; ++j) {
+            T* C = cols[j].base + (i - j) * bs * cols[j].ld;
+            rc = L.update(s0, C, cols[j].ld, ring[sl], bs, bpool[q] + (j - j0) * bs * bs, bs, dk, wi,
+                          pl.col_width(j), bs, false, true, nullptr, -1, prescaled);
+          }
+          if (!slot_free[sl]) slot_free[sl] = events.get();
+          MDET_HIP(fail, hipEventRecord(slot_free[sl], s0));
+        };
+        // Factored columns 0 and 1 pass in one sweep, the rest one sweep each.  The first
+        // sweep also brings in the group's original blocks, wc of them per block row beside
+        // the one streamed block whose wc products pay for the transfer; with two streamed
+        // blocks per row it is the products again, not the link, that set the pace.  Every
+        // entry still receives its updates in the order k = 0, 1, 2, ...
+        for (int64_t k = 0; k < j0 && rc == MDET_OK;) {
+          const int64_t cnt = (k == 0 && j0 >= 2) ? 2 : 1;
+          if (k == 0)
+            for (int64_t i = j0; i < j1; ++i) upload_row(i);
+          for (int64_t t = 0; t < cnt; ++t) upload_operands(k + t);
+          for (int64_t t = 0; t < cnt && rc == MDET_OK; ++t) update_group_rows(k + t);
+          for (int64_t i = j1; i < T_ && rc == MDET_OK; ++i) {
+            if (k == 0) upload_row(i);
+            for (int64_t t = 0; t < cnt && rc == MDET_OK; ++t) stream_block(k + t, i);
+          }
+          for (int64_t t = 0; t < cnt; ++t) {
+            const int q = (int)((k + t) & 1);
+            if (!b_free[q]) b_free[q] = events.get();
+            MDET_HIP(fail, hipEventRecord(b_free[q], s0));
+          }
+          k += cnt;
         }
         if (rc == MDET_OK) {
           ResidentHooks hooks;
@@ -1623,7 +1747,7 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
   res->bytes_d2h = d2h_bytes;
   res->t_h2d = cprof.collect(0);
   res->t_d2h = cprof.collect(1);
-  res->dev_bytes_high_water = sa.total + pl.stage_bytes + (pl.general ? pl.arena_half : 0) + arena_used;
+  res->dev_bytes_high_water = sa.total + pl.pb_bytes + pl.stage_bytes + (pl.general ? pl.arena_half : 0) + arena_used;
   if (prov_rc != MDET_OK) return prov_rc;
   if (stager_in.io_failed() || stager_out.io_failed()) return MDET_EIO;
   if (!fail.ok()) { res->hip_error = fail.code; return MDET_EHIP; }

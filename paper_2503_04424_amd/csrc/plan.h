@@ -32,7 +32,9 @@ struct Plan {
   bool device_input = false;
   bool out_of_core = false;
   bool need_copy = false;          // device input: work on a copy (overwrite = 0)
-  bool pivot = false;              // MDET_FLAG_PIVOT
+  bool pivot = false;              // MDET_FLAG_PIVOT or MDET_FLAG_PIVOT_BLOCK: a permutation is kept
+  bool pivot_block = false;        // MDET_FLAG_PIVOT_BLOCK: candidates = the whole diagonal block
+  uint64_t pb_bytes = 0;           // its workspace (pivot_block_area), right behind the small area
   bool general = false;            // MDET_FLAG_GENERAL: P A = L D U, two triangular arrays
   uint64_t q_bytes = 0;            // the second of them (device input)
   uint64_t arena_half = 0;         // host input: bytes of block columns and streamed blocks of ONE array
@@ -99,6 +101,32 @@ inline SmallArea small_area(int64_t n, int64_t T, int beta, bool pivot) {
   return a;
 }
 
+// Workspace of MDET_FLAG_PIVOT_BLOCK (offsets in bytes from its start): the diagonal block as
+// a full symmetric matrix, the block's multipliers with rows in input order and columns in
+// pivot order, the rows below the block with their columns in pivot order, and small arrays.
+struct PivotBlockArea {
+  uint64_t S, Lfull, Y, Bg, leaf, linv, dg, active, piv, part, total;
+  int64_t ldl;                 // leading dimension of S, Lfull, Y and Bg: bs rounded up to 64
+};
+inline PivotBlockArea pivot_block_area(int64_t n, int64_t bs, int beta) {
+  PivotBlockArea a;
+  a.ldl = round_up(bs > 0 ? bs : 64, 64);
+  const uint64_t rows_below = (uint64_t)(n > bs ? n - bs : 0);
+  uint64_t o = 0;
+  a.S = o; o += align256((uint64_t)bs * a.ldl * beta);
+  a.Lfull = o; o += align256((uint64_t)bs * a.ldl * beta);
+  a.Y = o; o += align256((rows_below + 64) * a.ldl * beta);
+  a.Bg = o; o += align256((uint64_t)64 * a.ldl * beta);
+  a.leaf = o; o += align256((uint64_t)64 * 64 * beta);
+  a.linv = o; o += align256((uint64_t)64 * 16 * beta);
+  a.dg = o; o += align256((uint64_t)bs * beta);
+  a.active = o; o += align256((uint64_t)bs * 4);
+  a.piv = o; o += align256((uint64_t)bs * 4);
+  a.part = o; o += align256((uint64_t)2 * 64 * 16);
+  a.total = o;
+  return a;
+}
+
 // Returns an mdet_status.
 inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& pl) {
   if (p.n < 0 || p.block_size < 0) return MDET_EINVAL;
@@ -115,7 +143,9 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
   pl.T = p.n > 0 ? (p.n + pl.bs - 1) / pl.bs : 0;
   pl.device_input = device_input;
   pl.tile_bytes = (uint64_t)pl.bs * pl.bs * pl.beta;
-  pl.pivot = (p.flags & MDET_FLAG_PIVOT) != 0;
+  pl.pivot_block = (p.flags & MDET_FLAG_PIVOT_BLOCK) != 0;
+  if (pl.pivot_block && (p.flags & (MDET_FLAG_PIVOT | MDET_FLAG_GENERAL))) return MDET_EINVAL;
+  pl.pivot = (p.flags & (MDET_FLAG_PIVOT | MDET_FLAG_PIVOT_BLOCK)) != 0;
   // general matrix: in the arithmetic of its own type; the row order inside each leaf is
   // always recorded.  From host memory both triangles travel: twice the arrays, twice the traffic
   pl.general = (p.flags & MDET_FLAG_GENERAL) != 0;
@@ -124,7 +154,9 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
   if (pl.general) pl.pivot = true;
   if (pl.pivot && (p.flags & MDET_FLAG_ASSUME_SPD)) return MDET_EINVAL;   // nothing to choose from
   if (pl.pivot && p.n > INT32_MAX) return MDET_EINVAL;
-  pl.small_bytes = small_area(pl.n, pl.T, pl.beta, pl.pivot).total;
+  pl.pb_bytes = pl.pivot_block ? pivot_block_area(pl.n, pl.bs, pl.beta).total : 0;
+  // counted with the fixed part of the workspace, which it follows
+  pl.small_bytes = small_area(pl.n, pl.T, pl.beta, pl.pivot).total + pl.pb_bytes;
   pl.layout_bytes = pl.T > 0 ? (uint64_t)pl.col_offset(pl.T) * pl.beta : 0;
   pl.panels.clear();
   pl.h2d = pl.d2h = 0;
@@ -138,7 +170,7 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
   // one is given up again if the workspace cannot be had (wcopy_optional)
   const bool wcopy_auto = !(p.flags & MDET_FLAG_SCALED_COPY) && budget == 0 && p.n >= 24576;
   const uint64_t wcopy = (((p.flags & MDET_FLAG_SCALED_COPY) || wcopy_auto) &&
-                          !(p.flags & MDET_FLAG_ASSUME_SPD) && !pl.general && pl.T >= 2)
+                          !(p.flags & MDET_FLAG_ASSUME_SPD) && !pl.general && !pl.pivot_block && pl.T >= 2)
                              ? 2 * align256((uint64_t)pl.n * pl.bs * pl.beta) : 0;
   pl.wcopy_optional = wcopy_auto && wcopy != 0;
   pl.arena_half = 0;
