@@ -213,10 +213,11 @@ def kernel_report(reps=5):
         dvec = torch.rand(n, dtype=torch.float64, device="cuda") + 0.5
         res = torch.zeros(8, dtype=torch.float64, device="cuda")
         ms = timed(lambda: M.mdet_step_logdet_reduce(dvec, res))
-        gb = n * 8 / 1e9
         out.append({"kernel": "logdet_partial_kernel + logdet_combine_kernel", "dtype": "f64",
-                    "shape": f"n={n}", "ms": ms, "bound": "hbm", "peak": HBM, "unit": "GB/s",
-                    "achieved": gb / (ms * 1e-3), "frac": gb / (ms * 1e-3) / HBM})
+                    "shape": f"n={n} as ONE block column", "ms": ms, "bytes": n * 8,
+                    "note": "latency-bound, not a bandwidth kernel: one workgroup reduces one block column's pivots "
+                            "(n logs by 256 threads) and one thread adds the columns' terms in order; in the path a "
+                            "block column has 1024 ... 8192 pivots and the two launches take under 10 us together"})
     # principal-minor sequence and the FLODANCE regression (Sec. 3.2, Alg. 2) at the size of the
     # paper's experiments: 50 000 data points with d = 10 outputs, q = 10 correction terms
     n_s, dd, n0, q = 50000, 10, 100, 10
@@ -402,6 +403,8 @@ def main():
                          "factored as a general matrix (P A = L D U; counts 2n^3/3)")
     ap.add_argument("--pivot", action="store_true",
                     help="MDET_FLAG_PIVOT: pivoting on the diagonal inside each group of 64 columns")
+    ap.add_argument("--pivot-block", action="store_true",
+                    help="MDET_FLAG_PIVOT_BLOCK: pivoting on the diagonal over each whole diagonal block")
     ap.add_argument("--kernels", action="store_true",
                     help="instead of the path: stand-alone rates of its kernels (one JSON line)")
     ap.add_argument("--mfma-peak", action="store_true",
@@ -478,8 +481,10 @@ def main():
         xflags |= M.FLAG_SCALED_COPY
     if args.pivot:
         xflags |= M.FLAG_PIVOT
+    if args.pivot_block:
+        xflags |= M.FLAG_PIVOT_BLOCK
     if args.general:
-        if out_of_core or widen or args.assume_spd or args.pivot or args.scaled_copy:
+        if out_of_core or widen or args.assume_spd or args.pivot or args.pivot_block or args.scaled_copy:
             print("bench.py: --general goes with an in-core configuration and no other form", file=sys.stderr)
             sys.exit(2)
         xflags |= M.FLAG_GENERAL
@@ -672,6 +677,7 @@ def main():
                    **({"form": "positive definite (Cholesky), MDET_FLAG_ASSUME_SPD"} if args.assume_spd else {}),
                    **({"workspace": "MDET_FLAG_SCALED_COPY"} if args.scaled_copy else {}),
                    **({"pivoting": "inside groups of 64, MDET_FLAG_PIVOT"} if args.pivot else {}),
+                   **({"pivoting": "over each whole diagonal block, MDET_FLAG_PIVOT_BLOCK"} if args.pivot_block else {}),
                    **({"form": "general matrix (rows shuffled inside groups of 64), P A = L D U, "
                                "MDET_FLAG_GENERAL; value counts 2n^3/3"} if args.general else {})},
         "time_to_logdet_s": sec, "frac_of_matrix_peak": value / peak,

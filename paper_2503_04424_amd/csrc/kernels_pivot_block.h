@@ -65,12 +65,36 @@ __device__ __forceinline__ PbCand pb_block_best(PbCand mine, PbCand* s) {
   return r;
 }
 
-// S <- the w x w diagonal block as a full symmetric matrix (only its lower triangle is
-// read from P), the running diagonal, all rows candidates, columns w .. ldl of Lfull zero,
-// and the first step's partial maxima.
+// S <- the w x w diagonal block as a full symmetric matrix (only its lower triangle is read
+// from P): 32 x 32 tiles on and below the diagonal, each written straight and transposed
+// through LDS so that both the reads and the writes run along rows.  Grid: (tiles per side)^2.
+template <typename T>
+__global__ __launch_bounds__(256) void pb_symmetrize_kernel(const T* __restrict__ P, int64_t ld, int w,
+                                                            T* __restrict__ S, int64_t lds) {
+  __shared__ T t[32][33];
+  const int nt = (w + 31) / 32;
+  const int bi = blockIdx.x / nt, bj = blockIdx.x % nt;
+  if (bj > bi) return;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;         // 32 x 8
+  for (int r = ty; r < 32; r += 8) {
+    const int gr = bi * 32 + r, gc = bj * 32 + tx;
+    T v = T(0);
+    if (gr < w && gc < w) v = gc <= gr ? P[(int64_t)gr * ld + gc] : P[(int64_t)gc * ld + gr];
+    t[r][tx] = v;
+    if (gr < w && gc < w) S[(int64_t)gr * lds + gc] = v;
+  }
+  __syncthreads();
+  if (bi != bj)
+    for (int r = ty; r < 32; r += 8) {
+      const int gr = bj * 32 + r, gc = bi * 32 + tx;            // the mirrored tile
+      if (gr < w && gc < w) S[(int64_t)gr * lds + gc] = t[tx][r];
+    }
+}
+
+// The running diagonal, all rows candidates, columns w .. ldl of Lfull zero, and the first
+// step's partial maxima.
 template <typename T>
 __global__ __launch_bounds__(PB_THREADS) void pb_init_kernel(const T* __restrict__ P, int64_t ld, int w,
-                                                             T* __restrict__ S, int64_t lds,
                                                              T* __restrict__ Lfull, int64_t ldl,
                                                              T* __restrict__ dg, int* __restrict__ active,
                                                              PbCand* __restrict__ part) {
@@ -84,10 +108,6 @@ __global__ __launch_bounds__(PB_THREADS) void pb_init_kernel(const T* __restrict
     mine = PbCand{pb_key(d), i};
     for (int64_t c = w; c < ldl; ++c) Lfull[(int64_t)i * ldl + c] = T(0);
   }
-  // row i of S: coalesced along the row for j <= i, strided for j > i (done once per block column)
-  for (int r = blockIdx.x * PB_THREADS; r < w && r < (blockIdx.x + 1) * PB_THREADS; ++r)
-    for (int j = threadIdx.x; j < w; j += PB_THREADS)
-      S[(int64_t)r * lds + j] = j <= r ? P[(int64_t)r * ld + j] : P[(int64_t)j * ld + r];
   const PbCand best = pb_block_best(mine, red);
   if (threadIdx.x == 0) part[blockIdx.x] = best;
 }

@@ -470,10 +470,13 @@ struct Launcher {
     const int nparts = (int)((w + PB_THREADS - 1) / PB_THREADS);
     if (nparts > 64) return MDET_EINVAL;
     PbCand* part[2] = {pb.part, pb.part + 64};
+    const int64_t nt = (w + 31) / 32;
+    hipLaunchKernelGGL((pb_symmetrize_kernel<T>), dim3((unsigned)(nt * nt)), dim3(256), 0, st, (const T*)P, ld, (int)w,
+                       pb.S, ldl);
     hipLaunchKernelGGL((pb_init_kernel<T>), dim3((unsigned)nparts), dim3(PB_THREADS), 0, st, (const T*)P, ld, (int)w,
-                       pb.S, ldl, pb.Lfull, ldl, pb.dg, pb.active, part[0]);
+                       pb.Lfull, ldl, pb.dg, pb.active, part[0]);
     fail->check(hipGetLastError());
-    ++launches;
+    launches += 2;
     int cur = 0;
     int rc = MDET_OK;
     for (int64_t c0 = 0; c0 < w && rc == MDET_OK; c0 += LEAF) {

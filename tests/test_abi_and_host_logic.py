@@ -179,6 +179,26 @@ def test_plan_for_a_general_matrix(M):
     assert not whole.out_of_core and whole.dev_bytes_needed >= 2 * whole.host_matrix_bytes
 
 
+def test_plan_for_pivoting_over_the_whole_diagonal_block(M):
+    # MDET_FLAG_PIVOT_BLOCK: the permutation plus two b x b arrays and one (n - b) x b array
+    n, b = 4096, 512
+    plain = M.mdet_plan(n, "f64", b, overwrite=True, for_device_input=True).dev_bytes_needed
+    blk = M.mdet_plan(n, "f64", b, overwrite=True, flags=M.FLAG_PIVOT_BLOCK, for_device_input=True).dev_bytes_needed
+    assert blk >= plain + n * 4 + (2 * b * b + (n - b) * b) * 8
+    assert blk <= plain + n * 4 + (2 * b * b + (n - b + 64) * b + 64 * b + 64 * 64 + 64 * 16 + 2 * b) * 8 + 65536
+    # no scaled copy is taken in this form, asked for or not
+    big = M.mdet_plan(32768, "f64", 2048, overwrite=True, flags=M.FLAG_PIVOT_BLOCK, for_device_input=True)
+    assert big.dev_bytes_needed < 2 * 32768 * 2048 * 8
+    # host entry points: counted against the budget like the rest of the fixed workspace
+    h = M.mdet_plan(n, "f64", b, 64 << 20, flags=M.FLAG_PIVOT_BLOCK)
+    assert h.out_of_core and h.dev_bytes_needed <= 64 << 20
+    assert h.num_superpanels >= M.mdet_plan(n, "f64", b, 64 << 20).num_superpanels
+    for extra in (M.FLAG_PIVOT, M.FLAG_GENERAL):
+        with pytest.raises(M.MemdetError) as e:
+            M.mdet_plan(n, "f64", b, flags=M.FLAG_PIVOT_BLOCK | extra, for_device_input=True)
+        assert e.value.status == M.Status.EINVAL
+
+
 def test_plan_fp32_storage_with_fp64_arithmetic(M):
     n = 3000
     plain = M.mdet_plan(n, "f32", 256, overwrite=True, for_device_input=True)

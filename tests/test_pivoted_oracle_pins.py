@@ -43,7 +43,7 @@ def test_hand_computed_three_by_three_with_a_tie():
 
 
 @pytest.mark.parametrize("n,group", [(1, 64), (2, 64), (5, 2), (7, 4), (64, 64), (65, 64), (150, 64),
-                                     (150, 16), (200, 1)])
+                                     (150, 16), (200, 1), (300, 128), (300, 256), (260, 320), (200, 200)])
 def test_reconstruction_and_determinant(n, group):
     a = _sym(np.random.default_rng(100 * n + group), n)
     r = oracle.ldlt_pivoted(a, group=group, want_L=True)
