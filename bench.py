@@ -567,7 +567,15 @@ def main():
         # overwrite = 0: the factored block columns go to a scratch area in host memory (the paper's
         # scratchpad, Sec. 2.2) and the matrix stays as it is, so no pass needs it formed again;
         # workspace and scratch are the caller's, sized by the library's own query
-        ws_bytes, hs_bytes = M.mdet_workspace_query(n, h.dtype, bs, w.mem_budget, overwrite=False, flags=run_flags)
+        # (a matrix too large for a second copy in host memory is factored in place and formed again,
+        # untimed, before every pass)
+        avail = 0
+        for ln in open("/proc/meminfo"):
+            if ln.startswith("MemAvailable:"):
+                avail = int(ln.split()[1]) * 1024
+        keep_input = h.numel() * h.element_size() < 0.45 * avail or widen
+        ws_bytes, hs_bytes = M.mdet_workspace_query(n, h.dtype, bs, w.mem_budget, overwrite=not keep_input,
+                                                    flags=run_flags)
         ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
         hs = None
         mpath = spath = None
@@ -579,14 +587,19 @@ def main():
         elif hs_bytes:
             hs = torch.empty(hs_bytes, dtype=torch.uint8, pin_memory=pinned and hs_bytes <= PINNED_CAP // 2)
 
+        passes_done = [0]
+
         def run_streamed():
+            if not keep_input and passes_done[0]:
+                form_matrix_host_packed(w, torch, M, out=h)
+            passes_done[0] += 1
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             if args.file_dir:
                 r = M.mdet_logdet_file(mpath, n, w.dtype, bs, mem_budget=w.mem_budget, overwrite=False,
                                        scratch_path=spath, flags=run_flags, diag=diag, workspace=ws)
             else:
-                r = M.mdet_logdet_host(h, n, bs, mem_budget=w.mem_budget, overwrite=False,
+                r = M.mdet_logdet_host(h, n, bs, mem_budget=w.mem_budget, overwrite=not keep_input,
                                        flags=run_flags, diag=diag, workspace=ws, host_scratch=hs)
             torch.cuda.synchronize()
             return r, time.perf_counter() - t0
@@ -669,8 +682,9 @@ def main():
         "vs_baseline": None, "dtype": "f64" if widen else w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "n": n, "block_size": bs,
                    "placement": ("file (pread/pwrite through pinned chunks), streamed" if args.file_dir else
-                                 ("pinned" if pinned else "pageable") + " host memory, streamed; factors to a "
-                                 "host scratch area (overwrite = 0)")
+                                 ("pinned" if pinned else "pageable") + " host memory, streamed; factors " +
+                                 ("to a host scratch area (overwrite = 0)" if keep_input else
+                                  "over the matrix (overwrite = 1; formed again, untimed, before every pass)"))
                    if out_of_core else "HBM, in-core",
                    "mem_budget_bytes": w.mem_budget, "seed": w.seed,
                    **({"storage": "f32, widened exactly; arithmetic f64"} if widen else {}),
@@ -720,7 +734,7 @@ def main():
 
     if not args.no_cpu_baseline:
         import oracle
-        m = args.cpu_sample or min(n, 8192 if out_of_core else 6144)
+        m = args.cpu_sample or min(n, 8192)      # configurations 1 and 2: the whole matrix
         if args.general:
             m = max(64, m // 64 * 64) if n >= 64 else n
         if a is None:
