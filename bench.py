@@ -147,6 +147,14 @@ def kernel_report(reps=5):
             out.append({"kernel": "trailing_update_kernel, positive-definite form (no diagonal scaling)",
                         "dtype": name, "shape": f"M=N={Mr} K={K} lower", "ms": ms, "achieved": tf,
                         "unit": "TFLOP/s", "bound": "mfma", "peak": PEAK[name], "frac": tf / PEAK[name]})
+            if K == 4096:
+                # all 128 x 128 blocks of a square C: 16384 blocks = 32 full rounds of the device's 512
+                # workgroup slots (the lower-triangular launch above has 8256 = 16.1, a nearly empty last one)
+                ms = timed(lambda: M.mdet_step_schur_update(c, a, a, None, lower=False))
+                tf = 2.0 * K * Mr * Mr / ms / 1e9
+                out.append({"kernel": "trailing_update_kernel, positive-definite form (no diagonal scaling)",
+                            "dtype": name, "shape": f"M=N={Mr} K={K} full", "ms": ms, "achieved": tf,
+                            "unit": "TFLOP/s", "bound": "mfma", "peak": PEAK[name], "frac": tf / PEAK[name]})
             del a, c, d
     # one 64-column leaf: factorisation of the 64 x 64 diagonal block + solve of the rows below
     for m in (32768, 131072):
