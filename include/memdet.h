@@ -192,9 +192,8 @@ typedef struct mdet_params {
                                      M = P L U for generic matrices, with pivoting inside a
                                      block and none between blocks), fp32 or fp64 in their
                                      own arithmetic; MDET_FLAG_ASSUME_SPD, MDET_FLAG_PIVOT and
-                                     MDET_FLAG_COMPUTE_F64 with it, and mdet_logdet_provider,
-                                     give MDET_EINVAL.  All n x n entries of the input are
-                                     read.  Gaussian elimination in the order of the symmetric
+                                     MDET_FLAG_COMPUTE_F64 with it give MDET_EINVAL.  All
+                                     n x n entries of the input are read.  Gaussian elimination in the order of the symmetric
                                      path (block columns, leaves of 64); in column j the pivot
                                      is the entry of largest magnitude among the rows j .. end
                                      of j's group of 64 consecutive rows (the first on ties),
@@ -227,6 +226,9 @@ typedef struct mdet_params {
                                      (device bytes, traffic, host scratch) is twice the
                                      symmetric one; with overwrite = 1 a streamed run leaves
                                      L and D in the first layout and U^T (unit) in the second.
+                                     mdet_logdet_provider: the callback is asked for the
+                                     blocks of both triangles (see mdet_block_provider), plus
+                                     a staging buffer of at most 64 MiB on the device.
                                      A column whose candidates are all zero ends the call with
                                      MDET_ESINGULAR.                                     */
 
@@ -278,6 +280,10 @@ typedef struct mdet_result {
  * return value aborts the call with MDET_EPROVIDER.  For diagonal blocks only the
  * lower triangle need be filled.  Every block is asked for exactly once, block columns in
  * ascending order within a resident group, elements of params->dtype.
+ * With MDET_FLAG_GENERAL (Sec. 2.2, Eq. 1: generic matrices) the blocks of both triangles
+ * are asked for, bi < bj included and diagonal blocks in full, each still exactly once:
+ * block (bj, bi) right after block (bi, bj); the library transposes the upper ones on the
+ * device.
  */
 typedef int (*mdet_block_provider)(void* user, int64_t bi, int64_t bj, int64_t rows,
                                    int64_t cols, void* dst, int64_t ld);

@@ -105,6 +105,23 @@ __global__ __launch_bounds__(256) void widen_rows_kernel(const S* __restrict__ s
   }
 }
 
+// dst[c][r] = src[r][c] for a rows x cols rectangle on its way from host memory (a block of
+// the upper triangle of a general matrix into the transposed store).  32 x 32 tiles through
+// LDS, reads and writes along rows.  Grid: (ceil(cols / 32), ceil(rows / 32)).
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_rows_kernel(const T* __restrict__ src, int64_t lds,
+                                                             T* __restrict__ dst, int64_t ldd,
+                                                             int64_t rows, int64_t cols) {
+  __shared__ T t[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;         // 32 x 8
+  const int64_t r0 = (int64_t)blockIdx.y * 32, c0 = (int64_t)blockIdx.x * 32;
+  for (int r = ty; r < 32; r += 8)
+    if (r0 + r < rows && c0 + tx < cols) t[r][tx] = src[(r0 + r) * lds + c0 + tx];
+  __syncthreads();
+  for (int c = ty; c < 32; c += 8)
+    if (c0 + c < cols && r0 + tx < rows) dst[(c0 + c) * ldd + r0 + tx] = t[tx][c];
+}
+
 // X[r][c] *= d[c] in place, rows x cols with leading dimension ld (cols and ld multiples
 // of the 16-byte vector): rows of L of a finished block column become rows of W = L D,
 // each product rounded once, as the update kernels round it when they scale on the fly.

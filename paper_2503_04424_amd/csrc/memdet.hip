@@ -1461,6 +1461,14 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
       ++L.launches;
     }
   };
+  // rows x cols elements at `src` (leading dimension lds, device memory) transposed into dst
+  // (a general matrix is stored in the arithmetic's type)
+  auto transpose_piece = [&](const void* src, int64_t lds, T* dst, int64_t ldd, int64_t rows, int64_t cols) {
+    const dim3 grid((unsigned)((cols + 31) / 32), (unsigned)((rows + 31) / 32));
+    hipLaunchKernelGGL((transpose_rows_kernel<T>), grid, dim3(256), 0, sh, (const T*)src, lds, dst, ldd, rows, cols);
+    MDET_HIP(fail, hipGetLastError());
+    ++L.launches;
+  };
   // Rows [r0, r1) of the ORIGINAL block column j into its device image, on the upload stream.
   auto upload_orig = [&](int64_t j, int64_t r0, int64_t r1) {
     if (r1 <= r0) return;
@@ -1470,30 +1478,55 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
       // block by block through the caller's function, each into a pinned buffer and on from there
       for (int64_t i = r0 / bs; i * bs < r1 && prov_rc == MDET_OK; ++i) {
         const int64_t b0 = i * bs, b1 = std::min<int64_t>(n, b0 + bs);
-        const int q = prov_next;
+        int q = prov_next;
         prov_next ^= 1;
         MDET_HIP(fail, hipEventSynchronize(prov_ev[q]));     // its last transfer has left the buffer
         if (source->provider(source->user, i, j, b1 - b0, w, prov_buf[q].p, w) != 0) { prov_rc = MDET_EPROVIDER; break; }
-        CopyProfile::Scope timed(&cprof, 0, sh);
-        T* dst = dcol + (b0 - j * bs) * ldd;
-        const size_t row_bytes = (size_t)w * pl.src_beta;
-        if (pl.widen) {
-          // pieces of at most the staging buffer, widened from there (one stream: in order)
-          const int64_t per = std::max<int64_t>(1, (int64_t)(pl.stage_bytes / row_bytes));
-          for (int64_t r = b0; r < b1; r += per) {
-            const int64_t rn = std::min<int64_t>(per, b1 - r);
-            MDET_HIP(fail, hipMemcpyAsync(stage, (const char*)prov_buf[q].p + (size_t)(r - b0) * row_bytes,
-                                          (size_t)rn * row_bytes, hipMemcpyHostToDevice, sh));
-            widen_piece(stage, w, dcol + (r - j * bs) * ldd, ldd, rn, w);
+        {
+          CopyProfile::Scope timed(&cprof, 0, sh);
+          T* dst = dcol + (b0 - j * bs) * ldd;
+          const size_t row_bytes = (size_t)w * pl.src_beta;
+          if (pl.widen) {
+            // pieces of at most the staging buffer, widened from there (one stream: in order)
+            const int64_t per = std::max<int64_t>(1, (int64_t)(pl.stage_bytes / row_bytes));
+            for (int64_t r = b0; r < b1; r += per) {
+              const int64_t rn = std::min<int64_t>(per, b1 - r);
+              MDET_HIP(fail, hipMemcpyAsync(stage, (const char*)prov_buf[q].p + (size_t)(r - b0) * row_bytes,
+                                            (size_t)rn * row_bytes, hipMemcpyHostToDevice, sh));
+              widen_piece(stage, w, dcol + (r - j * bs) * ldd, ldd, rn, w);
+            }
+          } else if (ldd == w) {
+            MDET_HIP(fail, hipMemcpyAsync(dst, prov_buf[q].p, (size_t)(b1 - b0) * row_bytes, hipMemcpyHostToDevice, sh));
+          } else {
+            MDET_HIP(fail, hipMemcpy2DAsync(dst, ldd * sizeof(T), prov_buf[q].p, row_bytes, row_bytes,
+                                            (size_t)(b1 - b0), hipMemcpyHostToDevice, sh));
           }
-        } else if (ldd == w) {
-          MDET_HIP(fail, hipMemcpyAsync(dst, prov_buf[q].p, (size_t)(b1 - b0) * row_bytes, hipMemcpyHostToDevice, sh));
-        } else {
-          MDET_HIP(fail, hipMemcpy2DAsync(dst, ldd * sizeof(T), prov_buf[q].p, row_bytes, row_bytes,
-                                          (size_t)(b1 - b0), hipMemcpyHostToDevice, sh));
+          h2d_bytes += (uint64_t)(b1 - b0) * row_bytes;
+        }
+        if (arrays == 2) {
+          // The same place of the transposed store holds block (j, i) of the matrix, transposed:
+          // w x (b1 - b0) as the caller hands it over.  The diagonal block has just arrived.
+          const int64_t srows = w, scols = b1 - b0;
+          if (i != j) {
+            MDET_HIP(fail, hipEventRecord(prov_ev[q], sh));
+            q = prov_next;
+            prov_next ^= 1;
+            MDET_HIP(fail, hipEventSynchronize(prov_ev[q]));
+            if (source->provider(source->user, j, i, srows, scols, prov_buf[q].p, scols) != 0) { prov_rc = MDET_EPROVIDER; break; }
+          }
+          CopyProfile::Scope timed(&cprof, 0, sh);
+          const size_t row_bytes = (size_t)scols * pl.src_beta;
+          const int64_t per = std::max<int64_t>(1, (int64_t)(pl.stage_bytes / row_bytes));
+          T* dst = dcol + dev_half + (b0 - j * bs) * ldd;       // its row c, column r: entry (r, c) of the block
+          for (int64_t r = 0; r < srows; r += per) {
+            const int64_t rn = std::min<int64_t>(per, srows - r);
+            MDET_HIP(fail, hipMemcpyAsync(stage, (const char*)prov_buf[q].p + (size_t)r * row_bytes,
+                                          (size_t)rn * row_bytes, hipMemcpyHostToDevice, sh));
+            transpose_piece(stage, scols, dst + r, ldd, rn, scols);
+          }
+          h2d_bytes += (uint64_t)srows * row_bytes;
         }
         MDET_HIP(fail, hipEventRecord(prov_ev[q], sh));
-        h2d_bytes += (uint64_t)(b1 - b0) * row_bytes;
       }
       return;
     }
@@ -1773,7 +1806,6 @@ static int logdet_host_any(const mdet_params* p, void* hA, mdet_result* res, voi
   if (rc != MDET_OK) return rc;
   PinnedBuf scratch;
   std::unique_ptr<char[]> plain_scratch;
-  if (pl.general && provider) return MDET_EINVAL;           // the callback's blocks are those of one triangle
   const bool own_store = pl.widen || provider != nullptr;   // the factors cannot go where the matrix is
   void* hOut = own_store ? nullptr : hA;
   const uint64_t store_bytes = (pl.general ? 2 : 1) * pl.layout_bytes;

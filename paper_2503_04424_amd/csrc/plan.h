@@ -204,9 +204,10 @@ inline int make_plan(const mdet_params& p, bool device_input, int64_t ld, Plan& 
   for (int64_t j = 0; j < pl.T; ++j) dev_layout += align256(pl.dev_col_bytes(j));
   // narrow storage: the originals arrive in the stored width in a staging buffer of at most
   // 64 MiB (one block row of a block column at a time, cut further if need be) and are
-  // widened from there into their block column
+  // widened from there into their block column.  A general matrix has the buffer too: blocks
+  // of its upper triangle that a block provider hands over are transposed from there.
   pl.stage_bytes = 0;
-  if (widen && pl.T > 0) {
+  if ((widen || pl.general) && pl.T > 0) {
     const uint64_t piece = (uint64_t)pl.bs * pl.bs * pl.src_beta;
     const uint64_t one_row = (uint64_t)pl.bs * pl.src_beta;
     uint64_t st = piece < (64ull << 20) ? piece : (64ull << 20);

@@ -308,9 +308,6 @@ def test_bad_arguments_and_workspace(M):
         M.mdet_logdet_device(dev(np.eye(128, dtype=np.float32)), block_size=64,
                              flags=M.FLAG_GENERAL | M.FLAG_COMPUTE_F64)
     assert e.value.status == M.Status.EINVAL
-    with pytest.raises(M.MemdetError) as e:          # the callback supplies one triangle's blocks only
-        M.mdet_logdet_provider(lambda *args: 0, 128, "f64", 64, flags=M.FLAG_GENERAL)
-    assert e.value.status == M.Status.EINVAL
     # the workspace grows by the transposed upper triangle and the permutation
     plain, _ = M.mdet_workspace_query(4096, "f64", 512, for_device_input=True)
     gen, _ = M.mdet_workspace_query(4096, "f64", 512, flags=M.FLAG_GENERAL, for_device_input=True)
@@ -453,6 +450,52 @@ def test_general_matrix_from_host_memory_in_core_and_streamed(M, kind, n, bs, dt
     first_diag = hw[:bs * bs].view(bs, bs).diagonal() if n >= bs else None
     if first_diag is not None:
         assert np.array_equal(first_diag.numpy(), d.numpy()[:bs])          # D on the diagonal of the first layout
+
+
+@pytest.mark.parametrize("n,bs,store", [(1100, 192, "f64"), (777, 64, "f64"), (1280, 256, "f32"), (130, 64, "f64")])
+def test_general_matrix_through_the_block_provider(M, n, bs, store):
+    # every block of the matrix, of both triangles, is asked for once; the result is that of the same
+    # matrix handed over in host memory, bit for bit, resident and streamed
+    import ctypes
+    name = store
+    npdt = np.float64 if name == "f64" else np.float32
+    a = shuffled_dominant(n + 3, n, npdt)
+    stored = torch.from_numpy(a)
+    G = M.FLAG_GENERAL
+    h = M.pack_general_block_columns(stored, bs)
+    ddt = stored.dtype
+    d0 = torch.empty(n, dtype=ddt)
+    p0 = torch.full((n,), -1, dtype=torch.int32)
+    ref = M.mdet_logdet_host(h.clone(), n, bs, flags=G, diag=d0, perm=p0)
+    o = oracle.lu_logdet(a)
+    assert ref.sign == o.sign and rel(ref.logabsdet, o.logabsdet) <= TOL[name]
+    esize = stored.element_size()
+    raw = stored.contiguous().view(torch.uint8).numpy().reshape(n, n * esize)
+    calls = []
+
+    def provider(bi, bj, rows, cols, dst, ld):
+        calls.append((bi, bj))
+        buf = (ctypes.c_uint8 * (rows * ld * esize)).from_address(dst)
+        view = np.frombuffer(buf, dtype=np.uint8).reshape(rows, ld * esize)
+        view[:, :cols * esize] = raw[bi * bs:bi * bs + rows, bj * bs * esize:(bj * bs + cols) * esize]
+        return 0
+
+    T = (n + bs - 1) // bs
+    lo = min_budget_general(M, n, name, bs)
+    for budget in (0, lo, int(lo * 1.4)):
+        calls.clear()
+        d1 = torch.empty(n, dtype=ddt)
+        p1 = torch.full((n,), -1, dtype=torch.int32)
+        fl = G | (M.FLAG_FORCE_OUT_OF_CORE if budget else 0)
+        res = M.mdet_logdet_provider(provider, n, name, bs, mem_budget=budget, flags=fl, diag=d1, perm=p1)
+        assert res.status == 0 and res.out_of_core == bool(budget)
+        assert sorted(calls) == [(i, j) for i in range(T) for j in range(T)]          # each block exactly once
+        assert res.logabsdet == ref.logabsdet and res.sign == ref.sign
+        assert torch.equal(d1, d0) and torch.equal(p1, p0)
+        if budget:
+            assert res.dev_bytes_high_water <= budget
+    bad = M.mdet_logdet_provider(lambda bi, bj, *rest: 7 if bj > bi else 0, n, name, bs, flags=G, raise_on_error=False)
+    assert bad.status == M.Status.EPROVIDER
 
 
 def test_general_matrix_in_a_file_and_error_paths(M, tmp_path):
