@@ -1677,11 +1677,22 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
         auto update_group_rows = [&](int64_t k) {
           const int q = (int)(k & 1);
           for (int64_t j = j0; j < j1 && rc == MDET_OK; ++j) {
-            if (k == 0)
-              for (int64_t i = j; i < j1; ++i) MDET_HIP(fail, hipStreamWaitEvent(s0, row_ready[i], 0));
             const T* A = bpool[q] + (j - j0) * bs * bs;
             rc = L.update(s0, cols[j].base, cols[j].ld, A, bs, A, bs, L.dvec + k * bs, rows_end_J - j * bs,
                           pl.col_width(j), bs, true, true);
+          }
+        };
+        // The same products one block row of the group at a time, for the sweep that brings the
+        // originals: block row i can be worked on as soon as it has arrived, instead of the
+        // whole group waiting for all of its rows (the last group consists of nothing else).
+        auto update_own_row = [&](int64_t k, int64_t i) {
+          const int q = (int)(k & 1);
+          MDET_HIP(fail, hipStreamWaitEvent(s0, row_ready[i], 0));
+          const T* A = bpool[q] + (i - j0) * bs * bs;
+          for (int64_t j = j0; j <= i && rc == MDET_OK; ++j) {
+            T* C = cols[j].base + (i - j) * bs * cols[j].ld;
+            rc = L.update(s0, C, cols[j].ld, A, bs, bpool[q] + (j - j0) * bs * bs, bs, L.dvec + k * bs,
+                          pl.col_width(i), pl.col_width(j), bs, i == j, true);
           }
         };
         // block row i below the group: the streamed block (i, k), used by every column of the group
@@ -1732,10 +1743,15 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
         // entry still receives its updates in the order k = 0, 1, 2, ...
         for (int64_t k = 0; k < j0 && rc == MDET_OK;) {
           const int64_t cnt = (k == 0 && j0 >= 2) ? 2 : 1;
-          if (k == 0)
-            for (int64_t i = j0; i < j1; ++i) upload_row(i);
           for (int64_t t = 0; t < cnt; ++t) upload_operands(k + t);
-          for (int64_t t = 0; t < cnt && rc == MDET_OK; ++t) update_group_rows(k + t);
+          if (k == 0) {
+            for (int64_t i = j0; i < j1 && rc == MDET_OK; ++i) {
+              upload_row(i);
+              for (int64_t t = 0; t < cnt && rc == MDET_OK; ++t) update_own_row(k + t, i);
+            }
+          } else {
+            for (int64_t t = 0; t < cnt && rc == MDET_OK; ++t) update_group_rows(k + t);
+          }
           for (int64_t i = j1; i < T_ && rc == MDET_OK; ++i) {
             if (k == 0) upload_row(i);
             for (int64_t t = 0; t < cnt && rc == MDET_OK; ++t) stream_block(k + t, i);
