@@ -389,6 +389,22 @@ int mdet_logdet_host(const mdet_params* params, void* hA, mdet_result* result,
 int mdet_logdet_provider(const mdet_params* params, mdet_block_provider provider,
                          void* user, mdet_result* result, void* diag);
 
+/* The block provider for blocks that are PRODUCED ON THE DEVICE (a kernel matrix or a Gram
+ * matrix formed block by block, App. D: the matrix need never exist in one piece): the callback
+ * is handed `dst`, a DEVICE pointer into the library's workspace where block (bi, bj), bi >= bj,
+ * belongs (rows x cols, row-major, leading dimension ld elements of params->dtype; for diagonal
+ * blocks only the lower triangle need be filled), and `stream`, a hipStream_t: it must queue on
+ * that stream the kernels or copies that fill the block and return 0 without waiting for them;
+ * any other return value ends the call with MDET_EPROVIDER.  Every block is asked for exactly
+ * once, when the schedule first needs it, as for mdet_block_provider.  Nothing of the matrix
+ * crosses the host link; a run that streams still keeps its factored block columns in host
+ * memory (params->host_scratch or the library's own).  MDET_FLAG_COMPUTE_F64 and
+ * MDET_FLAG_GENERAL are not taken (MDET_EINVAL); `diag` is a HOST pointer. */
+typedef int (*mdet_block_provider_device)(void* user, int64_t bi, int64_t bj, int64_t rows,
+                                          int64_t cols, void* dst, int64_t ld, void* stream);
+int mdet_logdet_provider_device(const mdet_params* params, mdet_block_provider_device provider,
+                                void* user, mdet_result* result, void* diag);
+
 /* As mdet_logdet_host, with the matrix in a FILE (the paper's third tier, Sec. 2.2: the
  * matrix lives on disk, blocks are loaded as needed, a scratchpad on disk takes the
  * updated blocks; the software appendix: scratch_dir, parallel_io): `matrix_path` holds

@@ -9,7 +9,7 @@ from .binding import (  # noqa: F401
     MemdetError, LogdetResult, PlanInfo, Status,
     lib, lib_path, load,
     mdet_plan, mdet_workspace_query, mdet_logdet_device, mdet_logdet_host,
-    mdet_logdet_provider, mdet_logdet_file, mdet_host_layout_offset, mdet_paper_block_rule,
+    mdet_logdet_provider, mdet_logdet_provider_device, mdet_logdet_file, mdet_host_layout_offset, mdet_paper_block_rule,
     mdet_paper_fma_count, mdet_step_schur_update, mdet_step_panel_factor, mdet_step_panel_factor_pivoted, mdet_step_panel_factor_general,
     mdet_step_logdet_reduce, mdet_strerror, mdet_version,
     mdet_sequence_workspace_query, mdet_principal_logdets, mdet_flodance_fit, mdet_flodance_eval,

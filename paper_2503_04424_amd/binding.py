@@ -70,10 +70,12 @@ class _PlanInfo(C.Structure):
 
 PROVIDER_CB = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
                           C.c_void_p, C.c_int64)
+PROVIDER_DEVICE_CB = C.CFUNCTYPE(C.c_int, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
+                                 C.c_void_p, C.c_int64, C.c_void_p)
 
 EXPORTS = [
     "mdet_plan", "mdet_workspace_query", "mdet_logdet_device", "mdet_logdet_host",
-    "mdet_logdet_provider", "mdet_logdet_file", "mdet_host_layout_offset", "mdet_paper_block_rule",
+    "mdet_logdet_provider", "mdet_logdet_provider_device", "mdet_logdet_file", "mdet_host_layout_offset", "mdet_paper_block_rule",
     "mdet_paper_fma_count", "mdet_step_schur_update", "mdet_step_panel_factor",
     "mdet_step_panel_factor_pivoted",
     "mdet_step_panel_factor_general",
@@ -105,6 +107,7 @@ def load():
     L.mdet_logdet_device.argtypes = [C.POINTER(_Params), vp, i64, C.POINTER(_Result), vp]
     L.mdet_logdet_host.argtypes = [C.POINTER(_Params), vp, C.POINTER(_Result), vp]
     L.mdet_logdet_provider.argtypes = [C.POINTER(_Params), PROVIDER_CB, vp, C.POINTER(_Result), vp]
+    L.mdet_logdet_provider_device.argtypes = [C.POINTER(_Params), PROVIDER_DEVICE_CB, vp, C.POINTER(_Result), vp]
     L.mdet_logdet_file.argtypes = [C.POINTER(_Params), C.c_char_p, C.c_char_p, C.POINTER(_Result), vp]
     L.mdet_host_layout_offset.argtypes = [i64, i64, i64]
     L.mdet_host_layout_offset.restype = i64
@@ -388,6 +391,26 @@ def mdet_logdet_provider(provider: Callable, n, dtype, block_size, mem_budget=0,
     r = _Result()
     st = load().mdet_logdet_provider(C.byref(p), cb, None, C.byref(r),
                                      C.c_void_p(diag.data_ptr()) if diag is not None else None)
+    if st not in _SOFT and raise_on_error:
+        raise MemdetError(st, r)
+    return _result(st, r)
+
+
+def mdet_logdet_provider_device(provider: Callable, n, dtype, block_size, mem_budget=0, flags=0,
+                                diag=None, stream=None, raise_on_error=True, perm=None) -> LogdetResult:
+    """``provider(bi, bj, rows, cols, dst_device_ptr, ld, stream_handle) -> int`` queues on the stream
+    it is handed the work that fills one block in device memory."""
+    def _cb(user, bi, bj, rows, cols, dst, ld, st):
+        try:
+            return int(provider(bi, bj, rows, cols, dst, ld, st) or 0)
+        except Exception:  # never let an exception cross the C boundary
+            return -1
+    cb = PROVIDER_DEVICE_CB(_cb)
+    p = _params(n, dtype, block_size, mem_budget, True, flags, _stream_handle(stream),
+                perm=_perm_ptr(perm, n, False))
+    r = _Result()
+    st = load().mdet_logdet_provider_device(C.byref(p), cb, None, C.byref(r),
+                                            C.c_void_p(diag.data_ptr()) if diag is not None else None)
     if st not in _SOFT and raise_on_error:
         raise MemdetError(st, r)
     return _result(st, r)

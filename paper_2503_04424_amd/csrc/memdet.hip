@@ -1360,6 +1360,8 @@ struct HostSource {
   int32_t dtype = MDET_F64;
   // blocks fetched through the caller's function instead (mdet_logdet_provider)
   mdet_block_provider provider = nullptr;
+  // or produced in device memory by the caller's function (mdet_logdet_provider_device)
+  mdet_block_provider_device provider_dev = nullptr;
   void* user = nullptr;
 };
 
@@ -1427,9 +1429,10 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
   // pageable host memory goes through pinned chunks (see HostStager)
   HostStager stager_in(&fail, fd_in), stager_out(&fail, fd_out);
   const bool from_provider = source && source->provider;
-  const bool narrow = source && !from_provider && pl.widen;
+  const bool from_device = source && source->provider_dev;
+  const bool narrow = source && !from_provider && !from_device && pl.widen;
   const void* const in_base = narrow ? (const void*)source->narrow : (const void*)hA;
-  HostStager* stage_in = (!from_provider && (fd_in >= 0 || (n > 0 && HostStager::pageable(in_base)))) ? &stager_in : nullptr;
+  HostStager* stage_in = (!from_provider && !from_device && (fd_in >= 0 || (n > 0 && HostStager::pageable(in_base)))) ? &stager_in : nullptr;
   HostStager* stage_out = (fd_out >= 0 || (n > 0 && hOut && HostStager::pageable(hOut))) ? &stager_out : nullptr;
   // two pinned buffers of one block each for the provider's blocks, used in turn
   PinnedBuf prov_buf[2];
@@ -1474,6 +1477,15 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
     if (r1 <= r0) return;
     const int64_t w = pl.col_width(j), ldd = pl.col_ld(j);
     T* dcol = cols[j].base;
+    if (from_device) {
+      // the caller's function puts each block where it belongs, with work queued on the upload stream
+      for (int64_t i = r0 / bs; i * bs < r1 && prov_rc == MDET_OK; ++i) {
+        const int64_t b0 = i * bs, b1 = std::min<int64_t>(n, b0 + bs);
+        if (source->provider_dev(source->user, i, j, b1 - b0, w, dcol + (b0 - j * bs) * ldd, ldd, (void*)sh) != 0)
+          prov_rc = MDET_EPROVIDER;
+      }
+      return;
+    }
     if (from_provider) {
       // block by block through the caller's function, each into a pinned buffer and on from there
       for (int64_t i = r0 / bs; i * bs < r1 && prov_rc == MDET_OK; ++i) {
@@ -1815,14 +1827,17 @@ static int logdet_host_t(const mdet_params& p, const Plan& plan, T* hA, T* hOut,
 // (overwrite = 1 and the matrix stored in the arithmetic's type), else to the caller's
 // host_scratch, else to memory the library allocates (pinned if that much can be pinned).
 static int logdet_host_any(const mdet_params* p, void* hA, mdet_result* res, void* diag,
-                           mdet_block_provider provider = nullptr, void* user = nullptr) {
+                           mdet_block_provider provider = nullptr, void* user = nullptr,
+                           mdet_block_provider_device provider_dev = nullptr) {
   Plan pl;
   int rc = make_plan(*p, false, 0, pl);
   init_result(res, pl);
   if (rc != MDET_OK) return rc;
   PinnedBuf scratch;
   std::unique_ptr<char[]> plain_scratch;
-  const bool own_store = pl.widen || provider != nullptr;   // the factors cannot go where the matrix is
+  // blocks produced on the device arrive in the arithmetic's type, one triangle
+  if (provider_dev && (pl.widen || pl.general)) return MDET_EINVAL;
+  const bool own_store = pl.widen || provider != nullptr || provider_dev != nullptr;   // the factors cannot go where the matrix is
   void* hOut = own_store ? nullptr : hA;
   const uint64_t store_bytes = (pl.general ? 2 : 1) * pl.layout_bytes;
   if (pl.out_of_core && (!p->overwrite || own_store)) {
@@ -1842,8 +1857,9 @@ static int logdet_host_any(const mdet_params* p, void* hA, mdet_result* res, voi
   src.narrow = pl.widen ? (const char*)hA : nullptr;
   src.dtype = p->dtype;
   src.provider = provider;
+  src.provider_dev = provider_dev;
   src.user = user;
-  const HostSource* sp = (pl.widen || provider) ? &src : nullptr;
+  const HostSource* sp = (pl.widen || provider || provider_dev) ? &src : nullptr;
   auto t0 = std::chrono::steady_clock::now();
   if (p->dtype == MDET_F64 || pl.widen)
     rc = logdet_host_t<double>(*p, pl, own_store ? nullptr : (double*)hA, (double*)hOut, res, (double*)diag, -1, -1, sp);
@@ -2160,4 +2176,12 @@ extern "C" int mdet_logdet_provider(const mdet_params* p, mdet_block_provider pr
   // streams keeps its factored block columns in host memory (the caller's host_scratch or the
   // library's own).
   return logdet_host_any(p, nullptr, res, diag, provider, user);
+}
+
+// The same with blocks that the caller's function produces in device memory, with work it queues on
+// the stream it is handed: nothing of the matrix crosses the host link.
+extern "C" int mdet_logdet_provider_device(const mdet_params* p, mdet_block_provider_device provider,
+                                           void* user, mdet_result* res, void* diag) {
+  if (!params_ok(p) || !res || !provider) return MDET_EINVAL;
+  return logdet_host_any(p, nullptr, res, diag, nullptr, user, provider);
 }

@@ -314,3 +314,53 @@ def test_block_provider(M):
     assert res.out_of_core and rel(res.logabsdet, o.logabsdet) <= TOL["f64"]
     bad = M.mdet_logdet_provider(lambda *args: 7, n, "f64", bs, raise_on_error=False)
     assert bad.status == M.Status.EPROVIDER
+
+
+@pytest.mark.parametrize("n,bs,dtype", [(1000, 128, "f64"), (777, 64, "f64"), (1536, 256, "f32"), (200, 256, "f64")])
+def test_block_provider_on_the_device(M, n, bs, dtype):
+    # blocks produced in device memory by work queued on the stream the callback is handed (here: copies out
+    # of a dense device matrix): each block once, nothing of the matrix over the host link, the bits of the
+    # host-memory run, resident and streamed
+    w = W.scaled_down(W.config(4), n, bs)
+    tdt = torch.float64 if dtype == "f64" else torch.float32
+    a = torch.from_numpy(w.dense()).to(tdt)
+    ad = a.cuda()
+    h = M.pack_lower_block_columns(a, bs)
+    d0 = torch.empty(n, dtype=tdt)
+    ref = M.mdet_logdet_host(h.clone(), n, bs, diag=d0)
+    if dtype == "f64":      # (the jitter of this kernel matrix is below fp32's resolution: in fp32 only the bits are compared)
+        o = oracle.ldlt_logdet(a.numpy())
+        assert rel(ref.logabsdet, o.logabsdet) <= TOL[dtype]
+    esize = a.element_size()
+    calls, keep = [], []
+
+    def provider(bi, bj, rows, cols, dst, ld, stream):
+        calls.append((bi, bj))
+        block = ad[bi * bs:bi * bs + rows, bj * bs:bj * bs + cols]
+        padded = torch.zeros((rows, ld), dtype=tdt, device="cuda")       # the rows as they lie at dst
+        padded[:, :cols] = block
+        keep.append(padded)                                               # alive until the copy has run
+        torch.cuda.current_stream().synchronize()
+        return M.lib().mdet_step_copy(ctypes.c_void_p(dst), ctypes.c_void_p(padded.data_ptr()),
+                                      ctypes.c_uint64(rows * ld * esize), ctypes.c_void_p(stream))
+
+    T = (n + bs - 1) // bs
+    budgets = [0] if n <= bs else [0, min_budget(M, n, dtype, bs), min_budget(M, n, dtype, bs) * 2]
+    for budget in budgets:
+        calls.clear()
+        d1 = torch.empty(n, dtype=tdt)
+        res = M.mdet_logdet_provider_device(provider, n, dtype, bs, mem_budget=budget,
+                                            flags=M.FLAG_FORCE_OUT_OF_CORE if budget else 0, diag=d1)
+        keep.clear()
+        assert res.status == 0 and res.out_of_core == bool(budget)
+        assert sorted(calls) == [(i, j) for i in range(T) for j in range(i + 1)]
+        assert res.logabsdet == ref.logabsdet and res.sign == ref.sign and torch.equal(d1, d0)
+        if not budget:
+            assert res.bytes_h2d == 0                      # nothing of the matrix crossed the link
+    bad = M.mdet_logdet_provider_device(lambda *args: 3, n, dtype, bs, raise_on_error=False)
+    assert bad.status == M.Status.EPROVIDER
+    for fl in (M.FLAG_GENERAL, M.FLAG_COMPUTE_F64):
+        with pytest.raises(M.MemdetError) as e:
+            M.mdet_logdet_provider_device(lambda *args: 0, n, "f32", bs, flags=fl)
+        assert e.value.status == M.Status.EINVAL
+
