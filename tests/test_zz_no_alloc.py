@@ -89,3 +89,42 @@ def test_noalloc_entry_point_other_forms_and_error_reports(M):
     p = M.binding._params(400000, "f64", 4096, 0, True, 0, None)
     assert M.lib().mdet_logdet_device_noalloc(C.byref(p), C.c_void_p(out.data_ptr()), 400000,
                                               C.c_void_p(out.data_ptr()), None) == S.ENOMEM_DEVICE
+
+
+def test_noalloc_entry_point_recorded_into_a_graph_and_replayed(M):
+    # what the entry point is for: the whole path recorded once into a HIP graph (capture refuses
+    # allocations and waits) and replayed on new matrices in the same buffers, with eager work and
+    # synchronisation between the replays; every replay gives the bits of the allocating entry point
+    n, bs = 1024, 128
+    srcs = [torch.from_numpy(W.scaled_down(W.config(c), n, bs).dense()).cuda() for c in (1, 2, 4)]
+    refs, drefs = [], []
+    for src in srcs:
+        dref = torch.empty(n, dtype=torch.float64, device="cuda")
+        refs.append(M.mdet_logdet_device(src.clone(), block_size=bs, overwrite=True, diag=dref,
+                                         flags=M.FLAG_NO_LOOKAHEAD))
+        drefs.append(dref)
+    work = srcs[0].clone()
+    out = torch.zeros(5, dtype=torch.float64, device="cuda")
+    d = torch.empty(n, dtype=torch.float64, device="cuda")
+    # one call outside the capture: the scratch array's address is looked up on the first call
+    assert M.mdet_logdet_device_noalloc(work, out, block_size=bs, diag=d) == M.Status.OK
+    torch.cuda.synchronize()
+    work.copy_(srcs[0])
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    stream = torch.cuda.Stream()
+    with torch.cuda.graph(g, stream=stream):
+        st = M.mdet_logdet_device_noalloc(work, out, block_size=bs, diag=d, stream=stream)
+    assert st == M.Status.OK
+    for rep in range(2):
+        for src, ref, dref in zip(srcs, refs, drefs):
+            work.copy_(src)                    # eager work between the replays
+            out.fill_(-7.0)
+            d.zero_()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+            assert got[4] == M.Status.OK and got[0] == ref.logabsdet and int(got[1]) == ref.sign
+            assert torch.equal(d, dref)
+
