@@ -16,4 +16,4 @@ from .binding import (  # noqa: F401
     mdet_step_copy, mdet_step_mfma_peak, mdet_logdet_device_noalloc,
     pack_lower_block_columns, pack_general_block_columns,
 )
-from .api import memdet, parse_bytes  # noqa: E402,F401
+from .api import memdet, parse_bytes, FitLogdet  # noqa: E402,F401

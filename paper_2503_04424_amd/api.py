@@ -98,3 +98,45 @@ def memdet(M, max_mem=None, assume="gen", triangle=None, overwrite=False, mixed_
         import dataclasses
         return out + (dataclasses.asdict(r),)
     return out
+
+
+class FitLogdet:
+    """The regression of Alg. 2 behind the ``fit`` / ``eval`` pair of the software appendix:
+    ``fit(n, ell)`` takes consecutive integers ``n`` (the fit interval) and the log-determinants
+    ``ell`` of the leading principal blocks of those orders (every d-th cumulative sum of
+    ``log|diag|``, already sub-sampled by the caller as in the appendix); ``eval(n)`` returns the
+    extrapolated log-determinants ``n * Lhat_n``.  Both run in the library (``mdet_flodance_fit``,
+    ``mdet_flodance_eval``); this class only arranges the arrays."""
+
+    def __init__(self, q: int = 0):
+        self.q = int(q)
+        self.coef = None
+
+    def fit(self, n, ell):
+        import numpy as np
+        import torch
+        n = np.asarray(n)
+        ell = np.asarray(ell, dtype=np.float64)
+        ni = np.rint(n).astype(np.int64)
+        if n.ndim != 1 or n.shape != ell.shape or n.size < self.q + 3 or np.any(ni != n) or \
+                np.any(np.diff(ni) != 1) or ni[0] < 1:
+            raise ValueError("n must be consecutive integers >= 1, with one log-determinant each")
+        # the library reads ell[j - 1] for j = n0 .. ns (one sample per order: d = 1)
+        full = np.zeros(int(ni[-1]), dtype=np.float64)
+        full[ni - 1] = ell
+        self.coef = B.mdet_flodance_fit(torch.from_numpy(full).cuda(), 1, int(ni[0]), int(ni[-1]), self.q)
+        return self
+
+    def eval(self, n):
+        import numpy as np
+        import torch
+        if self.coef is None:
+            raise ValueError("fit first")
+        nv = torch.from_numpy(np.asarray(n, dtype=np.float64).reshape(-1).copy()).cuda()
+        lhat = B.mdet_flodance_eval(self.coef, self.q, nv)
+        return (lhat * nv).cpu().numpy().reshape(np.shape(n))
+
+    @property
+    def parameters(self):
+        """c_0, nu_0 .. nu_q, L_{n0}, residual norm, as the library returns them."""
+        return None if self.coef is None else self.coef.cpu().numpy()

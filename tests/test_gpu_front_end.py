@@ -95,3 +95,32 @@ def test_pivoted_and_general_forms(M):
         M.memdet(a, assume="gen", pivot="leaf")
     with pytest.raises(ValueError):
         M.memdet(a, assume="lower")
+
+
+@pytest.mark.gpu
+def test_fit_and_extrapolate_in_the_shape_of_the_appendix(M):
+    # the ratio law exact (Assumption 1 of Sec. 3.2): ell_n - ell_{n-1} = log C - nu log n; fitted on
+    # n = 1 .. 2000 (Eq. 7 is written relative to L_{n0}; it reproduces the law exactly for n0 = 1), the
+    # curve gives ell at n = 20000; and the pivots of a factorisation feed it
+    import math
+    ell_1, Cc, nu = -0.8, 5.0, 1.7
+    k = np.arange(2, 20001, dtype=np.float64)
+    ell = np.concatenate([[ell_1], ell_1 + np.cumsum(np.log(Cc) - nu * np.log(k))])     # ell[n - 1]
+    n = np.arange(1, 20001)
+    mask = (n >= 1) & (n <= 2000)
+    f = M.FitLogdet(q=0).fit(n[mask], ell[mask])
+    got = f.eval(np.array([5000.0, 20000.0]))
+    assert np.max(np.abs(got - ell[[4999, 19999]]) / np.abs(ell[[4999, 19999]])) <= 1e-9
+    assert abs(f.parameters[1] - nu) <= 1e-9
+    with pytest.raises(ValueError):
+        M.FitLogdet(q=1).fit(np.array([1, 2, 4, 5, 6]), np.zeros(5))
+    a = spd_matrix(5, 1200)
+    ld, sign, diag, perm = M.memdet(torch.from_numpy(a).cuda(), assume="sym", block_size=128)
+    cum = np.cumsum(np.log(np.abs(diag)))[3::4]                 # every 4th: orders 1 .. 300 of 4 x 4 blocks
+    nn = np.arange(1, cum.size + 1)
+    fit = M.FitLogdet(q=1).fit(nn[20:200], cum[20:200])
+    from oracle import flodance_oracle as F
+    want = F.fit(np.cumsum(np.log(np.abs(diag))), 4, 21, 200, 1)         # the same samples: d = 4, n = 21 .. 200
+    ref = want.eval(np.array([300.0]))[0] * 300.0
+    assert abs(fit.eval(np.array([300.0]))[0] - ref) <= 1e-7 * abs(ref)
+
