@@ -22,6 +22,22 @@ def test_sizes_are_read_as_written():
         parse_bytes("12 parsecs")
 
 
+def test_arguments_are_checked_before_anything_runs():
+    from paper_2503_04424_amd.api import memdet, FitLogdet
+    with pytest.raises(ValueError):
+        memdet(np.zeros((3, 4)))
+    with pytest.raises(ValueError):
+        memdet(np.eye(4), assume="lower")
+    with pytest.raises(ValueError):
+        memdet(np.eye(4), assume="sym", triangle="x")
+    with pytest.raises(ValueError):
+        memdet(np.eye(4), assume="gen", pivot="leaf")
+    with pytest.raises(ValueError):
+        memdet(np.eye(4), assume="sym", mixed_precision="float16")
+    with pytest.raises(ValueError):
+        FitLogdet(q=2).eval([10.0])
+
+
 @pytest.fixture(scope="module")
 def M():
     if not torch.cuda.is_available():
